@@ -1,0 +1,127 @@
+/*
+ * mi355conv — fp32 NHWC 2-D convolution for small feature maps on AMD MI355X (gfx950).
+ *
+ * C ABI of the three operators that the paper's fp32 GPU library contributes and
+ * that its Sec. IV credits for the training speed on 32x32 images: forward
+ * convolution, deconvolution (= backward-data) and backward-weight
+ * (Sec. III "Layer-1 Native libs"; Sec. IV, paragraph on the small-feature-map
+ * conv\deconv operators; Table I: float32, tensors in [N,H,W,C] order; Fig. 2:
+ * argument set in_channel, out_channel, kernel, stride, padding).
+ *
+ * Conventions shared by every entry point
+ *   - Tensors are dense fp32, last index fastest, DEVICE pointers, 16-byte aligned:
+ *       X, dX : [N, IH, IW, IC]        W, dW : [OC, FH, FW, IC]
+ *       Y, dY : [N, OH, OW, OC]        OH = floor((IH + 2*ph - FH)/sh) + 1 (same in w)
+ *   - Cross-correlation (no filter flip), zero padding, dilation 1, groups 1, no bias.
+ *   - Outputs are overwritten (beta = 0) and every element is written, including the
+ *     zeros of dX that no filter tap reaches.  Inputs are never modified.  Input and
+ *     output must not alias.
+ *   - The caller owns all memory, including the workspace.  The library allocates no
+ *     device memory and keeps no pointer after returning.
+ *   - Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and return; completion is the caller's stream synchronisation
+ *     (the paper's async mode, Sec. III Layer-4).  Calls on different streams are safe
+ *     if their outputs and workspaces do not overlap.
+ *   - Every tensor must hold fewer than 2^31 elements.
+ *   - All argument checks happen before the first HIP call, so they can be exercised
+ *     on a machine without a GPU.
+ *   - Return value: MI355CONV_OK (0) or a negative mi355conv_status.
+ */
+#ifndef MI355CONV_H
+#define MI355CONV_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum mi355conv_status {
+    MI355CONV_OK = 0,
+    MI355CONV_ERR_NULL_PTR = -1,    /* a required pointer is NULL                          */
+    MI355CONV_ERR_BAD_DIM = -2,     /* dim <= 0, stride <= 0, pad < 0, OH/OW <= 0, >= 2^31 */
+    MI355CONV_ERR_WORKSPACE = -3,   /* ws_bytes below conv2d_workspace_bytes(), or ws NULL */
+    MI355CONV_ERR_ALIGNMENT = -4,   /* a tensor or the workspace is not 16-byte aligned    */
+    MI355CONV_ERR_UNSUPPORTED = -5, /* bad op code / tuning value                          */
+    MI355CONV_ERR_HIP = -6          /* a HIP runtime call or kernel launch failed          */
+} mi355conv_status;
+
+/* Operator codes for conv2d_workspace_bytes / conv2d_query_plan. */
+enum { MI355CONV_OP_FWD = 0, MI355CONV_OP_BWD_DATA = 1, MI355CONV_OP_BWD_WEIGHT = 2 };
+
+/* Problem shape.  Square configurations set sh == sw and ph == pw. */
+typedef struct conv2d_desc {
+    int N, IH, IW, IC;   /* input batch, height, width, channels */
+    int OC, FH, FW;      /* output channels, filter height, width */
+    int sh, sw;          /* stride (>= 1) */
+    int ph, pw;          /* symmetric zero padding (>= 0) */
+} conv2d_desc;
+
+/* Kernel variants (conv2d_plan_info.variant, conv2d_set_tuning). */
+enum {
+    MI355CONV_VARIANT_AUTO = -1,
+    MI355CONV_VARIANT_DIRECT = 0,  /* one thread per output element; any shape             */
+    MI355CONV_VARIANT_MFMA = 1     /* implicit GEMM on v_mfma_f32_32x32x2_f32, LDS-staged  */
+};
+
+/* What the host-side selection picked for a problem (the paper's "operators selected by a
+ * feature-map-size threshold", Sec. IV; Sec. III Layer-2 holds that logic). */
+typedef struct conv2d_plan_info {
+    int variant;        /* MI355CONV_VARIANT_*                                              */
+    int tile_m, tile_n; /* workgroup output tile (GEMM rows x cols); 0 for DIRECT           */
+    int split;          /* number of reduction slices (1 = no split)                        */
+    int pos_major;      /* 1: GEMM rows ordered (oh,ow,n) so tiles skip padded taps         */
+    int grid;           /* workgroups of the main kernel                                    */
+    size_t workspace_bytes;
+} conv2d_plan_info;
+
+/* Bytes of device workspace the given operator needs for this shape under the current
+ * tuning (0 is possible).  Returns 0 on invalid arguments too; the entry points report
+ * the error. */
+size_t conv2d_workspace_bytes(int op, const conv2d_desc *d);
+
+/* Fill *info with the plan the entry point would run.  Host only; no HIP call. */
+int conv2d_query_plan(int op, const conv2d_desc *d, conv2d_plan_info *info);
+
+/* Process-wide override for tests and sweeps: variant = MI355CONV_VARIANT_AUTO or a
+ * variant code, split = 0 (auto) or a forced slice count >= 1 (clamped to what the shape
+ * allows).  Not thread-safe against concurrent operator calls. */
+int conv2d_set_tuning(int variant, int split);
+
+/* Forward convolution (Sec. III Layer-1; Fig. 2 conv3D arguments):
+ *   Y[n,oh,ow,oc] = sum_{fh,fw,ic} X[n, oh*sh-ph+fh, ow*sw-pw+fw, ic] * W[oc,fh,fw,ic],
+ * X taken as 0 outside the image.  X, W: device, read-only.  Y: device, overwritten.
+ * ws: device scratch of at least conv2d_workspace_bytes(OP_FWD, d) bytes (may be NULL
+ * when that is 0). */
+int conv2d_fwd(const float *X, const float *W, float *Y, const conv2d_desc *d,
+               void *ws, size_t ws_bytes, void *stream);
+
+/* Backward-data = deconvolution (Sec. IV: the deconv operator for small feature maps):
+ *   dX[n,ih,iw,ic] = sum over (oc,fh,fw) with oh*sh-ph+fh == ih, ow*sw-pw+fw == iw of
+ *                    dY[n,oh,ow,oc] * W[oc,fh,fw,ic].
+ * d->IH, d->IW give the size of dX (the transposed convolution's output size is not
+ * unique when (IH+2ph-FH) % sh != 0); elements no tap reaches are written as 0.
+ * deconv2d is the same function under the paper's name for it. */
+int conv2d_bwd_data(const float *dY, const float *W, float *dX, const conv2d_desc *d,
+                    void *ws, size_t ws_bytes, void *stream);
+int deconv2d(const float *dY, const float *W, float *dX, const conv2d_desc *d,
+             void *ws, size_t ws_bytes, void *stream);
+
+/* Backward-weight (implied by the paper's training loop, Fig. 2 backward + update):
+ *   dW[oc,fh,fw,ic] = sum_{n,oh,ow} dY[n,oh,ow,oc] * X[n, oh*sh-ph+fh, ow*sw-pw+fw, ic]
+ * over in-range taps.  The sum over N*OH*OW is always cut into slices whose partial
+ * results go through the workspace and are combined in a fixed order, so results are
+ * bitwise reproducible. */
+int conv2d_bwd_weight(const float *X, const float *dY, float *dW, const conv2d_desc *d,
+                      void *ws, size_t ws_bytes, void *stream);
+
+/* Static text for a status code. */
+const char *conv2d_status_string(int status);
+
+/* Text of the last HIP error seen by this thread inside the library ("" if none). */
+const char *conv2d_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MI355CONV_H */

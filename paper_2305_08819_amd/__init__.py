@@ -1,0 +1,174 @@
+"""MI355X-native fp32 NHWC convolution (forward, deconvolution/backward-data, backward-weight).
+
+Thin ctypes binding over ``libmi355conv.so`` (C ABI in ``include/mi355conv.h``).  The binding
+only marshals arguments: shapes into a ``conv2d_desc``, torch CUDA tensors into raw device
+pointers, the current torch stream into a ``hipStream_t``.  All arithmetic runs in the HIP
+kernels; there is no fallback, and importing the library fails loudly if it was not built.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libmi355conv.so")
+
+OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT = 0, 1, 2
+VARIANT_AUTO, VARIANT_DIRECT, VARIANT_MFMA = -1, 0, 1
+
+EXPORTS = ("conv2d_workspace_bytes", "conv2d_query_plan", "conv2d_set_tuning", "conv2d_fwd",
+           "conv2d_bwd_data", "deconv2d", "conv2d_bwd_weight", "conv2d_status_string",
+           "conv2d_last_hip_error")
+
+
+class ConvDesc(ctypes.Structure):
+    """Mirror of ``conv2d_desc``."""
+    _fields_ = [(n, ctypes.c_int) for n in
+                ("N", "IH", "IW", "IC", "OC", "FH", "FW", "sh", "sw", "ph", "pw")]
+
+    @property
+    def OH(self):
+        return (self.IH + 2 * self.ph - self.FH) // self.sh + 1
+
+    @property
+    def OW(self):
+        return (self.IW + 2 * self.pw - self.FW) // self.sw + 1
+
+
+class PlanInfo(ctypes.Structure):
+    """Mirror of ``conv2d_plan_info``."""
+    _fields_ = [("variant", ctypes.c_int), ("tile_m", ctypes.c_int), ("tile_n", ctypes.c_int),
+                ("split", ctypes.c_int), ("pos_major", ctypes.c_int), ("grid", ctypes.c_int),
+                ("workspace_bytes", ctypes.c_size_t)]
+
+
+class Mi355ConvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        lib = load()
+        msg = lib.conv2d_status_string(status).decode()
+        hip = lib.conv2d_last_hip_error().decode()
+        super().__init__("%s: %s (%d)%s" % (where, msg, status, " [" + hip + "]" if hip else ""))
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load the built library; raise if it is missing (no silent fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("%s not built: run `python -m paper_2305_08819_amd.build`" % LIB_PATH)
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, dp = ctypes.c_void_p, ctypes.POINTER(ConvDesc)
+        lib.conv2d_workspace_bytes.argtypes = [ctypes.c_int, dp]
+        lib.conv2d_workspace_bytes.restype = ctypes.c_size_t
+        lib.conv2d_query_plan.argtypes = [ctypes.c_int, dp, ctypes.POINTER(PlanInfo)]
+        lib.conv2d_query_plan.restype = ctypes.c_int
+        lib.conv2d_set_tuning.argtypes = [ctypes.c_int, ctypes.c_int]
+        lib.conv2d_set_tuning.restype = ctypes.c_int
+        for name in ("conv2d_fwd", "conv2d_bwd_data", "deconv2d", "conv2d_bwd_weight"):
+            fn = getattr(lib, name)
+            fn.argtypes = [vp, vp, vp, dp, vp, ctypes.c_size_t, vp]
+            fn.restype = ctypes.c_int
+        lib.conv2d_status_string.argtypes = [ctypes.c_int]
+        lib.conv2d_status_string.restype = ctypes.c_char_p
+        lib.conv2d_last_hip_error.argtypes = []
+        lib.conv2d_last_hip_error.restype = ctypes.c_char_p
+        _lib = lib
+    return _lib
+
+
+def _pair(v):
+    if isinstance(v, (tuple, list)):
+        return int(v[0]), int(v[1])
+    return int(v), int(v)
+
+
+def make_desc(N, IH, IW, IC, OC, FH, FW, stride=1, pad=0) -> ConvDesc:
+    sh, sw = _pair(stride)
+    ph, pw = _pair(pad)
+    return ConvDesc(N, IH, IW, IC, OC, FH, FW, sh, sw, ph, pw)
+
+
+def conv2d_workspace_bytes(op: int, desc: ConvDesc) -> int:
+    return int(load().conv2d_workspace_bytes(op, ctypes.byref(desc)))
+
+
+def conv2d_query_plan(op: int, desc: ConvDesc) -> PlanInfo:
+    info = PlanInfo()
+    rc = load().conv2d_query_plan(op, ctypes.byref(desc), ctypes.byref(info))
+    if rc != 0:
+        raise Mi355ConvError(rc, "conv2d_query_plan")
+    return info
+
+
+def conv2d_set_tuning(variant: int = VARIANT_AUTO, split: int = 0) -> None:
+    rc = load().conv2d_set_tuning(variant, split)
+    if rc != 0:
+        raise Mi355ConvError(rc, "conv2d_set_tuning")
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _stream_handle(stream):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check(t, shape, name):
+    import torch
+    if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+        raise ValueError("%s must be a contiguous fp32 CUDA tensor" % name)
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError("%s has shape %s, expected %s" % (name, tuple(t.shape), tuple(shape)))
+
+
+def _call(name, op, a, b, out, desc, ws, stream):
+    lib = load()
+    need = conv2d_workspace_bytes(op, desc)
+    if ws is None and need:
+        import torch
+        ws = torch.empty(need, dtype=torch.uint8, device=out.device)
+    nbytes = ws.numel() * ws.element_size() if ws is not None else 0
+    rc = getattr(lib, name)(_ptr(a), _ptr(b), _ptr(out), ctypes.byref(desc), _ptr(ws), nbytes,
+                            _stream_handle(stream))
+    if rc != 0:
+        raise Mi355ConvError(rc, name)
+    return out
+
+
+def conv2d_fwd(X, W, Y, desc: ConvDesc, ws=None, stream=None):
+    """Y[N,OH,OW,OC] <- conv(X[N,IH,IW,IC], W[OC,FH,FW,IC]); enqueue only."""
+    _check(X, (desc.N, desc.IH, desc.IW, desc.IC), "X")
+    _check(W, (desc.OC, desc.FH, desc.FW, desc.IC), "W")
+    _check(Y, (desc.N, desc.OH, desc.OW, desc.OC), "Y")
+    return _call("conv2d_fwd", OP_FWD, X, W, Y, desc, ws, stream)
+
+
+def conv2d_bwd_data(dY, W, dX, desc: ConvDesc, ws=None, stream=None):
+    """dX[N,IH,IW,IC] <- deconv(dY[N,OH,OW,OC], W[OC,FH,FW,IC]); enqueue only."""
+    _check(dY, (desc.N, desc.OH, desc.OW, desc.OC), "dY")
+    _check(W, (desc.OC, desc.FH, desc.FW, desc.IC), "W")
+    _check(dX, (desc.N, desc.IH, desc.IW, desc.IC), "dX")
+    return _call("conv2d_bwd_data", OP_BWD_DATA, dY, W, dX, desc, ws, stream)
+
+
+def deconv2d(dY, W, dX, desc: ConvDesc, ws=None, stream=None):
+    """Same as conv2d_bwd_data, through the library's ``deconv2d`` symbol."""
+    _check(dY, (desc.N, desc.OH, desc.OW, desc.OC), "dY")
+    _check(W, (desc.OC, desc.FH, desc.FW, desc.IC), "W")
+    _check(dX, (desc.N, desc.IH, desc.IW, desc.IC), "dX")
+    return _call("deconv2d", OP_BWD_DATA, dY, W, dX, desc, ws, stream)
+
+
+def conv2d_bwd_weight(X, dY, dW, desc: ConvDesc, ws=None, stream=None):
+    """dW[OC,FH,FW,IC] <- sum over pixels of dY x X; enqueue only."""
+    _check(X, (desc.N, desc.IH, desc.IW, desc.IC), "X")
+    _check(dY, (desc.N, desc.OH, desc.OW, desc.OC), "dY")
+    _check(dW, (desc.OC, desc.FH, desc.FW, desc.IC), "dW")
+    return _call("conv2d_bwd_weight", OP_BWD_WEIGHT, X, dY, dW, desc, ws, stream)

@@ -1,0 +1,431 @@
+// Host side of libmi355conv: argument checks, variant/tile/split selection, launches.
+// The selection logic is the analogue of the paper's Layer-2 (Sec. III) "logics and
+// strategies" above the native kernels, including the size threshold below which the
+// small-feature-map operators are chosen (Sec. IV).
+#include "../../include/mi355conv.h"
+#include "conv_internal.h"
+
+#include <atomic>
+#include <cstdio>
+#include <cstring>
+
+using namespace mi355conv;
+
+namespace {
+
+std::atomic<int> g_forceVariant{MI355CONV_VARIANT_AUTO};
+std::atomic<int> g_forceSplit{0};
+thread_local char t_hipError[256] = "";
+
+constexpr long long kMaxElems = (1LL << 31) - 1;
+constexpr int kTargetWorkgroups = 512;   // 256 CUs x 2 resident workgroups
+constexpr int kSmallMapPixels = 64;      // maps of at most 8x8 outputs use position-major rows
+constexpr int kMaxSplit = 256;
+
+struct Plan {
+    int variant = MI355CONV_VARIANT_DIRECT;
+    int bm = 0, bn = 0;
+    int split = 1;
+    int posMajor = 0;
+    int grid = 0;
+    int tilesM = 0, tilesN = 0;
+    int flushChunks = 16;
+    long long outElems = 0;
+    long long sliceStride = 0;
+    size_t wsBytes = 0;
+    // backward-data phase table
+    int nPhases = 1;
+    int phaseTileStart[kMaxPhases + 1] = {};
+    short phaseRa[kMaxPhases] = {}, phaseRb[kMaxPhases] = {}, phaseY0[kMaxPhases] = {}, phaseX0[kMaxPhases] = {};
+    int phaseDH[kMaxPhases] = {}, phaseDW[kMaxPhases] = {};
+};
+
+int out_extent(int in, int pad, int f, int stride)
+{
+    long long span = (long long)in + 2LL * pad - f;
+    if (span < 0) return 0;
+    return (int)(span / stride) + 1;
+}
+
+int check_desc(const conv2d_desc *d, Shape *s)
+{
+    if (!d) return MI355CONV_ERR_NULL_PTR;
+    if (d->N <= 0 || d->IH <= 0 || d->IW <= 0 || d->IC <= 0 || d->OC <= 0 || d->FH <= 0 || d->FW <= 0 ||
+        d->sh <= 0 || d->sw <= 0 || d->ph < 0 || d->pw < 0)
+        return MI355CONV_ERR_BAD_DIM;
+    if (d->ph > (1 << 20) || d->pw > (1 << 20)) return MI355CONV_ERR_BAD_DIM;
+    const int OH = out_extent(d->IH, d->ph, d->FH, d->sh), OW = out_extent(d->IW, d->pw, d->FW, d->sw);
+    if (OH <= 0 || OW <= 0) return MI355CONV_ERR_BAD_DIM;
+    const long long xe = (long long)d->N * d->IH * d->IW;
+    const long long ye = (long long)d->N * OH * OW;
+    const long long we = (long long)d->OC * d->FH * d->FW;
+    if (xe > kMaxElems / d->IC || ye > kMaxElems / d->OC || we > kMaxElems / d->IC) return MI355CONV_ERR_BAD_DIM;
+    *s = Shape{d->N, d->IH, d->IW, d->IC, d->OC, d->FH, d->FW, d->sh, d->sw, d->ph, d->pw, OH, OW};
+    return MI355CONV_OK;
+}
+
+inline long long pad4(long long v) { return (v + 3) & ~3LL; }
+inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+// Source-index headroom of the 32-bit offsets used by the gather-GEMM kernel.
+bool offsets_fit_32bit(long long srcElems, const Shape &s, int srcW, int srcC)
+{
+    const long long halo = ((long long)(s.FH + s.ph + 1) * srcW + s.FW + s.pw + 1) * srcC;
+    return srcElems + halo < kMaxElems && halo < (1 << 27);
+}
+
+int pick_split(int tiles, int maxSlices)
+{
+    int split = 1;
+    const int forced = g_forceSplit.load();
+    if (forced > 0) split = forced;
+    else if (tiles < kTargetWorkgroups * 3 / 4) split = ceil_div(kTargetWorkgroups, tiles);
+    if (split > maxSlices) split = maxSlices;
+    if (split > kMaxSplit) split = kMaxSplit;
+    if (split < 1) split = 1;
+    return split;
+}
+
+void finish_split(Plan &pl, int maxSlices)
+{
+    pl.split = pick_split(pl.tilesM * pl.tilesN, maxSlices);
+    pl.grid = pl.tilesM * pl.tilesN * pl.split;
+    pl.sliceStride = pad4(pl.outElems);
+    pl.wsBytes = pl.split > 1 ? (size_t)pl.split * (size_t)pl.sliceStride * sizeof(float) : 0;
+}
+
+int pick_bn(int cols)
+{
+    if (cols <= 32) return 32;
+    if (cols <= 64) return 64;
+    return 128;
+}
+
+Plan plan_fwd(const Shape &s)
+{
+    Plan pl;
+    pl.outElems = (long long)s.N * s.OH * s.OW * s.OC;
+    const int forced = g_forceVariant.load();
+    const bool eligible = s.IC % kBK == 0 && s.FH * s.FW <= kMaxTaps &&
+                          offsets_fit_32bit((long long)s.N * s.IH * s.IW * s.IC, s, s.IW, s.IC);
+    if (forced == MI355CONV_VARIANT_DIRECT || !eligible) return pl;
+    pl.variant = MI355CONV_VARIANT_MFMA;
+    pl.bn = pick_bn(s.OC);
+    pl.bm = 128;
+    const long long M = (long long)s.N * s.OH * s.OW;
+    pl.tilesN = ceil_div(s.OC, pl.bn);
+    if (pl.bn == 128 && (long long)ceil_div(M, 128) * pl.tilesN < kTargetWorkgroups) {
+        pl.bn = 64;   // more, smaller tiles before resorting to reduction slices
+        pl.tilesN = ceil_div(s.OC, pl.bn);
+    }
+    pl.posMajor = (s.ph > 0 || s.pw > 0) && s.OH * s.OW <= kSmallMapPixels && s.N % pl.bm == 0;
+    pl.tilesM = ceil_div(M, pl.bm);
+    pl.nPhases = 1;
+    pl.phaseTileStart[0] = 0;
+    pl.phaseTileStart[1] = pl.tilesM;
+    pl.phaseDH[0] = s.OH;
+    pl.phaseDW[0] = s.OW;
+    // a slice should keep at least 4 stages of the shortest tile (>= 1 tap)
+    const int minIters = (s.IC / kBK) * (pl.posMajor ? 4 : s.FH * s.FW);
+    finish_split(pl, minIters >= 8 ? minIters / 4 : 1);
+    return pl;
+}
+
+Plan plan_bwd_data(const Shape &s)
+{
+    Plan pl;
+    pl.outElems = (long long)s.N * s.IH * s.IW * s.IC;
+    const int forced = g_forceVariant.load();
+    const bool eligible = s.OC % kBK == 0 && s.IC % 4 == 0 && s.FH * s.FW <= kMaxTaps &&
+                          s.sh * s.sw <= kMaxPhases &&
+                          offsets_fit_32bit((long long)s.N * s.OH * s.OW * s.OC, s, s.OW, s.OC) &&
+                          pl.outElems < kMaxElems;
+    if (forced == MI355CONV_VARIANT_DIRECT || !eligible) return pl;
+    pl.variant = MI355CONV_VARIANT_MFMA;
+    pl.bn = pick_bn(s.IC);
+    pl.bm = 128;
+    pl.tilesN = ceil_div(s.IC, pl.bn);
+    const long long Mall = (long long)s.N * s.IH * s.IW;
+    if (pl.bn == 128 && (long long)ceil_div(Mall, 128) * pl.tilesN < kTargetWorkgroups) {
+        pl.bn = 64;
+        pl.tilesN = ceil_div(s.IC, pl.bn);
+    }
+    pl.posMajor = s.sh == 1 && s.sw == 1 && (s.FH > 1 || s.FW > 1) && s.IH * s.IW <= kSmallMapPixels &&
+                  s.N % pl.bm == 0;
+    // phases ordered by decreasing tap count so the long tiles are dispatched first
+    struct Ph { int ra, rb, taps; };
+    Ph ph[kMaxPhases];
+    int np = 0;
+    for (int ra = 0; ra < s.sh; ++ra)
+        for (int rb = 0; rb < s.sw; ++rb) {
+            int th = 0, tw = 0;
+            for (int fh = 0; fh < s.FH; ++fh) th += (fh % s.sh) == ra;
+            for (int fw = 0; fw < s.FW; ++fw) tw += (fw % s.sw) == rb;
+            ph[np++] = Ph{ra, rb, th * tw};
+        }
+    for (int i = 1; i < np; ++i)   // insertion sort, stable
+        for (int j = i; j > 0 && ph[j].taps > ph[j - 1].taps; --j) {
+            Ph t = ph[j]; ph[j] = ph[j - 1]; ph[j - 1] = t;
+        }
+    int tiles = 0, k = 0;
+    int minTaps = 1 << 30;
+    for (int i = 0; i < np; ++i) {
+        // destination rows ih with (ih + ph) % sh == ra:  ih = y0, y0 + sh, ...
+        const int y0 = ((ph[i].ra - s.ph) % s.sh + s.sh) % s.sh;
+        const int x0 = ((ph[i].rb - s.pw) % s.sw + s.sw) % s.sw;
+        const int dh = y0 < s.IH ? (s.IH - 1 - y0) / s.sh + 1 : 0;
+        const int dw = x0 < s.IW ? (s.IW - 1 - x0) / s.sw + 1 : 0;
+        if (dh == 0 || dw == 0) continue;
+        pl.phaseRa[k] = (short)ph[i].ra;
+        pl.phaseRb[k] = (short)ph[i].rb;
+        pl.phaseY0[k] = (short)y0;
+        pl.phaseX0[k] = (short)x0;
+        pl.phaseDH[k] = dh;
+        pl.phaseDW[k] = dw;
+        pl.phaseTileStart[k] = tiles;
+        tiles += ceil_div((long long)s.N * dh * dw, pl.bm);
+        if (ph[i].taps > 0 && ph[i].taps < minTaps) minTaps = ph[i].taps;
+        ++k;
+    }
+    pl.phaseTileStart[k] = tiles;
+    pl.nPhases = k;
+    pl.tilesM = tiles;
+    if (minTaps == (1 << 30)) minTaps = 1;
+    const int minIters = (s.OC / kBK) * (pl.posMajor ? (minTaps < 4 ? minTaps : 4) : minTaps);
+    finish_split(pl, minIters >= 8 ? minIters / 4 : 1);
+    return pl;
+}
+
+Plan plan_bwd_weight(const Shape &s)
+{
+    Plan pl;
+    pl.outElems = (long long)s.OC * s.FH * s.FW * s.IC;
+    const int forced = g_forceVariant.load();
+    const long long M = (long long)s.N * s.OH * s.OW;
+    const bool eligible = s.IC % 4 == 0 && s.OC % 4 == 0 && M < kMaxElems - kBK &&
+                          (long long)s.N * s.IH * s.IW < kMaxElems;
+    if (forced == MI355CONV_VARIANT_DIRECT || !eligible) return pl;
+    pl.variant = MI355CONV_VARIANT_MFMA;
+    const long long Ktot = (long long)s.FH * s.FW * s.IC;
+    pl.bm = s.OC <= 64 ? 64 : 128;
+    pl.bn = Ktot <= 64 ? 64 : 128;
+    pl.tilesM = ceil_div(s.OC, pl.bm);
+    pl.tilesN = ceil_div(Ktot, pl.bn);
+    pl.posMajor = (s.ph > 0 || s.pw > 0) && s.OH * s.OW <= kSmallMapPixels && s.N % kBK == 0;
+    const int chunks = ceil_div(M, kBK);
+    pl.flushChunks = 16;   // 512-product chains
+    finish_split(pl, chunks >= 8 ? chunks / 4 : 1);
+    return pl;
+}
+
+int make_plan(int op, const Shape &s, Plan *pl)
+{
+    switch (op) {
+    case MI355CONV_OP_FWD: *pl = plan_fwd(s); return MI355CONV_OK;
+    case MI355CONV_OP_BWD_DATA: *pl = plan_bwd_data(s); return MI355CONV_OK;
+    case MI355CONV_OP_BWD_WEIGHT: *pl = plan_bwd_weight(s); return MI355CONV_OK;
+    default: return MI355CONV_ERR_UNSUPPORTED;
+    }
+}
+
+int hip_fail(hipError_t e)
+{
+    snprintf(t_hipError, sizeof t_hipError, "%s", hipGetErrorString(e));
+    return MI355CONV_ERR_HIP;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_buffers(const void *a, const void *b, const void *c, const Plan &pl, const void *ws, size_t wsBytes)
+{
+    if (!a || !b || !c) return MI355CONV_ERR_NULL_PTR;
+    if (!aligned16(a) || !aligned16(b) || !aligned16(c)) return MI355CONV_ERR_ALIGNMENT;
+    if (pl.wsBytes > 0) {
+        if (!ws || wsBytes < pl.wsBytes) return MI355CONV_ERR_WORKSPACE;
+        if (!aligned16(ws)) return MI355CONV_ERR_ALIGNMENT;
+    }
+    return MI355CONV_OK;
+}
+
+void fill_gather_params(GatherGemmParams &g, const Plan &pl)
+{
+    g.posMajor = pl.posMajor;
+    g.split = pl.split;
+    g.sliceStride = pl.sliceStride;
+    g.tilesN = pl.tilesN;
+    g.nPhases = pl.nPhases;
+    for (int i = 0; i <= kMaxPhases; ++i) g.phaseTileStart[i] = pl.phaseTileStart[i];
+    for (int i = 0; i < kMaxPhases; ++i) {
+        g.phaseRa[i] = pl.phaseRa[i];
+        g.phaseRb[i] = pl.phaseRb[i];
+        g.phaseY0[i] = pl.phaseY0[i];
+        g.phaseX0[i] = pl.phaseX0[i];
+        g.phaseDH[i] = pl.phaseDH[i];
+        g.phaseDW[i] = pl.phaseDW[i];
+    }
+}
+
+int run_gather(const float *A, const float *B, float *out, const Shape &s, const Plan &pl, bool bwd,
+               void *ws, hipStream_t st)
+{
+    GatherGemmParams g;
+    memset(&g, 0, sizeof g);
+    g.A = A;
+    g.B = B;
+    g.C = pl.split > 1 ? static_cast<float *>(ws) : out;
+    g.Nimg = s.N;
+    if (bwd) {
+        g.SH = s.OH; g.SW = s.OW; g.SC = s.OC;
+        g.DH = s.IH; g.DW = s.IW; g.DC = s.IC;
+    } else {
+        g.SH = s.IH; g.SW = s.IW; g.SC = s.IC;
+        g.DH = s.OH; g.DW = s.OW; g.DC = s.OC;
+    }
+    g.FH = s.FH; g.FW = s.FW;
+    g.sh = s.sh; g.sw = s.sw; g.ph = s.ph; g.pw = s.pw;
+    fill_gather_params(g, pl);
+    hipError_t e = launch_gather_gemm(g, bwd, pl.bm, pl.bn, pl.grid, st);
+    if (e != hipSuccess) return hip_fail(e);
+    if (pl.split > 1) {
+        e = launch_slice_reduce(static_cast<const float *>(ws), out, pl.outElems, pl.split, pl.sliceStride, st);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return MI355CONV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t conv2d_workspace_bytes(int op, const conv2d_desc *d)
+{
+    Shape s;
+    Plan pl;
+    if (check_desc(d, &s) != MI355CONV_OK || make_plan(op, s, &pl) != MI355CONV_OK) return 0;
+    return pl.wsBytes;
+}
+
+int conv2d_query_plan(int op, const conv2d_desc *d, conv2d_plan_info *info)
+{
+    if (!info) return MI355CONV_ERR_NULL_PTR;
+    Shape s;
+    Plan pl;
+    int rc = check_desc(d, &s);
+    if (rc != MI355CONV_OK) return rc;
+    rc = make_plan(op, s, &pl);
+    if (rc != MI355CONV_OK) return rc;
+    info->variant = pl.variant;
+    info->tile_m = pl.bm;
+    info->tile_n = pl.bn;
+    info->split = pl.split;
+    info->pos_major = pl.posMajor;
+    info->grid = pl.grid;
+    info->workspace_bytes = pl.wsBytes;
+    return MI355CONV_OK;
+}
+
+int conv2d_set_tuning(int variant, int split)
+{
+    if (variant < MI355CONV_VARIANT_AUTO || variant > MI355CONV_VARIANT_MFMA || split < 0)
+        return MI355CONV_ERR_UNSUPPORTED;
+    g_forceVariant.store(variant);
+    g_forceSplit.store(split);
+    return MI355CONV_OK;
+}
+
+int conv2d_fwd(const float *X, const float *W, float *Y, const conv2d_desc *d, void *ws, size_t ws_bytes,
+               void *stream)
+{
+    Shape s;
+    Plan pl;
+    int rc = check_desc(d, &s);
+    if (rc != MI355CONV_OK) return rc;
+    pl = plan_fwd(s);
+    rc = check_buffers(X, W, Y, pl, ws, ws_bytes);
+    if (rc != MI355CONV_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (pl.variant == MI355CONV_VARIANT_DIRECT) {
+        hipError_t e = launch_direct_fwd(X, W, Y, s, st);
+        return e == hipSuccess ? MI355CONV_OK : hip_fail(e);
+    }
+    return run_gather(X, W, Y, s, pl, false, ws, st);
+}
+
+int conv2d_bwd_data(const float *dY, const float *W, float *dX, const conv2d_desc *d, void *ws,
+                    size_t ws_bytes, void *stream)
+{
+    Shape s;
+    Plan pl;
+    int rc = check_desc(d, &s);
+    if (rc != MI355CONV_OK) return rc;
+    pl = plan_bwd_data(s);
+    rc = check_buffers(dY, W, dX, pl, ws, ws_bytes);
+    if (rc != MI355CONV_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (pl.variant == MI355CONV_VARIANT_DIRECT) {
+        hipError_t e = launch_direct_bwd_data(dY, W, dX, s, st);
+        return e == hipSuccess ? MI355CONV_OK : hip_fail(e);
+    }
+    return run_gather(dY, W, dX, s, pl, true, ws, st);
+}
+
+int deconv2d(const float *dY, const float *W, float *dX, const conv2d_desc *d, void *ws, size_t ws_bytes,
+             void *stream)
+{
+    return conv2d_bwd_data(dY, W, dX, d, ws, ws_bytes, stream);
+}
+
+int conv2d_bwd_weight(const float *X, const float *dY, float *dW, const conv2d_desc *d, void *ws,
+                      size_t ws_bytes, void *stream)
+{
+    Shape s;
+    Plan pl;
+    int rc = check_desc(d, &s);
+    if (rc != MI355CONV_OK) return rc;
+    pl = plan_bwd_weight(s);
+    rc = check_buffers(X, dY, dW, pl, ws, ws_bytes);
+    if (rc != MI355CONV_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (pl.variant == MI355CONV_VARIANT_DIRECT) {
+        hipError_t e = launch_direct_bwd_weight(X, dY, dW, s, st);
+        return e == hipSuccess ? MI355CONV_OK : hip_fail(e);
+    }
+    WgradParams w;
+    memset(&w, 0, sizeof w);
+    w.X = X;
+    w.G = dY;
+    w.C = pl.split > 1 ? static_cast<float *>(ws) : dW;
+    w.N = s.N; w.IH = s.IH; w.IW = s.IW; w.IC = s.IC; w.OC = s.OC; w.OH = s.OH; w.OW = s.OW;
+    w.FH = s.FH; w.FW = s.FW; w.sh = s.sh; w.sw = s.sw; w.ph = s.ph; w.pw = s.pw;
+    w.posMajor = pl.posMajor;
+    w.split = pl.split;
+    w.sliceStride = pl.sliceStride;
+    w.tilesN = pl.tilesN;
+    w.M = s.N * s.OH * s.OW;
+    w.flushChunks = pl.flushChunks;
+    hipError_t e = launch_wgrad(w, pl.bm, pl.bn, pl.grid, st);
+    if (e != hipSuccess) return hip_fail(e);
+    if (pl.split > 1) {
+        e = launch_slice_reduce(static_cast<const float *>(ws), dW, pl.outElems, pl.split, pl.sliceStride, st);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return MI355CONV_OK;
+}
+
+const char *conv2d_status_string(int status)
+{
+    switch (status) {
+    case MI355CONV_OK: return "ok";
+    case MI355CONV_ERR_NULL_PTR: return "null pointer";
+    case MI355CONV_ERR_BAD_DIM: return "bad dimension";
+    case MI355CONV_ERR_WORKSPACE: return "workspace missing or too small";
+    case MI355CONV_ERR_ALIGNMENT: return "pointer not 16-byte aligned";
+    case MI355CONV_ERR_UNSUPPORTED: return "unsupported argument";
+    case MI355CONV_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+const char *conv2d_last_hip_error(void) { return t_hipError; }
+
+}  // extern "C"

@@ -1,0 +1,381 @@
+// Implicit-GEMM ("gather-GEMM") kernel for forward convolution and backward-data on
+// v_mfma_f32_32x32x2_f32, written for gfx950 (wave64, 4 waves per workgroup).
+//
+// GEMM view (never materialised): rows = pixels of the tensor being produced, columns =
+// its channels, reduction = (filter tap, source channel).  A workgroup owns a BM x BN
+// output tile and walks the reduction in stages of kBK source channels of one tap:
+//   global (NHWC, 16-byte loads along the channel axis) -> registers -> LDS -> MFMA.
+// The next stage's global loads are issued before the current stage's MFMAs and land in
+// the other LDS buffer afterwards, so one barrier per stage suffices.
+//
+// Two things make it a small-feature-map operator (paper Sec. IV: special conv\deconv
+// operators that cut the work more the smaller the map is):
+//  * every tile first ORs, over its rows, the set of filter taps that fall inside the
+//    source image, and only walks that set.  With rows ordered (y, x, n) a tile sits on one
+//    pixel position, so at 2x2/4x4/8x8 maps with a padded 3x3 filter only 44/69/84 % of the
+//    taps are ever multiplied;
+//  * backward-data is split into sh*sw stride phases; a tile belongs to one phase and its
+//    tap set holds only the taps congruent to that phase, so no inserted zero is multiplied
+//    and pixels no tap reaches are written as 0 by tiles with an empty tap set.
+//
+// MFMA operand layout used below (AMD CDNA3/4 ISA, v_mfma_f32_32x32x2_f32): lane l holds
+// A[i = l%32][k = l/32] and B[k = l/32][j = l%32]; accumulator register r of lane l is
+// D[i = 8*(r/4) + 4*(l/32) + r%4][j = l%32].  The order in which reduction elements are fed
+// is free as long as A and B agree, so a lane reads FOUR consecutive k (one 16-byte LDS
+// read at k = 8*jj + 4*(l/32)) and uses them in four successive MFMAs.
+#include "conv_internal.h"
+
+namespace mi355conv {
+
+typedef float float16v __attribute__((ext_vector_type(16)));
+
+namespace {
+
+constexpr int LDA = kBK + 4;   // LDS row pitch (floats) of a [row][k] tile: 16-byte aligned, bank-skewed
+
+template <int BM, int BN, int WAVES_M, bool BWD>
+struct GG {
+    static constexpr int WAVES_N = 4 / WAVES_M;
+    static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;   // wave tile
+    static constexpr int MB = WTM / 32, NB = WTN / 32;             // 32x32 MFMA blocks per wave
+    static constexpr int PA = BM / 32;                             // A loader passes (32 rows each)
+    // forward: B tile is [BN cols][kBK] (k contiguous, like A); backward-data: [kBK][BN] (col contiguous)
+    static constexpr int LDB = BWD ? (BN + 8) : LDA;
+    static constexpr int B_TPR = BWD ? BN / 4 : 8;                 // threads per B tile row
+    static constexpr int B_RPP = kThreads / B_TPR;                 // B rows per pass
+    static constexpr int B_ROWS = BWD ? kBK : BN;
+    static constexpr int PB = (B_ROWS + B_RPP - 1) / B_RPP;
+    static constexpr int A_STAGE = BM * LDA;
+    static constexpr int B_STAGE = B_ROWS * LDB;
+    static constexpr int TABLE_INTS = 4 * BM + 4;
+    static constexpr size_t SMEM_BYTES = (2 * (A_STAGE + B_STAGE) + TABLE_INTS) * sizeof(float);
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be whole 32x32 blocks");
+    static_assert(B_ROWS % B_RPP == 0 || B_ROWS < B_RPP, "B loader passes");
+};
+
+constexpr int kInvalidCoord = -(1 << 28);
+
+}  // namespace
+
+template <int BM, int BN, int WAVES_M, bool BWD>
+__global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGemmParams p)
+{
+    using T = GG<BM, BN, WAVES_M, BWD>;
+    extern __shared__ float4 smem_raw[];
+    float *smem = reinterpret_cast<float *>(smem_raw);
+    float *As = smem;
+    float *Bs = As + 2 * T::A_STAGE;
+    int *rowBase = reinterpret_cast<int *>(Bs + 2 * T::B_STAGE);
+    int *rowY = rowBase + BM;
+    int *rowX = rowY + BM;
+    int *outRow = rowX + BM;
+    unsigned *tapMaskS = reinterpret_cast<unsigned *>(outRow + BM);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+
+    // ---- which tile / slice / phase --------------------------------------------------
+    int bid = blockIdx.x;
+    const int tn = bid % p.tilesN;
+    bid /= p.tilesN;
+    const int slice = bid % p.split;
+    const int tmGlobal = bid / p.split;
+    int phase = 0;
+    while (phase + 1 < p.nPhases && tmGlobal >= p.phaseTileStart[phase + 1]) ++phase;
+    const int tmLocal = tmGlobal - p.phaseTileStart[phase];
+    const int ra = p.phaseRa[phase], rb = p.phaseRb[phase];
+    const int PY0 = p.phaseY0[phase], PX0 = p.phaseX0[phase];
+    const int PDH = p.phaseDH[phase], PDW = p.phaseDW[phase];
+    const int Mphase = p.Nimg * PDH * PDW;
+    const int n0 = tn * BN;
+
+    if (tid < 2) tapMaskS[tid] = 0u;
+    __syncthreads();
+
+    // ---- row tables: one thread per tile row ------------------------------------------
+    if (tid < BM) {
+        const int m = tmLocal * BM + tid;
+        int base = 0, y0 = kInvalidCoord, x0 = kInvalidCoord, orow = -1;
+        if (m < Mphase) {
+            int n, i, j;
+            if (p.posMajor) {
+                n = m % p.Nimg;
+                const int pos = m / p.Nimg;
+                i = pos / PDW;
+                j = pos - i * PDW;
+            } else {
+                const int hw = PDH * PDW;
+                n = m / hw;
+                const int r = m - n * hw;
+                i = r / PDW;
+                j = r - i * PDW;
+            }
+            int dyc, dxc;
+            if (BWD) {
+                dyc = PY0 + i * p.sh;
+                dxc = PX0 + j * p.sw;
+                y0 = (PY0 + p.ph) / p.sh + i;
+                x0 = (PX0 + p.pw) / p.sw + j;
+            } else {
+                dyc = i;
+                dxc = j;
+                y0 = i * p.sh - p.ph;
+                x0 = j * p.sw - p.pw;
+            }
+            orow = (n * p.DH + dyc) * p.DW + dxc;
+            base = ((n * p.SH + y0) * p.SW + x0) * p.SC;
+        }
+        unsigned lo = 0u, hi = 0u;
+        int t = 0;
+        for (int fh = 0; fh < p.FH; ++fh) {
+            bool okh;
+            int sy;
+            if (BWD) {
+                okh = (fh % p.sh) == ra;
+                sy = y0 - fh / p.sh;
+            } else {
+                okh = true;
+                sy = y0 + fh;
+            }
+            okh = okh && (unsigned)sy < (unsigned)p.SH;
+            for (int fw = 0; fw < p.FW; ++fw, ++t) {
+                bool okw;
+                int sx;
+                if (BWD) {
+                    okw = (fw % p.sw) == rb;
+                    sx = x0 - fw / p.sw;
+                } else {
+                    okw = true;
+                    sx = x0 + fw;
+                }
+                okw = okw && (unsigned)sx < (unsigned)p.SW;
+                if (okh && okw) {
+                    if (t < 32) lo |= 1u << t;
+                    else hi |= 1u << (t - 32);
+                }
+            }
+        }
+        if (lo) atomicOr(&tapMaskS[0], lo);
+        if (hi) atomicOr(&tapMaskS[1], hi);
+        rowBase[tid] = base;
+        rowY[tid] = y0;
+        rowX[tid] = x0;
+        outRow[tid] = orow;
+    }
+    __syncthreads();
+
+    const unsigned long long tapMask =
+        (unsigned long long)tapMaskS[0] | ((unsigned long long)tapMaskS[1] << 32);
+    const int chunksPerTap = p.SC / kBK;
+    const int nIter = __popcll(tapMask) * chunksPerTap;
+    const int it0 = (int)((long long)slice * nIter / p.split);
+    const int it1 = (int)((long long)(slice + 1) * nIter / p.split);
+
+    // ---- per-thread loader state --------------------------------------------------------
+    const int aSeg = tid & 7, aRow = tid >> 3;
+    int rBase[T::PA], rY[T::PA], rX[T::PA];
+#pragma unroll
+    for (int i = 0; i < T::PA; ++i) {
+        const int r = aRow + 32 * i;
+        rBase[i] = rowBase[r] + aSeg * 4;
+        rY[i] = rowY[r];
+        rX[i] = rowX[r];
+    }
+    const int bSeg = tid % T::B_TPR, bRow = tid / T::B_TPR;
+    const long long wRowStride = (long long)p.FH * p.FW * (BWD ? p.DC : p.SC);  // floats per oc in W
+
+    // reduction cursor: remaining taps (bit set), current tap's offsets, chunk within the tap
+    unsigned long long rem = tapMask;
+    for (int k = it0 / chunksPerTap; k > 0; --k) rem &= rem - 1;
+    int chunk = it0 % chunksPerTap;
+    int dy = 0, dx = 0, tapOffA = 0, tapOffB = 0;
+    unsigned aValid = 0u;
+
+    auto set_tap = [&]() {
+        const int t = __ffsll((long long)rem) - 1;
+        const int fh = t / p.FW, fw = t - fh * p.FW;
+        if (BWD) {
+            dy = -(fh / p.sh);
+            dx = -(fw / p.sw);
+            tapOffB = t * p.DC;
+        } else {
+            dy = fh;
+            dx = fw;
+            tapOffB = t * p.SC;
+        }
+        tapOffA = (dy * p.SW + dx) * p.SC;
+        aValid = 0u;
+#pragma unroll
+        for (int i = 0; i < T::PA; ++i)
+            if ((unsigned)(rY[i] + dy) < (unsigned)p.SH && (unsigned)(rX[i] + dx) < (unsigned)p.SW)
+                aValid |= 1u << i;
+    };
+
+    float4 ga[T::PA], gb[T::PB];
+    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+
+    auto gload = [&]() {
+        const int c0 = chunk * kBK;
+#pragma unroll
+        for (int i = 0; i < T::PA; ++i) {
+            ga[i] = zero4;
+            if (aValid & (1u << i))
+                ga[i] = *reinterpret_cast<const float4 *>(p.A + (long long)(rBase[i] + tapOffA + c0));
+        }
+#pragma unroll
+        for (int i = 0; i < T::PB; ++i) {
+            gb[i] = zero4;
+            const int r = bRow + T::B_RPP * i;
+            if (BWD) {
+                const int col = n0 + bSeg * 4;
+                if (r < kBK && col < p.DC)
+                    gb[i] = *reinterpret_cast<const float4 *>(p.B + (long long)(c0 + r) * wRowStride +
+                                                              tapOffB + col);
+            } else {
+                const int col = n0 + r;
+                if (r < BN && col < p.DC)
+                    gb[i] = *reinterpret_cast<const float4 *>(p.B + (long long)col * wRowStride +
+                                                              tapOffB + c0 + bSeg * 4);
+            }
+        }
+    };
+
+    auto advance = [&]() {
+        if (++chunk == chunksPerTap) {
+            chunk = 0;
+            rem &= rem - 1;
+            if (rem) set_tap();
+        }
+    };
+
+    auto lds_store = [&](int buf) {
+        float *a = As + buf * T::A_STAGE;
+        float *b = Bs + buf * T::B_STAGE;
+#pragma unroll
+        for (int i = 0; i < T::PA; ++i)
+            *reinterpret_cast<float4 *>(a + (aRow + 32 * i) * LDA + aSeg * 4) = ga[i];
+#pragma unroll
+        for (int i = 0; i < T::PB; ++i) {
+            const int r = bRow + T::B_RPP * i;
+            if (r < T::B_ROWS) *reinterpret_cast<float4 *>(b + r * T::LDB + bSeg * 4) = gb[i];
+        }
+    };
+
+    // ---- accumulators -------------------------------------------------------------------
+    float16v acc[T::MB][T::NB];
+#pragma unroll
+    for (int i = 0; i < T::MB; ++i)
+#pragma unroll
+        for (int j = 0; j < T::NB; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int wm = wave / T::WAVES_N, wn = wave % T::WAVES_N;
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    auto compute = [&](int buf) {
+        const float *a = As + buf * T::A_STAGE + (wm * T::WTM + l32) * LDA + lh * 4;
+        const float *b = BWD ? Bs + buf * T::B_STAGE + (lh * 4) * T::LDB + wn * T::WTN + l32
+                             : Bs + buf * T::B_STAGE + (wn * T::WTN + l32) * T::LDB + lh * 4;
+#pragma unroll
+        for (int jj = 0; jj < kBK / 8; ++jj) {
+            float4 fa[T::MB], fb[T::NB];
+#pragma unroll
+            for (int i = 0; i < T::MB; ++i)
+                fa[i] = *reinterpret_cast<const float4 *>(a + i * 32 * LDA + jj * 8);
+#pragma unroll
+            for (int j = 0; j < T::NB; ++j) {
+                if (BWD) {
+                    const float *q = b + (jj * 8) * T::LDB + j * 32;
+                    fb[j] = make_float4(q[0], q[T::LDB], q[2 * T::LDB], q[3 * T::LDB]);
+                } else {
+                    fb[j] = *reinterpret_cast<const float4 *>(b + j * 32 * T::LDB + jj * 8);
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+#pragma unroll
+                for (int i = 0; i < T::MB; ++i)
+#pragma unroll
+                    for (int j = 0; j < T::NB; ++j) {
+                        const float av = t == 0 ? fa[i].x : t == 1 ? fa[i].y : t == 2 ? fa[i].z : fa[i].w;
+                        const float bv = t == 0 ? fb[j].x : t == 1 ? fb[j].y : t == 2 ? fb[j].z : fb[j].w;
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
+                    }
+            }
+        }
+    };
+
+    // ---- main loop ----------------------------------------------------------------------
+    if (it0 < it1) {
+        set_tap();
+        gload();
+        advance();
+        lds_store(0);
+        __syncthreads();
+        int buf = 0;
+        for (int it = it0; it < it1; ++it) {
+            const bool more = it + 1 < it1;
+            if (more) {
+                gload();
+                advance();
+            }
+            compute(buf);
+            if (more) lds_store(buf ^ 1);
+            __syncthreads();
+            buf ^= 1;
+        }
+    }
+
+    // ---- epilogue: rows of a 32x32 block are spread over registers, columns over lanes ----
+    float *C = p.C + (long long)slice * p.sliceStride;
+#pragma unroll
+    for (int i = 0; i < T::MB; ++i)
+#pragma unroll
+        for (int j = 0; j < T::NB; ++j) {
+            const int col = n0 + wn * T::WTN + j * 32 + l32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = wm * T::WTM + i * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
+                const int orow = outRow[row];
+                if (orow >= 0 && col < p.DC) C[(long long)orow * p.DC + col] = acc[i][j][r];
+            }
+        }
+}
+
+template <int BM, int BN, int WAVES_M, bool BWD>
+static hipError_t launch_one(const GatherGemmParams &p, int grid, hipStream_t st)
+{
+    using T = GG<BM, BN, WAVES_M, BWD>;
+    auto kern = gather_gemm_kernel<BM, BN, WAVES_M, BWD>;
+    static bool attrSet[16] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 16 || !attrSet[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)T::SMEM_BYTES);
+        if (e != hipSuccess) return e;
+        if (dev >= 0 && dev < 16) attrSet[dev] = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), T::SMEM_BYTES, st, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_gemm(const GatherGemmParams &p, bool bwdData, int bm, int bn, int grid,
+                              hipStream_t st)
+{
+#define MI355_GG_CASE(BM_, BN_, WM_)                                                    \
+    if (bm == BM_ && bn == BN_)                                                          \
+        return bwdData ? launch_one<BM_, BN_, WM_, true>(p, grid, st)                    \
+                       : launch_one<BM_, BN_, WM_, false>(p, grid, st);
+    MI355_GG_CASE(128, 128, 2)
+    MI355_GG_CASE(128, 64, 2)
+    MI355_GG_CASE(64, 64, 2)
+    MI355_GG_CASE(128, 32, 4)
+#undef MI355_GG_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace mi355conv

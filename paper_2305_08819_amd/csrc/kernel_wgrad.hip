@@ -1,0 +1,257 @@
+// Backward-weight on v_mfma_f32_32x32x2_f32 for gfx950.
+//
+// GEMM view: dW[oc, col] = sum_m G[m, oc] * Xg[m, col], m = (n, oh, ow) over N*OH*OW rows,
+// col = (fh*FW + fw)*IC + ic, Xg the input pixel that tap (fh,fw) reads for output pixel m
+// (zero outside the image).  The output is small and the reduction is long, so the row
+// range is always cut into slices (grid = tiles x slices); slice partials go to the
+// workspace and a separate kernel adds them in a fixed order.
+//
+// Both operands arrive with the reduction index m as the SLOW memory index (NHWC rows are
+// channel-contiguous), so both LDS tiles are [k = m][channel] and MFMA operands are read
+// with 4-byte LDS loads: lane l takes k = 8*jj + 4*(l/32) + t for t = 0..3 and channel l%32.
+//
+// Accuracy: an fp32 accumulator is folded into a second one every `flushChunks` stages, so
+// no running sum is longer than flushChunks*kBK products however long the slice is.
+//
+// Small maps (paper Sec. IV): with rows ordered (oh, ow, n) a stage of kBK rows sits on one
+// output position; stages whose position lies in the padding for every tap of the tile are
+// skipped outright.
+#include "conv_internal.h"
+
+namespace mi355conv {
+
+typedef float float16v __attribute__((ext_vector_type(16)));
+
+namespace {
+template <int BM, int BN>
+struct WG {
+    static constexpr int WTM = BM / 2, WTN = BN / 2;
+    static constexpr int MB = WTM / 32, NB = WTN / 32;
+    static constexpr int LDG = BM + 8, LDX = BN + 8;
+    static constexpr int G_TPR = BM / 4, G_RPP = kThreads / G_TPR, PG = kBK / G_RPP;
+    static constexpr int X_TPR = BN / 4, X_RPP = kThreads / X_TPR, PX = kBK / X_RPP;
+    static constexpr int G_STAGE = kBK * LDG, X_STAGE = kBK * LDX;
+    static constexpr size_t SMEM_BYTES = 2 * (G_STAGE + X_STAGE) * sizeof(float);
+};
+}  // namespace
+
+template <int BM, int BN>
+__global__ __launch_bounds__(kThreads, 2) void wgrad_kernel(const WgradParams p)
+{
+    using T = WG<BM, BN>;
+    extern __shared__ float4 smem_raw[];
+    float *Gs = reinterpret_cast<float *>(smem_raw);
+    float *Xs = Gs + 2 * T::G_STAGE;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int bid = blockIdx.x;
+    const int tn = bid % p.tilesN;
+    bid /= p.tilesN;
+    const int slice = bid % p.split;
+    const int tmo = bid / p.split;
+    const int oc0 = tmo * BM, col0 = tn * BN;
+    const int Ktot = p.FH * p.FW * p.IC;
+
+    const int chunksTotal = (p.M + kBK - 1) / kBK;
+    const int ch0 = (int)((long long)slice * chunksTotal / p.split);
+    const int ch1 = (int)((long long)(slice + 1) * chunksTotal / p.split);
+
+    // loader roles: fixed channel segment, rows vary per stage
+    const int gSeg = tid % T::G_TPR, gRow = tid / T::G_TPR;
+    const int xSeg = tid % T::X_TPR, xRow = tid / T::X_TPR;
+    const int gOc = oc0 + gSeg * 4;
+    const bool gOk = gOc < p.OC;
+    const int xCol = col0 + xSeg * 4;
+    const bool xOk = xCol < Ktot;
+    const int xTap = xOk ? xCol / p.IC : 0;
+    const int xIc = xCol - xTap * p.IC;
+    const int xFh = xTap / p.FW, xFw = xTap - xFh * p.FW;
+    const int ohow = p.OH * p.OW;
+
+    // taps covered by this tile (for the stage-skip test)
+    const int tapLo = col0 / p.IC;
+    const int lastCol = (col0 + BN - 1 < Ktot - 1) ? col0 + BN - 1 : Ktot - 1;
+    const int tapHi = lastCol / p.IC;
+
+    auto stage_live = [&](int ch) -> bool {
+        if (!p.posMajor) return true;
+        const int pos = (ch * kBK) / p.N;   // all kBK rows of the stage share this position
+        const int oh = pos / p.OW, ow = pos - oh * p.OW;
+        for (int t = tapLo; t <= tapHi; ++t) {
+            const int fh = t / p.FW, fw = t - fh * p.FW;
+            if ((unsigned)(oh * p.sh - p.ph + fh) < (unsigned)p.IH &&
+                (unsigned)(ow * p.sw - p.pw + fw) < (unsigned)p.IW)
+                return true;
+        }
+        return false;
+    };
+    auto next_live = [&](int ch) -> int {
+        while (ch < ch1 && !stage_live(ch)) ++ch;
+        return ch;
+    };
+
+    float4 gg[T::PG], gx[T::PX];
+    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+
+    auto gload = [&](int ch) {
+#pragma unroll
+        for (int i = 0; i < T::PG; ++i) {
+            gg[i] = zero4;
+            const int m = ch * kBK + gRow + T::G_RPP * i;
+            if (gOk && m < p.M) {
+                int pix = m;
+                if (p.posMajor) {
+                    const int pos = m / p.N, n = m - pos * p.N;
+                    pix = n * ohow + pos;
+                }
+                gg[i] = *reinterpret_cast<const float4 *>(p.G + (long long)pix * p.OC + gOc);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < T::PX; ++i) {
+            gx[i] = zero4;
+            const int m = ch * kBK + xRow + T::X_RPP * i;
+            if (xOk && m < p.M) {
+                int n, oh, ow;
+                if (p.posMajor) {
+                    const int pos = m / p.N;
+                    n = m - pos * p.N;
+                    oh = pos / p.OW;
+                    ow = pos - oh * p.OW;
+                } else {
+                    n = m / ohow;
+                    const int r = m - n * ohow;
+                    oh = r / p.OW;
+                    ow = r - oh * p.OW;
+                }
+                const int ih = oh * p.sh - p.ph + xFh, iw = ow * p.sw - p.pw + xFw;
+                if ((unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW)
+                    gx[i] = *reinterpret_cast<const float4 *>(
+                        p.X + ((long long)(n * p.IH + ih) * p.IW + iw) * p.IC + xIc);
+            }
+        }
+    };
+    auto lds_store = [&](int buf) {
+        float *g = Gs + buf * T::G_STAGE, *x = Xs + buf * T::X_STAGE;
+#pragma unroll
+        for (int i = 0; i < T::PG; ++i)
+            *reinterpret_cast<float4 *>(g + (gRow + T::G_RPP * i) * T::LDG + gSeg * 4) = gg[i];
+#pragma unroll
+        for (int i = 0; i < T::PX; ++i)
+            *reinterpret_cast<float4 *>(x + (xRow + T::X_RPP * i) * T::LDX + xSeg * 4) = gx[i];
+    };
+
+    float16v acc[T::MB][T::NB], acc2[T::MB][T::NB];
+#pragma unroll
+    for (int i = 0; i < T::MB; ++i)
+#pragma unroll
+        for (int j = 0; j < T::NB; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                acc[i][j][r] = 0.f;
+                acc2[i][j][r] = 0.f;
+            }
+
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    auto compute = [&](int buf) {
+        const float *g = Gs + buf * T::G_STAGE + (lh * 4) * T::LDG + wm * T::WTM + l32;
+        const float *x = Xs + buf * T::X_STAGE + (lh * 4) * T::LDX + wn * T::WTN + l32;
+#pragma unroll
+        for (int jj = 0; jj < kBK / 8; ++jj) {
+            float fa[T::MB][4], fb[T::NB][4];
+#pragma unroll
+            for (int i = 0; i < T::MB; ++i)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) fa[i][t] = g[(jj * 8 + t) * T::LDG + i * 32];
+#pragma unroll
+            for (int j = 0; j < T::NB; ++j)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) fb[j][t] = x[(jj * 8 + t) * T::LDX + j * 32];
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int i = 0; i < T::MB; ++i)
+#pragma unroll
+                    for (int j = 0; j < T::NB; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t], fb[j][t], acc[i][j], 0, 0, 0);
+        }
+    };
+    auto flush = [&]() {
+#pragma unroll
+        for (int i = 0; i < T::MB; ++i)
+#pragma unroll
+            for (int j = 0; j < T::NB; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    acc2[i][j][r] += acc[i][j][r];
+                    acc[i][j][r] = 0.f;
+                }
+    };
+
+    int cur = next_live(ch0);
+    if (cur < ch1) {
+        gload(cur);
+        lds_store(0);
+        __syncthreads();
+        int buf = 0, sinceFlush = 0;
+        while (cur < ch1) {
+            const int nxt = next_live(cur + 1);
+            if (nxt < ch1) gload(nxt);
+            compute(buf);
+            if (++sinceFlush == p.flushChunks) {
+                flush();
+                sinceFlush = 0;
+            }
+            if (nxt < ch1) lds_store(buf ^ 1);
+            __syncthreads();
+            buf ^= 1;
+            cur = nxt;
+        }
+    }
+    flush();
+
+    float *C = p.C + (long long)slice * p.sliceStride;
+#pragma unroll
+    for (int i = 0; i < T::MB; ++i)
+#pragma unroll
+        for (int j = 0; j < T::NB; ++j) {
+            const int col = col0 + wn * T::WTN + j * 32 + l32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int oc = oc0 + wm * T::WTM + i * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
+                if (oc < p.OC && col < Ktot) C[(long long)oc * Ktot + col] = acc2[i][j][r];
+            }
+        }
+}
+
+template <int BM, int BN>
+static hipError_t launch_one(const WgradParams &p, int grid, hipStream_t st)
+{
+    using T = WG<BM, BN>;
+    auto kern = wgrad_kernel<BM, BN>;
+    static bool attrSet[16] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 16 || !attrSet[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)T::SMEM_BYTES);
+        if (e != hipSuccess) return e;
+        if (dev >= 0 && dev < 16) attrSet[dev] = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), T::SMEM_BYTES, st, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_wgrad(const WgradParams &p, int bm, int bn, int grid, hipStream_t st)
+{
+    if (bm == 128 && bn == 128) return launch_one<128, 128>(p, grid, st);
+    if (bm == 64 && bn == 128) return launch_one<64, 128>(p, grid, st);
+    if (bm == 64 && bn == 64) return launch_one<64, 64>(p, grid, st);
+    if (bm == 128 && bn == 64) return launch_one<128, 64>(p, grid, st);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace mi355conv

@@ -1,0 +1,94 @@
+"""Helpers for the GPU parity tests: run the three operators through the C ABI binding on
+guarded, NaN-poisoned device buffers and compare with the CPU oracle."""
+import numpy as np
+import torch
+
+import oracle
+import paper_2305_08819_amd as mc
+
+REL_L2_TOL = 1e-5     # ||gpu - ref||_2 / ||ref||_2, the bar stated for this build
+MAX_ABS_TOL = 1e-3    # max |gpu - ref|
+GUARD = 1024          # floats of canary on each side of every output
+
+
+def desc_of(layer):
+    return mc.make_desc(layer.N, layer.IH, layer.IW, layer.IC, layer.OC, layer.FH, layer.FW,
+                        layer.stride, layer.pad)
+
+
+def guarded(shape):
+    """NaN-filled output of `shape` inside a larger buffer whose margins hold a canary."""
+    n = int(np.prod(shape))
+    buf = torch.full((n + 2 * GUARD,), 12345.0, dtype=torch.float32, device="cuda")
+    out = buf[GUARD:GUARD + n]
+    out.fill_(float("nan"))
+    return buf, out.view(*shape)
+
+
+def guards_intact(buf):
+    return bool((buf[:GUARD] == 12345.0).all().item() and (buf[-GUARD:] == 12345.0).all().item())
+
+
+def run_gpu(op, desc, a, b, stream=None, entry=None):
+    """op in {'fwd','bwd_data','bwd_weight'}; a, b numpy fp32 inputs in ABI order."""
+    ta, tb = torch.from_numpy(a).cuda(), torch.from_numpy(b).cuda()
+    shape = {"fwd": (desc.N, desc.OH, desc.OW, desc.OC),
+             "bwd_data": (desc.N, desc.IH, desc.IW, desc.IC),
+             "bwd_weight": (desc.OC, desc.FH, desc.FW, desc.IC)}[op]
+    buf, out = guarded(shape)
+    fn = entry or {"fwd": mc.conv2d_fwd, "bwd_data": mc.conv2d_bwd_data,
+                   "bwd_weight": mc.conv2d_bwd_weight}[op]
+    opcode = {"fwd": mc.OP_FWD, "bwd_data": mc.OP_BWD_DATA, "bwd_weight": mc.OP_BWD_WEIGHT}[op]
+    need = mc.conv2d_workspace_bytes(opcode, desc)
+    wsbuf = None
+    ws = None
+    if need:
+        wsbuf = torch.full((need // 4 + 2 * GUARD,), 12345.0, dtype=torch.float32, device="cuda")
+        ws = wsbuf[GUARD:GUARD + need // 4]
+        ws.fill_(float("nan"))
+    if stream is not None:
+        stream.wait_stream(torch.cuda.current_stream())
+    fn(ta, tb, out, desc, ws=ws, stream=stream)
+    if stream is not None:
+        stream.synchronize()
+    torch.cuda.synchronize()
+    assert guards_intact(buf), "%s wrote outside its output" % op
+    if wsbuf is not None:
+        assert guards_intact(wsbuf), "%s wrote outside its workspace" % op
+    return out.cpu().numpy()
+
+
+def run_oracle(op, desc, a, b):
+    s, p = (desc.sh, desc.sw), (desc.ph, desc.pw)
+    if op == "fwd":
+        return oracle.conv2d_fwd(a, b, s, p)
+    if op == "bwd_data":
+        return oracle.conv2d_bwd_data(a, b, (desc.IH, desc.IW), s, p)
+    return oracle.conv2d_bwd_weight(a, b, (desc.FH, desc.FW), s, p)
+
+
+def errors(got, ref):
+    got64 = got.astype(np.float64)
+    assert not np.isnan(got64).any(), "output has unwritten (NaN) elements"
+    diff = got64 - ref
+    denom = float(np.linalg.norm(ref.ravel()))
+    rel = float(np.linalg.norm(diff.ravel())) / denom if denom > 0 else float(np.abs(diff).max())
+    return rel, float(np.abs(diff).max())
+
+
+def operands(op, X, W, G):
+    return {"fwd": (X, W), "bwd_data": (G, W), "bwd_weight": (X, G)}[op]
+
+
+def check_all_ops(desc, X, W, G, ops=("fwd", "bwd_data", "bwd_weight"), label=""):
+    """Run the requested operators on GPU and oracle; assert the tolerance; return stats."""
+    stats = {}
+    for op in ops:
+        a, b = operands(op, X, W, G)
+        got = run_gpu(op, desc, a, b)
+        ref = run_oracle(op, desc, a, b)
+        rel, mx = errors(got, ref)
+        stats[op] = (rel, mx)
+        assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL, \
+            "%s %s: rel_l2=%.3e max_abs=%.3e" % (label, op, rel, mx)
+    return stats

@@ -1,0 +1,87 @@
+"""Host-side tests of the C ABI that need no GPU: the library loads, exports every declared
+symbol, validates arguments before any HIP call, and plans sensibly."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2305_08819_amd as mc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(mc.LIB_PATH):
+        from paper_2305_08819_amd import build
+        build.build()
+    return mc.load()
+
+
+def test_exports_match_header(lib):
+    hdr = open(os.path.join(ROOT, "include", "mi355conv.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(conv2d_\w+|deconv2d)\s*\(", hdr))
+    assert declared == set(mc.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(lib):
+    assert lib.conv2d_status_string(0) == b"ok"
+    for code in range(-6, 0):
+        assert lib.conv2d_status_string(code) not in (b"ok", b"unknown status")
+    assert lib.conv2d_status_string(-99) == b"unknown status"
+
+
+def _call(lib, name, a, b, c, desc, ws=0, nbytes=0):
+    return getattr(lib, name)(ctypes.c_void_p(a), ctypes.c_void_p(b), ctypes.c_void_p(c),
+                              ctypes.byref(desc) if desc is not None else None,
+                              ctypes.c_void_p(ws), nbytes, None)
+
+
+@pytest.mark.parametrize("name", ["conv2d_fwd", "conv2d_bwd_data", "deconv2d", "conv2d_bwd_weight"])
+def test_argument_errors_before_any_hip_call(lib, name):
+    good = mc.make_desc(4, 8, 8, 3, 16, 3, 3, 1, 1)
+    assert _call(lib, name, 0, 256, 512, good) == -1            # null tensor
+    assert _call(lib, name, 256, 512, 768, None) == -1          # null desc
+    assert _call(lib, name, 256, 512, 772, good) == -4          # misaligned
+    for field, val in (("N", 0), ("IC", -1), ("sh", 0), ("pw", -1), ("FH", 0)):
+        bad = mc.make_desc(4, 8, 8, 3, 16, 3, 3, 1, 1)
+        setattr(bad, field, val)
+        assert _call(lib, name, 256, 512, 768, bad) == -2, field
+    assert _call(lib, name, 256, 512, 768, mc.make_desc(1, 2, 2, 4, 4, 5, 5, 1, 0)) == -2   # OH <= 0
+    assert _call(lib, name, 256, 512, 768, mc.make_desc(1 << 20, 64, 64, 64, 64, 3, 3, 1, 1)) == -2  # 2^32 elems
+
+
+def test_workspace_errors(lib):
+    d = mc.make_desc(128, 2, 2, 512, 512, 3, 3, 1, 1)
+    need = mc.conv2d_workspace_bytes(mc.OP_FWD, d)
+    assert need > 0
+    assert _call(lib, "conv2d_fwd", 256, 512, 768, d, 0, 0) == -3
+    assert _call(lib, "conv2d_fwd", 256, 512, 768, d, 1024, need - 1) == -3
+    assert _call(lib, "conv2d_fwd", 256, 512, 768, d, 1028, need) == -4
+
+
+def test_plans(lib):
+    q = mc.conv2d_query_plan
+    p = q(mc.OP_FWD, mc.make_desc(4, 8, 8, 3, 16, 3, 3, 1, 1))
+    assert p.variant == mc.VARIANT_DIRECT and p.workspace_bytes == 0
+    p = q(mc.OP_FWD, mc.make_desc(128, 32, 32, 64, 128, 3, 3, 2, 1))
+    assert p.variant == mc.VARIANT_MFMA and p.split == 1 and p.pos_major == 0 and p.grid >= 256
+    p = q(mc.OP_FWD, mc.make_desc(128, 2, 2, 512, 512, 3, 3, 1, 1))
+    assert p.variant == mc.VARIANT_MFMA and p.pos_major == 1 and p.split > 1
+    assert p.workspace_bytes == p.split * 128 * 2 * 2 * 512 * 4
+    p = q(mc.OP_BWD_WEIGHT, mc.make_desc(128, 32, 32, 64, 64, 3, 3, 1, 1))
+    assert p.variant == mc.VARIANT_MFMA and p.split > 1
+    with pytest.raises(mc.Mi355ConvError):
+        q(7, mc.make_desc(4, 8, 8, 3, 16, 3, 3, 1, 1))
+    # tuning override
+    mc.conv2d_set_tuning(mc.VARIANT_DIRECT, 0)
+    try:
+        assert q(mc.OP_FWD, mc.make_desc(128, 2, 2, 512, 512, 3, 3, 1, 1)).variant == mc.VARIANT_DIRECT
+    finally:
+        mc.conv2d_set_tuning(mc.VARIANT_AUTO, 0)
+    with pytest.raises(mc.Mi355ConvError):
+        mc.conv2d_set_tuning(5, 0)

@@ -1,0 +1,130 @@
+"""GPU parity: every operator through the C ABI against the CPU oracle, element by element.
+
+Tolerance (stated for this build): relative L2 <= 1e-5 and max abs <= 1e-3, written in
+tests/gpu_util.py.  Small shapes sweep odd sizes, ragged tiles, every variant and forced
+reduction splits; the configuration layers run at full size in the launch configuration that
+bench.py times.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2305_08819_amd as mc
+import workloads as wl
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(autouse=True)
+def _reset_tuning():
+    mc.conv2d_set_tuning(mc.VARIANT_AUTO, 0)
+    yield
+    mc.conv2d_set_tuning(mc.VARIANT_AUTO, 0)
+
+
+def small_inputs(desc, seed):
+    k = wl.stream_key("sweep", seed)
+    X = wl.uniform_pm1(k, (desc.N, desc.IH, desc.IW, desc.IC))
+    W = wl.uniform_pm1(k + 1, (desc.OC, desc.FH, desc.FW, desc.IC))
+    G = wl.uniform_pm1(k + 2, (desc.N, desc.OH, desc.OW, desc.OC))
+    return X, W, G
+
+
+# N, IH, IW, IC, OC, FH, FW, stride, pad  -- shapes only the direct variant can take
+ODD_SHAPES = [
+    (4, 8, 8, 3, 16, 3, 3, 1, 1),          # configuration 1
+    (1, 5, 7, 1, 1, 3, 3, 1, 1),
+    (3, 9, 6, 5, 2, 3, 2, (2, 1), (0, 1)),
+    (2, 7, 7, 24, 10, 5, 5, 1, 2),
+    (1, 11, 10, 3, 5, 2, 3, (3, 2), (1, 2)),
+    (2, 6, 6, 16, 3, 1, 1, 2, 0),
+    (2, 10, 9, 1, 3, 7, 7, 3, 3),
+    (1, 3, 3, 2, 2, 3, 3, 1, 0),
+    (1, 2, 2, 1, 1, 4, 4, 1, 1),           # filter larger than the map
+]
+
+
+@pytest.mark.parametrize("shp", ODD_SHAPES)
+def test_direct_variant_odd_shapes(shp):
+    say("direct %s" % (shp,))
+    d = mc.make_desc(*shp)
+    mc.conv2d_set_tuning(mc.VARIANT_DIRECT, 0)
+    gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), label=str(shp))
+
+
+# shapes the MFMA variants accept, chosen to give ragged row tiles, ragged column tiles,
+# several stride phases, non-square filters/strides/pads and more than 32 taps
+MFMA_SHAPES = [
+    (3, 7, 5, 32, 96, 3, 3, 2, 1),
+    (2, 9, 9, 64, 32, 3, 3, 1, 1),
+    (5, 6, 7, 32, 160, 1, 1, 1, 0),
+    (2, 8, 8, 32, 64, 1, 1, 2, 0),
+    (1, 12, 11, 64, 64, 5, 5, 1, 2),
+    (2, 13, 9, 32, 32, 3, 2, (2, 1), (0, 1)),
+    (2, 10, 10, 32, 64, 7, 7, 3, 3),
+    (1, 9, 8, 96, 224, 2, 3, (3, 2), (1, 2)),
+    (128, 2, 2, 64, 96, 3, 3, 1, 1),       # position-major rows
+    (128, 3, 3, 32, 32, 3, 3, 1, 1),
+    (256, 4, 4, 32, 64, 5, 5, 1, 2),
+    (128, 4, 4, 64, 32, 3, 3, 2, 1),
+    (1, 1, 1, 32, 32, 1, 1, 1, 0),
+    (2, 5, 5, 32, 32, 3, 3, 1, 2),         # pad larger than (F-1)/2
+]
+
+
+@pytest.mark.parametrize("split", [0, 1, 3])
+@pytest.mark.parametrize("shp", MFMA_SHAPES)
+def test_mfma_variant_shapes(shp, split):
+    say("mfma %s split=%d" % (shp, split))
+    d = mc.make_desc(*shp)
+    mc.conv2d_set_tuning(mc.VARIANT_MFMA, split)
+    for op in (mc.OP_FWD, mc.OP_BWD_DATA, mc.OP_BWD_WEIGHT):
+        assert mc.conv2d_query_plan(op, d).variant == mc.VARIANT_MFMA
+    gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), label=str(shp))
+
+
+def test_mfma_and_direct_agree_with_plan_defaults():
+    d = mc.make_desc(2, 9, 9, 64, 32, 3, 3, 1, 1)
+    gu.check_all_ops(d, *small_inputs(d, 7))
+
+
+def test_bitwise_reproducible_and_deconv_alias():
+    d = mc.make_desc(128, 4, 4, 64, 64, 3, 3, 1, 1)
+    X, W, G = small_inputs(d, 11)
+    for op in ("fwd", "bwd_data", "bwd_weight"):
+        a, b = gu.operands(op, X, W, G)
+        r1, r2 = gu.run_gpu(op, d, a, b), gu.run_gpu(op, d, a, b)
+        assert np.array_equal(r1, r2), op
+    r3 = gu.run_gpu("bwd_data", d, G, W, entry=mc.deconv2d)
+    assert np.array_equal(r3, gu.run_gpu("bwd_data", d, G, W))
+
+
+def test_side_stream():
+    d = mc.make_desc(2, 9, 9, 64, 32, 3, 3, 1, 1)
+    X, W, G = small_inputs(d, 13)
+    st = torch.cuda.Stream()
+    for op in ("fwd", "bwd_data", "bwd_weight"):
+        a, b = gu.operands(op, X, W, G)
+        got = gu.run_gpu(op, d, a, b, stream=st)
+        rel, mx = gu.errors(got, gu.run_oracle(op, d, a, b))
+        assert rel <= gu.REL_L2_TOL and mx <= gu.MAX_ABS_TOL
+
+
+FULL_LAYERS = [l for l in wl.all_layers()]
+
+
+@pytest.mark.parametrize("layer", FULL_LAYERS, ids=[l.name for l in FULL_LAYERS])
+def test_configuration_layers_full_size(layer):
+    say("full-size %s" % (layer,))
+    d = gu.desc_of(layer)
+    t = wl.make_inputs(layer)
+    stats = gu.check_all_ops(d, t["X"], t["W"], t["G"], label=layer.name)
+    say("  %s" % {k: "rel=%.2e max=%.2e" % v for k, v in stats.items()})
