@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the fp32 convolution hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input: forward,
+backward-data and backward-weight of one layer, enqueued back to back on one stream with
+inputs resident in HBM.  The default workload is the ResNet-style down-sampling layer
+(N=128, 32x32x64 -> 16x16x128, 3x3, stride 2, pad 1).  Prints ONE JSON line on stdout.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-cpu-baseline]
+  python bench.py --table [cfg2 cfg3 ...]   per-layer, per-operator table (stderr + JSON line)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads as wl  # noqa: E402
+
+PEAK_FP32_MFMA_TFLOPS = 157.3   # 256 CU x 256 FLOP/clk x 2.4 GHz (published dense fp32 matrix peak)
+PEAK_HBM_GBS = 8000.0
+OPS = ("fwd", "bwd_data", "bwd_weight")
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class LayerRunner:
+    """Device tensors + workspace for one layer; enqueues operators through the C ABI binding."""
+
+    def __init__(self, layer, mc, torch, random_fill=False):
+        self.layer, self.mc, self.torch = layer, mc, torch
+        self.desc = mc.make_desc(layer.N, layer.IH, layer.IW, layer.IC, layer.OC, layer.FH, layer.FW,
+                                 layer.stride, layer.pad)
+        if random_fill:   # timing-only tensors: same distributions, generated on the host once
+            rng = np.random.default_rng(wl.stream_key(layer.name) & 0xffffffff)
+            host = {"X": rng.standard_normal(layer.x_shape, dtype=np.float32),
+                    "W": rng.standard_normal(layer.w_shape, dtype=np.float32) * np.float32(np.sqrt(2.0 / layer.K)),
+                    "G": rng.standard_normal(layer.y_shape, dtype=np.float32)}
+        else:
+            host = wl.make_inputs(layer)
+        self.host = host
+        self.X = torch.from_numpy(host["X"]).cuda()
+        self.W = torch.from_numpy(host["W"]).cuda()
+        self.G = torch.from_numpy(host["G"]).cuda()
+        self.Y = torch.empty(layer.y_shape, dtype=torch.float32, device="cuda")
+        self.dX = torch.empty(layer.x_shape, dtype=torch.float32, device="cuda")
+        self.dW = torch.empty(layer.w_shape, dtype=torch.float32, device="cuda")
+        opcodes = {"fwd": mc.OP_FWD, "bwd_data": mc.OP_BWD_DATA, "bwd_weight": mc.OP_BWD_WEIGHT}
+        self.plans = {op: mc.conv2d_query_plan(opcodes[op], self.desc) for op in OPS}
+        need = max(p.workspace_bytes for p in self.plans.values())
+        self.ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+
+    def run(self, op):
+        mc = self.mc
+        if op == "fwd":
+            mc.conv2d_fwd(self.X, self.W, self.Y, self.desc, ws=self.ws)
+        elif op == "bwd_data":
+            mc.conv2d_bwd_data(self.G, self.W, self.dX, self.desc, ws=self.ws)
+        else:
+            mc.conv2d_bwd_weight(self.X, self.G, self.dW, self.desc, ws=self.ws)
+
+    def step(self):
+        for op in OPS:
+            self.run(op)
+
+    def event_ms(self, fn, launches, warm):
+        """Average milliseconds per call of fn between two events on the launch stream."""
+        torch = self.torch
+        for _ in range(warm):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(launches):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / launches
+
+
+def fwd_bytes(l):
+    """Minimum algorithmic HBM bytes of one operator: each of X, W, Y touched once."""
+    return 4 * (l.N * l.IH * l.IW * l.IC + l.OC * l.K + l.M * l.OC)
+
+
+def cpu_baseline(layer, host, repeats=3):
+    """The oracle as it stands, timed on the host cores on the same layer (all three operators)."""
+    import oracle
+    s, p = layer.stride, layer.pad
+    t0 = time.perf_counter()
+    for _ in range(repeats):
+        oracle.conv2d_fwd(host["X"], host["W"], s, p)
+        oracle.conv2d_bwd_data(host["G"], host["W"], (layer.IH, layer.IW), s, p)
+        oracle.conv2d_bwd_weight(host["X"], host["G"], (layer.FH, layer.FW), s, p)
+    dt = time.perf_counter() - t0
+    return {"value": round(3 * layer.flops * repeats / dt / 1e12, 6), "unit": "TFLOP/s",
+            "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "%d x (fwd+bwd_data+bwd_weight) of %s at full size, %.1f s wall"
+                      % (repeats, layer.name, dt)}
+
+
+def table(mc, torch, cfg_names, launches=30, warm=5):
+    rows = []
+    seen = set()
+    log("%-5s %-10s %9s %9s %7s %7s  %s" % ("layer", "op", "ms", "TFLOP/s", "%peak", "GB/s", "plan"))
+    for cfg in cfg_names:
+        for layer in wl.CONFIGS[cfg]:
+            if layer.name in seen:
+                continue
+            seen.add(layer.name)
+            r = LayerRunner(layer, mc, torch, random_fill=True)
+            for op in OPS:
+                ms = r.event_ms(lambda: r.run(op), launches, warm)
+                tf = layer.flops / ms / 1e9
+                pl = r.plans[op]
+                plan = "v%d %dx%d s%d pm%d g%d" % (pl.variant, pl.tile_m, pl.tile_n, pl.split,
+                                                   pl.pos_major, pl.grid)
+                gbs = fwd_bytes(layer) / ms / 1e6
+                rows.append({"layer": layer.name, "op": op, "ms": round(ms, 5), "tflops": round(tf, 2),
+                             "pct_peak": round(100 * tf / PEAK_FP32_MFMA_TFLOPS, 1),
+                             "gbs": round(gbs, 1), "plan": plan})
+                log("%-5s %-10s %9.4f %9.2f %7.1f %7.0f  %s" % (layer.name, op, ms, tf,
+                                                               100 * tf / PEAK_FP32_MFMA_TFLOPS, gbs, plan))
+            del r
+            torch.cuda.empty_cache()
+    return rows
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--table", nargs="*", default=None, metavar="CFG")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures one GPU only (--gpus 1); the hot path has no "
+                 "multi-GPU part, see DESIGN.md for how it would shard")
+
+    import torch
+    import paper_2305_08819_amd as mc
+    mc.load()   # fails loudly if the HIP library is not built
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+
+    if args.table is not None:
+        names = args.table or list(wl.CONFIGS)
+        rows = table(mc, torch, names)
+        print(json.dumps({"table": rows}))
+        return
+
+    layer = {l.name: l for l in wl.all_layers()}[args.workload]
+    r = LayerRunner(layer, mc, torch)
+
+    for _ in range(args.warmup):
+        r.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        r.step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_step = dt * 1e3 / args.steps
+    value = 3 * layer.flops / (ms_step * 1e-3) / 1e12
+
+    # per-operator event timing (each operator alone on the launch stream); the slowest is the
+    # dominant kernel of the step
+    per_op = {op: r.event_ms(lambda op=op: r.run(op), args.steps, args.warmup) for op in OPS}
+    dom = max(per_op, key=per_op.get)
+    achieved = layer.flops / per_op[dom] / 1e9
+    out = {
+        "metric": "TFLOP/s and % FP32 MFMA peak per conv op (fwd/dgrad/wgrad), CIFAR shapes",
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: N=%d %dx%dx%d -> %dx%dx%d, %dx%d filter, stride %d, pad %d, "
+                               "fwd+bwd_data+bwd_weight per step"
+                               % (layer.name, layer.N, layer.IH, layer.IW, layer.IC, layer.OH, layer.OW,
+                                  layer.OC, layer.FH, layer.FW, layer.stride, layer.pad),
+                   "flop_per_step": 3 * layer.flops,
+                   "pct_fp32_mfma_peak": round(100 * value / PEAK_FP32_MFMA_TFLOPS, 2)},
+        "per_op": {op: {"ms": round(per_op[op], 5),
+                        "tflops": round(layer.flops / per_op[op] / 1e9, 2),
+                        "pct_peak": round(100 * layer.flops / per_op[op] / 1e9 / PEAK_FP32_MFMA_TFLOPS, 1),
+                        "split": r.plans[op].split, "tile": [r.plans[op].tile_m, r.plans[op].tile_n]}
+                   for op in OPS},
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2),
+                     "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(layer, r.host)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
