@@ -88,6 +88,11 @@ int conv2d_query_plan(int op, const conv2d_desc *d, conv2d_plan_info *info);
  * allows).  Not thread-safe against concurrent operator calls. */
 int conv2d_set_tuning(int variant, int split);
 
+/* Second process-wide override for sweeps: workgroup tile of the MFMA variants
+ * (tile_m x tile_n must be a compiled pair, 0 x 0 = auto) and the row order
+ * (pos_major = -1 auto, 0 (n,y,x) rows, 1 (y,x,n) rows where the shape allows it). */
+int conv2d_set_tile(int tile_m, int tile_n, int pos_major);
+
 /* Forward convolution (Sec. III Layer-1; Fig. 2 conv3D arguments):
  *   Y[n,oh,ow,oc] = sum_{fh,fw,ic} X[n, oh*sh-ph+fh, ow*sw-pw+fw, ic] * W[oc,fh,fw,ic],
  * X taken as 0 outside the image.  X, W: device, read-only.  Y: device, overwritten.

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_PKG, "libmi355conv.so")
 OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT = 0, 1, 2
 VARIANT_AUTO, VARIANT_DIRECT, VARIANT_MFMA = -1, 0, 1
 
-EXPORTS = ("conv2d_workspace_bytes", "conv2d_query_plan", "conv2d_set_tuning", "conv2d_fwd",
+EXPORTS = ("conv2d_workspace_bytes", "conv2d_query_plan", "conv2d_set_tuning", "conv2d_set_tile", "conv2d_fwd",
            "conv2d_bwd_data", "deconv2d", "conv2d_bwd_weight", "conv2d_status_string",
            "conv2d_last_hip_error")
 
@@ -68,6 +68,8 @@ def load() -> ctypes.CDLL:
         lib.conv2d_query_plan.restype = ctypes.c_int
         lib.conv2d_set_tuning.argtypes = [ctypes.c_int, ctypes.c_int]
         lib.conv2d_set_tuning.restype = ctypes.c_int
+        lib.conv2d_set_tile.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        lib.conv2d_set_tile.restype = ctypes.c_int
         for name in ("conv2d_fwd", "conv2d_bwd_data", "deconv2d", "conv2d_bwd_weight"):
             fn = getattr(lib, name)
             fn.argtypes = [vp, vp, vp, dp, vp, ctypes.c_size_t, vp]
@@ -108,6 +110,12 @@ def conv2d_set_tuning(variant: int = VARIANT_AUTO, split: int = 0) -> None:
     rc = load().conv2d_set_tuning(variant, split)
     if rc != 0:
         raise Mi355ConvError(rc, "conv2d_set_tuning")
+
+
+def conv2d_set_tile(tile_m: int = 0, tile_n: int = 0, pos_major: int = -1) -> None:
+    rc = load().conv2d_set_tile(tile_m, tile_n, pos_major)
+    if rc != 0:
+        raise Mi355ConvError(rc, "conv2d_set_tile")
 
 
 def _ptr(t):

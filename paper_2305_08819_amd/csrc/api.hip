@@ -15,10 +15,10 @@ namespace {
 
 std::atomic<int> g_forceVariant{MI355CONV_VARIANT_AUTO};
 std::atomic<int> g_forceSplit{0};
+std::atomic<int> g_forceBM{0}, g_forceBN{0}, g_forcePosMajor{-1};
 thread_local char t_hipError[256] = "";
 
 constexpr long long kMaxElems = (1LL << 31) - 1;
-constexpr int kTargetWorkgroups = 512;   // 256 CUs x 2 resident workgroups
 constexpr int kSmallMapPixels = 64;      // maps of at most 8x8 outputs use position-major rows
 constexpr int kMaxSplit = 256;
 
@@ -74,31 +74,104 @@ bool offsets_fit_32bit(long long srcElems, const Shape &s, int srcW, int srcC)
     return srcElems + halo < kMaxElems && halo < (1 << 27);
 }
 
-int pick_split(int tiles, int maxSlices)
+// ---- cost model ------------------------------------------------------------------------
+// Picks tile and slice count by a small analytic model instead of fixed thresholds.  Time of
+// a launch = rounds x (stages per workgroup x stage time + fixed per-workgroup cost), where a
+// round is one set of co-resident workgroups on the 256 CUs, plus the reduce pass when the
+// reduction is sliced.  Constants were fitted to sweeps on MI355X; only ratios matter.
+struct TileCand { int bm, bn; double eff; int resident; };
+
+constexpr double kCuFlopPerUs = 157.3e6 / 256.0;   // fp32 MFMA FLOP per microsecond per CU
+constexpr double kFixedUs = 5.0;                   // prologue + epilogue + ramp of one workgroup round
+constexpr double kReduceBytesPerUs = 3.0e6;        // bytes per microsecond the reduce pass streams (3 TB/s)
+constexpr size_t kMaxWorkspace = (size_t)1 << 30;
+
+double launch_cost(const TileCand &c, long long tiles, double avgStages, double maxStages, int split,
+                   long long outElems)
 {
-    int split = 1;
-    const int forced = g_forceSplit.load();
-    if (forced > 0) split = forced;
-    else if (tiles < kTargetWorkgroups * 3 / 4) split = ceil_div(kTargetWorkgroups, tiles);
-    if (split > maxSlices) split = maxSlices;
-    if (split > kMaxSplit) split = kMaxSplit;
-    if (split < 1) split = 1;
-    return split;
+    const long long grid = tiles * split;
+    const int cus = 256;
+    long long residentNow = (grid + cus - 1) / cus;
+    if (residentNow > c.resident) residentNow = c.resident;
+    // a lone workgroup on a CU cannot hide its own load latency and barriers
+    const double eff = residentNow >= 2 ? c.eff : c.eff * 0.8;
+    const double stageUs = (double)residentNow * (2.0 * c.bm * c.bn * kBK) / (kCuFlopPerUs * eff);
+    const long long slots = (long long)cus * c.resident;
+    const double rounds = (double)((grid + slots - 1) / slots);
+    const double avgWg = avgStages / split * stageUs + kFixedUs;
+    const double maxWg = maxStages / split * stageUs + kFixedUs;
+    double t = rounds * avgWg;
+    if (maxWg > t) t = maxWg;
+    if (split > 1) t += 3.0 + (2.0 * split + 1.0) * (double)outElems * 4.0 / kReduceBytesPerUs;
+    return t;
 }
 
-void finish_split(Plan &pl, int maxSlices)
+// Best slice count for one candidate; returns the cost.
+double best_split(const TileCand &c, long long tiles, double avgStages, double maxStages, long long outElems,
+                  int *splitOut)
 {
-    pl.split = pick_split(pl.tilesM * pl.tilesN, maxSlices);
+    const int forced = g_forceSplit.load();
+    int maxS = (int)(avgStages / 2.0);              // keep >= 2 stages per slice on average
+    if (maxS > kMaxSplit) maxS = kMaxSplit;
+    const long long wsPerSlice = pad4(outElems) * 4;
+    if ((long long)maxS * wsPerSlice > (long long)kMaxWorkspace) maxS = (int)(kMaxWorkspace / wsPerSlice);
+    if (maxS < 1) maxS = 1;
+    if (forced > 0) {
+        *splitOut = forced < maxS ? forced : maxS;
+        return launch_cost(c, tiles, avgStages, maxStages, *splitOut, outElems);
+    }
+    double best = 1e300;
+    int bestS = 1;
+    for (int sp = 1; sp <= maxS; ++sp) {
+        const double t = launch_cost(c, tiles, avgStages, maxStages, sp, outElems);
+        if (t < best) { best = t; bestS = sp; }
+    }
+    *splitOut = bestS;
+    return best;
+}
+
+void finish_plan(Plan &pl, int split)
+{
+    pl.split = split;
     pl.grid = pl.tilesM * pl.tilesN * pl.split;
     pl.sliceStride = pad4(pl.outElems);
     pl.wsBytes = pl.split > 1 ? (size_t)pl.split * (size_t)pl.sliceStride * sizeof(float) : 0;
 }
 
-int pick_bn(int cols)
+bool tile_compiled(int bm, int bn, bool gather)
 {
-    if (cols <= 32) return 32;
-    if (cols <= 64) return 64;
-    return 128;
+    if (gather) return (bm == 128 && (bn == 128 || bn == 64 || bn == 32)) || (bm == 64 && bn == 64);
+    return (bm == 128 || bm == 64) && (bn == 128 || bn == 64);
+}
+
+const TileCand kGatherTiles[] = {{128, 128, 0.80, 2}, {128, 64, 0.74, 2}, {64, 64, 0.66, 4}, {128, 32, 0.60, 3}};
+const TileCand kWgradTiles[] = {{128, 128, 0.70, 2}, {64, 128, 0.62, 3}, {128, 64, 0.62, 3}, {64, 64, 0.55, 4}};
+
+bool forced_tile(int *bm, int *bn, bool gather)
+{
+    const int fm = g_forceBM.load(), fn = g_forceBN.load();
+    if (fm > 0 && fn > 0 && tile_compiled(fm, fn, gather)) {
+        *bm = fm;
+        *bn = fn;
+        return true;
+    }
+    return false;
+}
+
+int resolve_order(int wanted, bool allowed)
+{
+    const int f = g_forcePosMajor.load();
+    if (f == 0) return 0;
+    if (f == 1) return allowed ? 1 : 0;
+    return wanted && allowed;
+}
+
+// Taps of a padded filter that land inside a map of `in` pixels for output index o.
+int taps_in_range(int o, int stride, int pad, int f, int in)
+{
+    int c = 0;
+    for (int t = 0; t < f; ++t) c += (unsigned)(o * stride - pad + t) < (unsigned)in;
+    return c;
 }
 
 Plan plan_fwd(const Shape &s)
@@ -110,48 +183,60 @@ Plan plan_fwd(const Shape &s)
                           offsets_fit_32bit((long long)s.N * s.IH * s.IW * s.IC, s, s.IW, s.IC);
     if (forced == MI355CONV_VARIANT_DIRECT || !eligible) return pl;
     pl.variant = MI355CONV_VARIANT_MFMA;
-    pl.bn = pick_bn(s.OC);
-    pl.bm = 128;
     const long long M = (long long)s.N * s.OH * s.OW;
-    pl.tilesN = ceil_div(s.OC, pl.bn);
-    if (pl.bn == 128 && (long long)ceil_div(M, 128) * pl.tilesN < kTargetWorkgroups) {
-        pl.bn = 64;   // more, smaller tiles before resorting to reduction slices
-        pl.tilesN = ceil_div(s.OC, pl.bn);
+    const int chunksPerTap = s.IC / kBK;
+    // taps per output position (what a position-major tile walks)
+    double avgTapsPos = 0;
+    int maxTapsPos = 0;
+    for (int oh = 0; oh < s.OH; ++oh)
+        for (int ow = 0; ow < s.OW; ++ow) {
+            const int t = taps_in_range(oh, s.sh, s.ph, s.FH, s.IH) * taps_in_range(ow, s.sw, s.pw, s.FW, s.IW);
+            avgTapsPos += t;
+            if (t > maxTapsPos) maxTapsPos = t;
+        }
+    avgTapsPos /= (double)s.OH * s.OW;
+    const bool smallMap = (s.ph > 0 || s.pw > 0) && s.OH * s.OW <= kSmallMapPixels;
+
+    int fbm = 0, fbn = 0;
+    const bool haveForced = forced_tile(&fbm, &fbn, true);
+    double best = 1e300;
+    for (const TileCand &c0 : kGatherTiles) {
+        TileCand c = c0;
+        if (haveForced) {
+            if (c.bm != fbm || c.bn != fbn) continue;
+        } else {
+            // no column tile wider than needed, and the narrow tile only for narrow outputs
+            if (c.bn > 32 && c.bn / 2 >= s.OC) continue;
+            if (c.bn == 32 && s.OC > 32) continue;
+        }
+        const int posMajor = resolve_order(smallMap, s.N % c.bm == 0);
+        const long long tiles = (long long)ceil_div(M, c.bm) * ceil_div(s.OC, c.bn);
+        const double avgStages = (posMajor ? avgTapsPos : s.FH * s.FW) * chunksPerTap;
+        const double maxStages = (posMajor ? maxTapsPos : s.FH * s.FW) * chunksPerTap;
+        int sp = 1;
+        const double t = best_split(c, tiles, avgStages, maxStages, pl.outElems, &sp);
+        if (t < best) {
+            best = t;
+            pl.bm = c.bm;
+            pl.bn = c.bn;
+            pl.posMajor = posMajor;
+            pl.split = sp;
+        }
     }
-    pl.posMajor = (s.ph > 0 || s.pw > 0) && s.OH * s.OW <= kSmallMapPixels && s.N % pl.bm == 0;
+    pl.tilesN = ceil_div(s.OC, pl.bn);
     pl.tilesM = ceil_div(M, pl.bm);
     pl.nPhases = 1;
     pl.phaseTileStart[0] = 0;
     pl.phaseTileStart[1] = pl.tilesM;
     pl.phaseDH[0] = s.OH;
     pl.phaseDW[0] = s.OW;
-    // a slice should keep at least 4 stages of the shortest tile (>= 1 tap)
-    const int minIters = (s.IC / kBK) * (pl.posMajor ? 4 : s.FH * s.FW);
-    finish_split(pl, minIters >= 8 ? minIters / 4 : 1);
+    finish_plan(pl, pl.split);
     return pl;
 }
 
-Plan plan_bwd_data(const Shape &s)
+// Phase table of backward-data for row tile bm; returns total row tiles.
+int build_phases(const Shape &s, int bm, Plan &pl, double *avgTaps, int *maxTaps)
 {
-    Plan pl;
-    pl.outElems = (long long)s.N * s.IH * s.IW * s.IC;
-    const int forced = g_forceVariant.load();
-    const bool eligible = s.OC % kBK == 0 && s.IC % 4 == 0 && s.FH * s.FW <= kMaxTaps &&
-                          s.sh * s.sw <= kMaxPhases &&
-                          offsets_fit_32bit((long long)s.N * s.OH * s.OW * s.OC, s, s.OW, s.OC) &&
-                          pl.outElems < kMaxElems;
-    if (forced == MI355CONV_VARIANT_DIRECT || !eligible) return pl;
-    pl.variant = MI355CONV_VARIANT_MFMA;
-    pl.bn = pick_bn(s.IC);
-    pl.bm = 128;
-    pl.tilesN = ceil_div(s.IC, pl.bn);
-    const long long Mall = (long long)s.N * s.IH * s.IW;
-    if (pl.bn == 128 && (long long)ceil_div(Mall, 128) * pl.tilesN < kTargetWorkgroups) {
-        pl.bn = 64;
-        pl.tilesN = ceil_div(s.IC, pl.bn);
-    }
-    pl.posMajor = s.sh == 1 && s.sw == 1 && (s.FH > 1 || s.FW > 1) && s.IH * s.IW <= kSmallMapPixels &&
-                  s.N % pl.bm == 0;
     // phases ordered by decreasing tap count so the long tiles are dispatched first
     struct Ph { int ra, rb, taps; };
     Ph ph[kMaxPhases];
@@ -168,7 +253,8 @@ Plan plan_bwd_data(const Shape &s)
             Ph t = ph[j]; ph[j] = ph[j - 1]; ph[j - 1] = t;
         }
     int tiles = 0, k = 0;
-    int minTaps = 1 << 30;
+    double tapTiles = 0;
+    *maxTaps = 0;
     for (int i = 0; i < np; ++i) {
         // destination rows ih with (ih + ph) % sh == ra:  ih = y0, y0 + sh, ...
         const int y0 = ((ph[i].ra - s.ph) % s.sh + s.sh) % s.sh;
@@ -183,16 +269,83 @@ Plan plan_bwd_data(const Shape &s)
         pl.phaseDH[k] = dh;
         pl.phaseDW[k] = dw;
         pl.phaseTileStart[k] = tiles;
-        tiles += ceil_div((long long)s.N * dh * dw, pl.bm);
-        if (ph[i].taps > 0 && ph[i].taps < minTaps) minTaps = ph[i].taps;
+        const int t = ceil_div((long long)s.N * dh * dw, bm);
+        tiles += t;
+        tapTiles += (double)t * ph[i].taps;
+        if (ph[i].taps > *maxTaps) *maxTaps = ph[i].taps;
         ++k;
     }
     pl.phaseTileStart[k] = tiles;
     pl.nPhases = k;
-    pl.tilesM = tiles;
-    if (minTaps == (1 << 30)) minTaps = 1;
-    const int minIters = (s.OC / kBK) * (pl.posMajor ? (minTaps < 4 ? minTaps : 4) : minTaps);
-    finish_split(pl, minIters >= 8 ? minIters / 4 : 1);
+    *avgTaps = tiles ? tapTiles / tiles : 0;
+    return tiles;
+}
+
+Plan plan_bwd_data(const Shape &s)
+{
+    Plan pl;
+    pl.outElems = (long long)s.N * s.IH * s.IW * s.IC;
+    const int forced = g_forceVariant.load();
+    const bool eligible = s.OC % kBK == 0 && s.IC % 4 == 0 && s.FH * s.FW <= kMaxTaps &&
+                          s.sh * s.sw <= kMaxPhases &&
+                          offsets_fit_32bit((long long)s.N * s.OH * s.OW * s.OC, s, s.OW, s.OC) &&
+                          pl.outElems < kMaxElems;
+    if (forced == MI355CONV_VARIANT_DIRECT || !eligible) return pl;
+    pl.variant = MI355CONV_VARIANT_MFMA;
+    const int chunksPerTap = s.OC / kBK;
+    const bool unitStride = s.sh == 1 && s.sw == 1;
+    // stride 1: taps reaching input position (ih, iw) = taps of the flipped filter with pad F-1-p
+    double avgTapsPos = 0;
+    int maxTapsPos = 0;
+    if (unitStride) {
+        for (int ih = 0; ih < s.IH; ++ih)
+            for (int iw = 0; iw < s.IW; ++iw) {
+                int th = 0, tw = 0;
+                for (int fh = 0; fh < s.FH; ++fh) th += (unsigned)(ih + s.ph - fh) < (unsigned)s.OH;
+                for (int fw = 0; fw < s.FW; ++fw) tw += (unsigned)(iw + s.pw - fw) < (unsigned)s.OW;
+                avgTapsPos += th * tw;
+                if (th * tw > maxTapsPos) maxTapsPos = th * tw;
+            }
+        avgTapsPos /= (double)s.IH * s.IW;
+    }
+    const bool smallMap = unitStride && (s.FH > 1 || s.FW > 1) && s.IH * s.IW <= kSmallMapPixels;
+
+    int fbm = 0, fbn = 0;
+    const bool haveForced = forced_tile(&fbm, &fbn, true);
+    double best = 1e300;
+    for (const TileCand &c0 : kGatherTiles) {
+        TileCand c = c0;
+        if (haveForced) {
+            if (c.bm != fbm || c.bn != fbn) continue;
+        } else {
+            if (c.bn > 32 && c.bn / 2 >= s.IC) continue;
+            if (c.bn == 32 && s.IC > 32) continue;
+        }
+        Plan trial = pl;
+        double avgTaps = 0;
+        int maxTaps = 0;
+        const int tilesM = build_phases(s, c.bm, trial, &avgTaps, &maxTaps);
+        const int posMajor = resolve_order(smallMap, s.N % c.bm == 0);
+        if (posMajor) {
+            avgTaps = avgTapsPos;
+            maxTaps = maxTapsPos;
+        }
+        const long long tiles = (long long)tilesM * ceil_div(s.IC, c.bn);
+        int sp = 1;
+        const double t = best_split(c, tiles, avgTaps * chunksPerTap, (double)maxTaps * chunksPerTap,
+                                    pl.outElems, &sp);
+        if (t < best) {
+            best = t;
+            trial.bm = c.bm;
+            trial.bn = c.bn;
+            trial.posMajor = posMajor;
+            trial.split = sp;
+            trial.tilesM = tilesM;
+            trial.tilesN = ceil_div(s.IC, c.bn);
+            pl = trial;
+        }
+    }
+    finish_plan(pl, pl.split);
     return pl;
 }
 
@@ -207,14 +360,43 @@ Plan plan_bwd_weight(const Shape &s)
     if (forced == MI355CONV_VARIANT_DIRECT || !eligible) return pl;
     pl.variant = MI355CONV_VARIANT_MFMA;
     const long long Ktot = (long long)s.FH * s.FW * s.IC;
-    pl.bm = s.OC <= 64 ? 64 : 128;
-    pl.bn = Ktot <= 64 ? 64 : 128;
+    const int chunks = ceil_div(M, kBK);
+    const bool smallMap = (s.ph > 0 || s.pw > 0) && s.OH * s.OW <= kSmallMapPixels;
+    const int posMajor = resolve_order(smallMap, s.N % kBK == 0);
+    // fraction of (position, tap) pairs inside the image = share of stages a tile keeps
+    double live = 1.0;
+    if (posMajor) {
+        double inside = 0;
+        for (int oh = 0; oh < s.OH; ++oh)
+            for (int ow = 0; ow < s.OW; ++ow)
+                inside += taps_in_range(oh, s.sh, s.ph, s.FH, s.IH) * taps_in_range(ow, s.sw, s.pw, s.FW, s.IW);
+        live = inside / ((double)s.OH * s.OW * s.FH * s.FW);
+    }
+    int fbm = 0, fbn = 0;
+    const bool haveForced = forced_tile(&fbm, &fbn, false);
+    double best = 1e300;
+    for (const TileCand &c : kWgradTiles) {
+        if (haveForced) {
+            if (c.bm != fbm || c.bn != fbn) continue;
+        } else {
+            if (c.bm > 64 && c.bm / 2 >= s.OC) continue;
+            if (c.bn > 64 && c.bn / 2 >= Ktot) continue;
+        }
+        const long long tiles = (long long)ceil_div(s.OC, c.bm) * ceil_div(Ktot, c.bn);
+        int sp = 1;
+        const double t = best_split(c, tiles, chunks * live, (double)chunks, pl.outElems, &sp);
+        if (t < best) {
+            best = t;
+            pl.bm = c.bm;
+            pl.bn = c.bn;
+            pl.split = sp;
+        }
+    }
+    pl.posMajor = posMajor;
     pl.tilesM = ceil_div(s.OC, pl.bm);
     pl.tilesN = ceil_div(Ktot, pl.bn);
-    pl.posMajor = (s.ph > 0 || s.pw > 0) && s.OH * s.OW <= kSmallMapPixels && s.N % kBK == 0;
-    const int chunks = ceil_div(M, kBK);
     pl.flushChunks = 16;   // 512-product chains
-    finish_split(pl, chunks >= 8 ? chunks / 4 : 1);
+    finish_plan(pl, pl.split);
     return pl;
 }
 
@@ -253,6 +435,7 @@ void fill_gather_params(GatherGemmParams &g, const Plan &pl)
     g.split = pl.split;
     g.sliceStride = pl.sliceStride;
     g.tilesN = pl.tilesN;
+    g.xcdUnit = pl.tilesN * pl.split * 2;   // both column tiles, all slices, two neighbouring row tiles
     g.nPhases = pl.nPhases;
     for (int i = 0; i <= kMaxPhases; ++i) g.phaseTileStart[i] = pl.phaseTileStart[i];
     for (int i = 0; i < kMaxPhases; ++i) {
@@ -333,6 +516,18 @@ int conv2d_set_tuning(int variant, int split)
     return MI355CONV_OK;
 }
 
+int conv2d_set_tile(int tile_m, int tile_n, int pos_major)
+{
+    if (tile_m < 0 || tile_n < 0 || pos_major < -1 || pos_major > 1 || (tile_m == 0) != (tile_n == 0))
+        return MI355CONV_ERR_UNSUPPORTED;
+    if (tile_m && !tile_compiled(tile_m, tile_n, true) && !tile_compiled(tile_m, tile_n, false))
+        return MI355CONV_ERR_UNSUPPORTED;
+    g_forceBM.store(tile_m);
+    g_forceBN.store(tile_n);
+    g_forcePosMajor.store(pos_major);
+    return MI355CONV_OK;
+}
+
 int conv2d_fwd(const float *X, const float *W, float *Y, const conv2d_desc *d, void *ws, size_t ws_bytes,
                void *stream)
 {
@@ -401,6 +596,7 @@ int conv2d_bwd_weight(const float *X, const float *dY, float *dW, const conv2d_d
     w.split = pl.split;
     w.sliceStride = pl.sliceStride;
     w.tilesN = pl.tilesN;
+    w.xcdUnit = pl.tilesN;   // the column tiles of one slice read the same G and X rows
     w.M = s.N * s.OH * s.OW;
     w.flushChunks = pl.flushChunks;
     hipError_t e = launch_wgrad(w, pl.bm, pl.bn, pl.grid, st);

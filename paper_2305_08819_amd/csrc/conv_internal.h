@@ -36,6 +36,7 @@ struct GatherGemmParams {
     int split;            // reduction slices
     long long sliceStride;// elements between consecutive partial outputs in the workspace
     int tilesN;
+    int xcdUnit;          // consecutive logical workgroup ids kept on one XCD
     int nPhases;
     int phaseTileStart[kMaxPhases + 1];
     // per phase: residues, first destination row/col, destination rows/cols in the phase
@@ -57,9 +58,25 @@ struct WgradParams {
     int split;
     long long sliceStride;
     int tilesN;           // tiles along the K' = FH*FW*IC axis
+    int xcdUnit;          // consecutive logical workgroup ids kept on one XCD
     int M;                // N*OH*OW
     int flushChunks;      // fold the running accumulator into a second one every this many stages
 };
+
+// MI355X spreads consecutive workgroup ids round-robin over its 8 XCDs, each with its own
+// L2.  Map the hardware id to a logical id so that `unit` consecutive logical ids (workgroups
+// that share operand tiles) run on one XCD, while units are still dealt round-robin so every
+// XCD gets the same mix of long and short tiles.  Ids past the last whole group of 8 units
+// keep their value.  A bijection on [0, grid).
+__device__ __forceinline__ int xcd_remap(int bid, int grid, int unit)
+{
+    constexpr int kXcds = 8;
+    const int span = kXcds * unit;
+    const int whole = (grid / span) * span;
+    if (bid >= whole) return bid;
+    const int x = bid % kXcds, q = bid / kXcds;
+    return ((q / unit) * kXcds + x) * unit + q % unit;
+}
 
 hipError_t launch_direct_fwd(const float *X, const float *W, float *Y, const Shape &s, hipStream_t st);
 hipError_t launch_direct_bwd_data(const float *G, const float *W, float *dX, const Shape &s, hipStream_t st);

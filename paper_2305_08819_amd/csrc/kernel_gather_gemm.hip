@@ -28,6 +28,7 @@
 namespace mi355conv {
 
 typedef float float16v __attribute__((ext_vector_type(16)));
+typedef float f4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers
 
 namespace {
 
@@ -61,7 +62,7 @@ template <int BM, int BN, int WAVES_M, bool BWD>
 __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGemmParams p)
 {
     using T = GG<BM, BN, WAVES_M, BWD>;
-    extern __shared__ float4 smem_raw[];
+    extern __shared__ f4 smem_raw[];
     float *smem = reinterpret_cast<float *>(smem_raw);
     float *As = smem;
     float *Bs = As + 2 * T::A_STAGE;
@@ -76,7 +77,7 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     const int wave = tid >> 6;
 
     // ---- which tile / slice / phase --------------------------------------------------
-    int bid = blockIdx.x;
+    int bid = xcd_remap(blockIdx.x, gridDim.x, p.xcdUnit);
     const int tn = bid % p.tilesN;
     bid /= p.tilesN;
     const int slice = bid % p.split;
@@ -192,7 +193,7 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     int dy = 0, dx = 0, tapOffA = 0, tapOffB = 0;
     unsigned aValid = 0u;
 
-    auto set_tap = [&]() {
+    auto set_tap = [&]() __attribute__((always_inline)) {
         const int t = __ffsll((long long)rem) - 1;
         const int fh = t / p.FW, fw = t - fh * p.FW;
         if (BWD) {
@@ -212,16 +213,16 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
                 aValid |= 1u << i;
     };
 
-    float4 ga[T::PA], gb[T::PB];
-    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    f4 ga[T::PA], gb[T::PB];
+    const f4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
-    auto gload = [&]() {
+    auto gload = [&]() __attribute__((always_inline)) {
         const int c0 = chunk * kBK;
 #pragma unroll
         for (int i = 0; i < T::PA; ++i) {
             ga[i] = zero4;
             if (aValid & (1u << i))
-                ga[i] = *reinterpret_cast<const float4 *>(p.A + (long long)(rBase[i] + tapOffA + c0));
+                ga[i] = *reinterpret_cast<const f4 *>(p.A + (long long)(rBase[i] + tapOffA + c0));
         }
 #pragma unroll
         for (int i = 0; i < T::PB; ++i) {
@@ -230,18 +231,18 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
             if (BWD) {
                 const int col = n0 + bSeg * 4;
                 if (r < kBK && col < p.DC)
-                    gb[i] = *reinterpret_cast<const float4 *>(p.B + (long long)(c0 + r) * wRowStride +
+                    gb[i] = *reinterpret_cast<const f4 *>(p.B + (long long)(c0 + r) * wRowStride +
                                                               tapOffB + col);
             } else {
                 const int col = n0 + r;
                 if (r < BN && col < p.DC)
-                    gb[i] = *reinterpret_cast<const float4 *>(p.B + (long long)col * wRowStride +
+                    gb[i] = *reinterpret_cast<const f4 *>(p.B + (long long)col * wRowStride +
                                                               tapOffB + c0 + bSeg * 4);
             }
         }
     };
 
-    auto advance = [&]() {
+    auto advance = [&]() __attribute__((always_inline)) {
         if (++chunk == chunksPerTap) {
             chunk = 0;
             rem &= rem - 1;
@@ -249,16 +250,16 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
         }
     };
 
-    auto lds_store = [&](int buf) {
+    auto lds_store = [&](int buf) __attribute__((always_inline)) {
         float *a = As + buf * T::A_STAGE;
         float *b = Bs + buf * T::B_STAGE;
 #pragma unroll
         for (int i = 0; i < T::PA; ++i)
-            *reinterpret_cast<float4 *>(a + (aRow + 32 * i) * LDA + aSeg * 4) = ga[i];
+            *reinterpret_cast<f4 *>(a + (aRow + 32 * i) * LDA + aSeg * 4) = ga[i];
 #pragma unroll
         for (int i = 0; i < T::PB; ++i) {
             const int r = bRow + T::B_RPP * i;
-            if (r < T::B_ROWS) *reinterpret_cast<float4 *>(b + r * T::LDB + bSeg * 4) = gb[i];
+            if (r < T::B_ROWS) *reinterpret_cast<f4 *>(b + r * T::LDB + bSeg * 4) = gb[i];
         }
     };
 
@@ -274,23 +275,23 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     const int wm = wave / T::WAVES_N, wn = wave % T::WAVES_N;
     const int l32 = lane & 31, lh = lane >> 5;
 
-    auto compute = [&](int buf) {
+    auto compute = [&](int buf) __attribute__((always_inline)) {
         const float *a = As + buf * T::A_STAGE + (wm * T::WTM + l32) * LDA + lh * 4;
         const float *b = BWD ? Bs + buf * T::B_STAGE + (lh * 4) * T::LDB + wn * T::WTN + l32
                              : Bs + buf * T::B_STAGE + (wn * T::WTN + l32) * T::LDB + lh * 4;
 #pragma unroll
         for (int jj = 0; jj < kBK / 8; ++jj) {
-            float4 fa[T::MB], fb[T::NB];
+            f4 fa[T::MB], fb[T::NB];
 #pragma unroll
             for (int i = 0; i < T::MB; ++i)
-                fa[i] = *reinterpret_cast<const float4 *>(a + i * 32 * LDA + jj * 8);
+                fa[i] = *reinterpret_cast<const f4 *>(a + i * 32 * LDA + jj * 8);
 #pragma unroll
             for (int j = 0; j < T::NB; ++j) {
                 if (BWD) {
                     const float *q = b + (jj * 8) * T::LDB + j * 32;
-                    fb[j] = make_float4(q[0], q[T::LDB], q[2 * T::LDB], q[3 * T::LDB]);
+                    fb[j] = f4{q[0], q[T::LDB], q[2 * T::LDB], q[3 * T::LDB]};
                 } else {
-                    fb[j] = *reinterpret_cast<const float4 *>(b + j * 32 * T::LDB + jj * 8);
+                    fb[j] = *reinterpret_cast<const f4 *>(b + j * 32 * T::LDB + jj * 8);
                 }
             }
 #pragma unroll
@@ -299,9 +300,7 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
                 for (int i = 0; i < T::MB; ++i)
 #pragma unroll
                     for (int j = 0; j < T::NB; ++j) {
-                        const float av = t == 0 ? fa[i].x : t == 1 ? fa[i].y : t == 2 ? fa[i].z : fa[i].w;
-                        const float bv = t == 0 ? fb[j].x : t == 1 ? fb[j].y : t == 2 ? fb[j].z : fb[j].w;
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t], fb[j][t], acc[i][j], 0, 0, 0);
                     }
             }
         }

@@ -21,6 +21,7 @@
 namespace mi355conv {
 
 typedef float float16v __attribute__((ext_vector_type(16)));
+typedef float f4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers
 
 namespace {
 template <int BM, int BN>
@@ -39,12 +40,12 @@ template <int BM, int BN>
 __global__ __launch_bounds__(kThreads, 2) void wgrad_kernel(const WgradParams p)
 {
     using T = WG<BM, BN>;
-    extern __shared__ float4 smem_raw[];
+    extern __shared__ f4 smem_raw[];
     float *Gs = reinterpret_cast<float *>(smem_raw);
     float *Xs = Gs + 2 * T::G_STAGE;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int bid = blockIdx.x;
+    int bid = xcd_remap(blockIdx.x, gridDim.x, p.xcdUnit);
     const int tn = bid % p.tilesN;
     bid /= p.tilesN;
     const int slice = bid % p.split;
@@ -73,7 +74,7 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_kernel(const WgradParams p)
     const int lastCol = (col0 + BN - 1 < Ktot - 1) ? col0 + BN - 1 : Ktot - 1;
     const int tapHi = lastCol / p.IC;
 
-    auto stage_live = [&](int ch) -> bool {
+    auto stage_live = [&](int ch) __attribute__((always_inline)) -> bool {
         if (!p.posMajor) return true;
         const int pos = (ch * kBK) / p.N;   // all kBK rows of the stage share this position
         const int oh = pos / p.OW, ow = pos - oh * p.OW;
@@ -85,60 +86,89 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_kernel(const WgradParams p)
         }
         return false;
     };
-    auto next_live = [&](int ch) -> int {
+    auto next_live = [&](int ch) __attribute__((always_inline)) -> int {
         while (ch < ch1 && !stage_live(ch)) ++ch;
         return ch;
     };
 
-    float4 gg[T::PG], gx[T::PX];
-    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    f4 gg[T::PG], gx[T::PX];
+    const f4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
-    auto gload = [&](int ch) {
-#pragma unroll
-        for (int i = 0; i < T::PG; ++i) {
-            gg[i] = zero4;
-            const int m = ch * kBK + gRow + T::G_RPP * i;
-            if (gOk && m < p.M) {
-                int pix = m;
-                if (p.posMajor) {
-                    const int pos = m / p.N, n = m - pos * p.N;
-                    pix = n * ohow + pos;
-                }
-                gg[i] = *reinterpret_cast<const float4 *>(p.G + (long long)pix * p.OC + gOc);
-            }
-        }
+    // (n, oh, ow) of this thread's X rows.  With (n,oh,ow) row order consecutive stages are
+    // kBK rows apart, so the triple advances by a fixed (dn, dh, dw) with at most one carry
+    // per digit and no division in the loop.
+    int rn[T::PX], rh[T::PX], rw[T::PX];
+    const int stepN = kBK / ohow, stepRem = kBK - stepN * ohow;
+    const int stepH = stepRem / p.OW, stepW = stepRem - stepH * p.OW;
+    auto seek_rows = [&](int ch) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < T::PX; ++i) {
-            gx[i] = zero4;
             const int m = ch * kBK + xRow + T::X_RPP * i;
-            if (xOk && m < p.M) {
-                int n, oh, ow;
-                if (p.posMajor) {
-                    const int pos = m / p.N;
-                    n = m - pos * p.N;
-                    oh = pos / p.OW;
-                    ow = pos - oh * p.OW;
-                } else {
-                    n = m / ohow;
-                    const int r = m - n * ohow;
-                    oh = r / p.OW;
-                    ow = r - oh * p.OW;
-                }
-                const int ih = oh * p.sh - p.ph + xFh, iw = ow * p.sw - p.pw + xFw;
-                if ((unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW)
-                    gx[i] = *reinterpret_cast<const float4 *>(
-                        p.X + ((long long)(n * p.IH + ih) * p.IW + iw) * p.IC + xIc);
-            }
+            rn[i] = m / ohow;
+            const int r = m - rn[i] * ohow;
+            rh[i] = r / p.OW;
+            rw[i] = r - rh[i] * p.OW;
         }
     };
-    auto lds_store = [&](int buf) {
+    auto step_rows = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < T::PX; ++i) {
+            rw[i] += stepW;
+            rh[i] += stepH;
+            rn[i] += stepN;
+            if (rw[i] >= p.OW) { rw[i] -= p.OW; ++rh[i]; }
+            if (rh[i] >= p.OH) { rh[i] -= p.OH; ++rn[i]; }
+        }
+    };
+
+    auto gload = [&](int ch) __attribute__((always_inline)) {
+        if (p.posMajor) {
+            // a stage sits on one output position; rows differ only in n
+            const int m0 = ch * kBK;
+            const int pos = m0 / p.N, nb = m0 - pos * p.N;
+            const int oh = pos / p.OW, ow = pos - oh * p.OW;
+            const int ih = oh * p.sh - p.ph + xFh, iw = ow * p.sw - p.pw + xFw;
+            const bool live = xOk && (unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW;
+#pragma unroll
+            for (int i = 0; i < T::PG; ++i) {
+                gg[i] = zero4;
+                const int n = nb + gRow + T::G_RPP * i;
+                if (gOk) gg[i] = *reinterpret_cast<const f4 *>(p.G + ((long long)n * ohow + pos) * p.OC + gOc);
+            }
+#pragma unroll
+            for (int i = 0; i < T::PX; ++i) {
+                gx[i] = zero4;
+                const int n = nb + xRow + T::X_RPP * i;
+                if (live)
+                    gx[i] = *reinterpret_cast<const f4 *>(
+                        p.X + ((long long)(n * p.IH + ih) * p.IW + iw) * p.IC + xIc);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < T::PG; ++i) {
+                gg[i] = zero4;
+                const int m = ch * kBK + gRow + T::G_RPP * i;
+                if (gOk && m < p.M) gg[i] = *reinterpret_cast<const f4 *>(p.G + (long long)m * p.OC + gOc);
+            }
+#pragma unroll
+            for (int i = 0; i < T::PX; ++i) {
+                gx[i] = zero4;
+                const int ih = rh[i] * p.sh - p.ph + xFh, iw = rw[i] * p.sw - p.pw + xFw;
+                if (xOk && rn[i] < p.N && (unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW)
+                    gx[i] = *reinterpret_cast<const f4 *>(
+                        p.X + ((long long)(rn[i] * p.IH + ih) * p.IW + iw) * p.IC + xIc);
+            }
+            step_rows();
+        }
+    };
+    auto lds_store = [&](int buf) __attribute__((always_inline)) {
         float *g = Gs + buf * T::G_STAGE, *x = Xs + buf * T::X_STAGE;
 #pragma unroll
         for (int i = 0; i < T::PG; ++i)
-            *reinterpret_cast<float4 *>(g + (gRow + T::G_RPP * i) * T::LDG + gSeg * 4) = gg[i];
+            *reinterpret_cast<f4 *>(g + (gRow + T::G_RPP * i) * T::LDG + gSeg * 4) = gg[i];
 #pragma unroll
         for (int i = 0; i < T::PX; ++i)
-            *reinterpret_cast<float4 *>(x + (xRow + T::X_RPP * i) * T::LDX + xSeg * 4) = gx[i];
+            *reinterpret_cast<f4 *>(x + (xRow + T::X_RPP * i) * T::LDX + xSeg * 4) = gx[i];
     };
 
     float16v acc[T::MB][T::NB], acc2[T::MB][T::NB];
@@ -155,7 +185,7 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_kernel(const WgradParams p)
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
 
-    auto compute = [&](int buf) {
+    auto compute = [&](int buf) __attribute__((always_inline)) {
         const float *g = Gs + buf * T::G_STAGE + (lh * 4) * T::LDG + wm * T::WTM + l32;
         const float *x = Xs + buf * T::X_STAGE + (lh * 4) * T::LDX + wn * T::WTN + l32;
 #pragma unroll
@@ -178,7 +208,7 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_kernel(const WgradParams p)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t], fb[j][t], acc[i][j], 0, 0, 0);
         }
     };
-    auto flush = [&]() {
+    auto flush = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < T::MB; ++i)
 #pragma unroll
@@ -192,6 +222,7 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_kernel(const WgradParams p)
 
     int cur = next_live(ch0);
     if (cur < ch1) {
+        if (!p.posMajor) seek_rows(cur);
         gload(cur);
         lds_store(0);
         __syncthreads();

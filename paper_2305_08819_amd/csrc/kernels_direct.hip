@@ -110,31 +110,53 @@ __global__ __launch_bounds__(256) void direct_bwd_weight_kernel(const float *__r
     if (threadIdx.x == 0) dW[e] = red[0];
 }
 
-// out[i] = sum_s ws[s*stride + i].  The partials are fp32; they are added in slice order in
-// fp64 and rounded once, so the result is reproducible and the combine step adds no error
-// of its own beyond the final rounding.
+// out[i] = sum_s ws[s*stride + i].  The partials are fp32; they are added in fp64 in a fixed
+// order and rounded once, so the result is reproducible and the combine step adds no error of
+// its own beyond the final rounding.  A workgroup owns 256/G float4 columns; G thread groups
+// each add every G-th slice, then group 0 adds the G group sums in group order through LDS.
+template <int G>
 __global__ __launch_bounds__(256) void slice_reduce_kernel(const float *__restrict__ ws,
                                                            float *__restrict__ out,
-                                                           long long count4, long long count,
-                                                           int split, long long stride)
+                                                           long long count4, int split, long long stride4)
 {
-    long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    constexpr int COLS = 256 / G;
+    __shared__ double red[G > 1 ? (G - 1) * COLS * 4 : 1];
+    const int c = threadIdx.x % COLS, g = threadIdx.x / COLS;
+    const long long i = (long long)blockIdx.x * COLS + c;
+    double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
     if (i < count4) {
-        double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
         const float4 *p = reinterpret_cast<const float4 *>(ws) + i;
-        long long stride4 = stride >> 2;
-        for (int s = 0; s < split; ++s) {
-            float4 v = p[s * stride4];
+        for (int s = g; s < split; s += G) {
+            const float4 v = p[s * stride4];
             a0 += v.x; a1 += v.y; a2 += v.z; a3 += v.w;
         }
-        reinterpret_cast<float4 *>(out)[i] = make_float4((float)a0, (float)a1, (float)a2, (float)a3);
-    } else {
-        long long j = count4 * 4 + (i - count4);   // scalar tail
-        if (j < count) {
-            double a = 0;
-            for (int s = 0; s < split; ++s) a += ws[s * stride + j];
-            out[j] = (float)a;
+    }
+    if (G > 1) {
+        if (g > 0) {
+            double *r = red + ((g - 1) * COLS + c) * 4;
+            r[0] = a0; r[1] = a1; r[2] = a2; r[3] = a3;
         }
+        __syncthreads();
+        if (g == 0) {
+            for (int k = 1; k < G; ++k) {
+                const double *r = red + ((k - 1) * COLS + c) * 4;
+                a0 += r[0]; a1 += r[1]; a2 += r[2]; a3 += r[3];
+            }
+        }
+    }
+    if (g == 0 && i < count4)
+        reinterpret_cast<float4 *>(out)[i] = make_float4((float)a0, (float)a1, (float)a2, (float)a3);
+}
+
+// scalar tail (count % 4 elements) of the reduce
+__global__ void slice_reduce_tail_kernel(const float *__restrict__ ws, float *__restrict__ out,
+                                         long long first, long long count, int split, long long stride)
+{
+    const long long j = first + threadIdx.x;
+    if (j < count) {
+        double a = 0;
+        for (int s = 0; s < split; ++s) a += ws[s * stride + j];
+        out[j] = (float)a;
     }
 }
 
@@ -165,10 +187,26 @@ hipError_t launch_slice_reduce(const float *ws, float *out, long long count, int
                                long long stride, hipStream_t st)
 {
     // stride is a multiple of 4 (the host pads it), so float4 loads of every slice are aligned
-    long long count4 = count >> 2;
-    long long threads = count4 + (count - count4 * 4);
-    hipLaunchKernelGGL(slice_reduce_kernel, dim3(blocks_for(threads)), dim3(256), 0, st, ws, out,
-                       count4, count, split, stride);
+    const long long count4 = count >> 2;
+    if (count4 > 0) {
+        // more thread groups per column when there are few columns and many slices
+        int G = 1;
+        while (G < 16 && G * 2 <= split && count4 * G < (1 << 17)) G *= 2;
+        const long long cols = 256 / G;
+        const unsigned grid = (unsigned)((count4 + cols - 1) / cols);
+        const long long stride4 = stride >> 2;
+        switch (G) {
+        case 1: hipLaunchKernelGGL(slice_reduce_kernel<1>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4); break;
+        case 2: hipLaunchKernelGGL(slice_reduce_kernel<2>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4); break;
+        case 4: hipLaunchKernelGGL(slice_reduce_kernel<4>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4); break;
+        case 8: hipLaunchKernelGGL(slice_reduce_kernel<8>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4); break;
+        default: hipLaunchKernelGGL(slice_reduce_kernel<16>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4); break;
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (count4 * 4 < count)
+        hipLaunchKernelGGL(slice_reduce_tail_kernel, dim3(1), dim3(4), 0, st, ws, out, count4 * 4, count, split, stride);
     return hipGetLastError();
 }
 
