@@ -81,34 +81,46 @@ bool offsets_fit_32bit(long long srcElems, const Shape &s, int srcW, int srcC)
 // reduction is sliced.  Constants were fitted to sweeps on MI355X; only ratios matter.
 struct TileCand { int bm, bn; double eff; int resident; };
 
+// Constants of the model, fitted by least squares to tile x split x row-order sweeps of the
+// benchmark layers on MI355X (separately for the gather-GEMM and the backward-weight kernel).
+struct CostParams {
+    double loneEff;        // efficiency factor when a workgroup has a CU to itself
+    double fixedUs;        // prologue + epilogue + ramp of one round of workgroups
+    double reduceUs;       // launch + ramp of the slice-reduce kernel
+    double reduceBytesPerUs;
+};
+constexpr CostParams kGatherCost = {0.55, 8.8, 5.4, 9.9e6};
+constexpr CostParams kWgradCost = {0.70, 1.0, 10.0, 8.6e6};
+
 constexpr double kCuFlopPerUs = 157.3e6 / 256.0;   // fp32 MFMA FLOP per microsecond per CU
-constexpr double kFixedUs = 5.0;                   // prologue + epilogue + ramp of one workgroup round
-constexpr double kReduceBytesPerUs = 3.0e6;        // bytes per microsecond the reduce pass streams (3 TB/s)
 constexpr size_t kMaxWorkspace = (size_t)1 << 30;
 
-double launch_cost(const TileCand &c, long long tiles, double avgStages, double maxStages, int split,
-                   long long outElems)
+double launch_cost(const CostParams &k, const TileCand &c, long long tiles, double avgStages, double maxStages,
+                   int split, long long outElems)
 {
     const long long grid = tiles * split;
     const int cus = 256;
     long long residentNow = (grid + cus - 1) / cus;
     if (residentNow > c.resident) residentNow = c.resident;
     // a lone workgroup on a CU cannot hide its own load latency and barriers
-    const double eff = residentNow >= 2 ? c.eff : c.eff * 0.8;
+    const double eff = residentNow >= 2 ? c.eff : c.eff * k.loneEff;
     const double stageUs = (double)residentNow * (2.0 * c.bm * c.bn * kBK) / (kCuFlopPerUs * eff);
     const long long slots = (long long)cus * c.resident;
     const double rounds = (double)((grid + slots - 1) / slots);
-    const double avgWg = avgStages / split * stageUs + kFixedUs;
-    const double maxWg = maxStages / split * stageUs + kFixedUs;
+    const double avgWg = avgStages / split * stageUs + k.fixedUs;
+    const double maxWg = maxStages / split * stageUs + k.fixedUs;
+    // one round lasts as long as its longest workgroup, but co-resident short ones free the
+    // matrix pipe early: take the middle between the longest and the average
     double t = rounds * avgWg;
-    if (maxWg > t) t = maxWg;
-    if (split > 1) t += 3.0 + (2.0 * split + 1.0) * (double)outElems * 4.0 / kReduceBytesPerUs;
+    const double longest = 0.5 * (maxWg + avgWg);
+    if (longest > t) t = longest;
+    if (split > 1) t += k.reduceUs + (2.0 * split + 1.0) * (double)outElems * 4.0 / k.reduceBytesPerUs;
     return t;
 }
 
 // Best slice count for one candidate; returns the cost.
-double best_split(const TileCand &c, long long tiles, double avgStages, double maxStages, long long outElems,
-                  int *splitOut)
+double best_split(const CostParams &k, const TileCand &c, long long tiles, double avgStages, double maxStages,
+                  long long outElems, int *splitOut)
 {
     const int forced = g_forceSplit.load();
     int maxS = (int)(avgStages / 2.0);              // keep >= 2 stages per slice on average
@@ -118,12 +130,12 @@ double best_split(const TileCand &c, long long tiles, double avgStages, double m
     if (maxS < 1) maxS = 1;
     if (forced > 0) {
         *splitOut = forced < maxS ? forced : maxS;
-        return launch_cost(c, tiles, avgStages, maxStages, *splitOut, outElems);
+        return launch_cost(k, c, tiles, avgStages, maxStages, *splitOut, outElems);
     }
     double best = 1e300;
     int bestS = 1;
     for (int sp = 1; sp <= maxS; ++sp) {
-        const double t = launch_cost(c, tiles, avgStages, maxStages, sp, outElems);
+        const double t = launch_cost(k, c, tiles, avgStages, maxStages, sp, outElems);
         if (t < best) { best = t; bestS = sp; }
     }
     *splitOut = bestS;
@@ -144,8 +156,8 @@ bool tile_compiled(int bm, int bn, bool gather)
     return (bm == 128 || bm == 64) && (bn == 128 || bn == 64);
 }
 
-const TileCand kGatherTiles[] = {{128, 128, 0.80, 2}, {128, 64, 0.74, 2}, {64, 64, 0.66, 4}, {128, 32, 0.60, 3}};
-const TileCand kWgradTiles[] = {{128, 128, 0.70, 2}, {64, 128, 0.62, 3}, {128, 64, 0.62, 3}, {64, 64, 0.55, 4}};
+const TileCand kGatherTiles[] = {{128, 128, 0.77, 2}, {128, 64, 0.76, 2}, {64, 64, 0.79, 4}, {128, 32, 0.60, 3}};
+const TileCand kWgradTiles[] = {{128, 128, 0.79, 2}, {64, 128, 0.68, 2}, {128, 64, 0.70, 2}, {64, 64, 0.60, 5}};
 
 bool forced_tile(int *bm, int *bn, bool gather)
 {
@@ -195,7 +207,8 @@ Plan plan_fwd(const Shape &s)
             if (t > maxTapsPos) maxTapsPos = t;
         }
     avgTapsPos /= (double)s.OH * s.OW;
-    const bool smallMap = (s.ph > 0 || s.pw > 0) && s.OH * s.OW <= kSmallMapPixels;
+    // position-major rows pay off whenever some taps fall into the padding
+    const bool padded = avgTapsPos < s.FH * s.FW;
 
     int fbm = 0, fbn = 0;
     const bool haveForced = forced_tile(&fbm, &fbn, true);
@@ -209,18 +222,21 @@ Plan plan_fwd(const Shape &s)
             if (c.bn > 32 && c.bn / 2 >= s.OC) continue;
             if (c.bn == 32 && s.OC > 32) continue;
         }
-        const int posMajor = resolve_order(smallMap, s.N % c.bm == 0);
         const long long tiles = (long long)ceil_div(M, c.bm) * ceil_div(s.OC, c.bn);
-        const double avgStages = (posMajor ? avgTapsPos : s.FH * s.FW) * chunksPerTap;
-        const double maxStages = (posMajor ? maxTapsPos : s.FH * s.FW) * chunksPerTap;
-        int sp = 1;
-        const double t = best_split(c, tiles, avgStages, maxStages, pl.outElems, &sp);
-        if (t < best) {
-            best = t;
-            pl.bm = c.bm;
-            pl.bn = c.bn;
-            pl.posMajor = posMajor;
-            pl.split = sp;
+        for (int order = 0; order < 2; ++order) {
+            if (resolve_order(order, s.N % c.bm == 0) != order) continue;
+            if (order && !padded && g_forcePosMajor.load() != 1) continue;
+            const double avgStages = (order ? avgTapsPos : s.FH * s.FW) * chunksPerTap;
+            const double maxStages = (order ? maxTapsPos : s.FH * s.FW) * chunksPerTap;
+            int sp = 1;
+            const double t = best_split(kGatherCost, c, tiles, avgStages, maxStages, pl.outElems, &sp);
+            if (t < best) {
+                best = t;
+                pl.bm = c.bm;
+                pl.bn = c.bn;
+                pl.posMajor = order;
+                pl.split = sp;
+            }
         }
     }
     pl.tilesN = ceil_div(s.OC, pl.bn);
@@ -308,7 +324,7 @@ Plan plan_bwd_data(const Shape &s)
             }
         avgTapsPos /= (double)s.IH * s.IW;
     }
-    const bool smallMap = unitStride && (s.FH > 1 || s.FW > 1) && s.IH * s.IW <= kSmallMapPixels;
+    const bool padded = unitStride && avgTapsPos < s.FH * s.FW;
 
     int fbm = 0, fbn = 0;
     const bool haveForced = forced_tile(&fbm, &fbn, true);
@@ -325,24 +341,24 @@ Plan plan_bwd_data(const Shape &s)
         double avgTaps = 0;
         int maxTaps = 0;
         const int tilesM = build_phases(s, c.bm, trial, &avgTaps, &maxTaps);
-        const int posMajor = resolve_order(smallMap, s.N % c.bm == 0);
-        if (posMajor) {
-            avgTaps = avgTapsPos;
-            maxTaps = maxTapsPos;
-        }
         const long long tiles = (long long)tilesM * ceil_div(s.IC, c.bn);
-        int sp = 1;
-        const double t = best_split(c, tiles, avgTaps * chunksPerTap, (double)maxTaps * chunksPerTap,
-                                    pl.outElems, &sp);
-        if (t < best) {
-            best = t;
-            trial.bm = c.bm;
-            trial.bn = c.bn;
-            trial.posMajor = posMajor;
-            trial.split = sp;
-            trial.tilesM = tilesM;
-            trial.tilesN = ceil_div(s.IC, c.bn);
-            pl = trial;
+        for (int order = 0; order < 2; ++order) {
+            if (resolve_order(order, s.N % c.bm == 0) != order) continue;
+            if (order && !padded && g_forcePosMajor.load() != 1) continue;
+            const double a = order && unitStride ? avgTapsPos : avgTaps;
+            const double m = order && unitStride ? (double)maxTapsPos : (double)maxTaps;
+            int sp = 1;
+            const double t = best_split(kGatherCost, c, tiles, a * chunksPerTap, m * chunksPerTap, pl.outElems, &sp);
+            if (t < best) {
+                best = t;
+                trial.bm = c.bm;
+                trial.bn = c.bn;
+                trial.posMajor = order;
+                trial.split = sp;
+                trial.tilesM = tilesM;
+                trial.tilesN = ceil_div(s.IC, c.bn);
+                pl = trial;
+            }
         }
     }
     finish_plan(pl, pl.split);
@@ -384,7 +400,7 @@ Plan plan_bwd_weight(const Shape &s)
         }
         const long long tiles = (long long)ceil_div(s.OC, c.bm) * ceil_div(Ktot, c.bn);
         int sp = 1;
-        const double t = best_split(c, tiles, chunks * live, (double)chunks, pl.outElems, &sp);
+        const double t = best_split(kWgradCost, c, tiles, chunks * live, (double)chunks, pl.outElems, &sp);
         if (t < best) {
             best = t;
             pl.bm = c.bm;

@@ -213,33 +213,50 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
                 aValid |= 1u << i;
     };
 
-    f4 ga[T::PA], gb[T::PB];
+    // two register sets: the loads of stage t+2 are in flight while stage t is multiplied
+    f4 gaS[2][T::PA], gbS[2][T::PB];
     const f4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
-    auto gload = [&]() __attribute__((always_inline)) {
+    // Loads are unconditional (rows or columns outside the problem read element 0 instead) and
+    // the zeros are selected when the registers move to LDS: no branch sits between the loads
+    // of different stages, so they stay in flight across a whole stage.
+    unsigned aMaskS[2] = {0u, 0u};
+    unsigned bMask = 0u;
+#pragma unroll
+    for (int i = 0; i < T::PB; ++i) {
+        const int r = bRow + T::B_RPP * i;
+        const bool ok = BWD ? (r < kBK && n0 + bSeg * 4 < p.DC) : (r < BN && n0 + r < p.DC);
+        if (ok) bMask |= 1u << i;
+    }
+    // item q of a stage: q < PA is A-tile pass q, otherwise B-tile pass q - PA
+    constexpr int kItems = T::PA + T::PB;
+    constexpr int kGroups = kBK / 8;
+    auto gload_item = [&](int q, f4 *ga, f4 *gb) __attribute__((always_inline)) {
         const int c0 = chunk * kBK;
-#pragma unroll
-        for (int i = 0; i < T::PA; ++i) {
-            ga[i] = zero4;
-            if (aValid & (1u << i))
-                ga[i] = *reinterpret_cast<const f4 *>(p.A + (long long)(rBase[i] + tapOffA + c0));
-        }
-#pragma unroll
-        for (int i = 0; i < T::PB; ++i) {
-            gb[i] = zero4;
+        if (q < T::PA) {
+#if defined(EXP_SAMEADDR)
+            const int off = (aValid & (1u << q)) ? (aRow + 32 * q) * 32 + aSeg * 4 + (c0 & 0) : 0;
+#else
+            const int off = (aValid & (1u << q)) ? rBase[q] + tapOffA + c0 : 0;
+#endif
+            ga[q] = *reinterpret_cast<const f4 *>(p.A + (long long)off);
+        } else {
+            const int i = q - T::PA;
             const int r = bRow + T::B_RPP * i;
-            if (BWD) {
-                const int col = n0 + bSeg * 4;
-                if (r < kBK && col < p.DC)
-                    gb[i] = *reinterpret_cast<const f4 *>(p.B + (long long)(c0 + r) * wRowStride +
-                                                              tapOffB + col);
-            } else {
-                const int col = n0 + r;
-                if (r < BN && col < p.DC)
-                    gb[i] = *reinterpret_cast<const f4 *>(p.B + (long long)col * wRowStride +
-                                                              tapOffB + c0 + bSeg * 4);
-            }
+            long long off;
+            if (BWD) off = (long long)(c0 + r) * wRowStride + tapOffB + n0 + bSeg * 4;
+            else off = (long long)(n0 + r) * wRowStride + tapOffB + c0 + bSeg * 4;
+            if (!(bMask & (1u << i))) off = 0;
+#if defined(EXP_SAMEADDR)
+            off = (r * 8 + bSeg) * 4;
+#endif
+            gb[i] = *reinterpret_cast<const f4 *>(p.B + off);
         }
+    };
+    auto gload = [&](f4 *ga, f4 *gb, unsigned &aMask) __attribute__((always_inline)) {
+        aMask = aValid;
+#pragma unroll
+        for (int q = 0; q < kItems; ++q) gload_item(q, ga, gb);
     };
 
     auto advance = [&]() __attribute__((always_inline)) {
@@ -250,17 +267,21 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
         }
     };
 
-    auto lds_store = [&](int buf) __attribute__((always_inline)) {
-        float *a = As + buf * T::A_STAGE;
-        float *b = Bs + buf * T::B_STAGE;
-#pragma unroll
-        for (int i = 0; i < T::PA; ++i)
-            *reinterpret_cast<f4 *>(a + (aRow + 32 * i) * LDA + aSeg * 4) = ga[i];
-#pragma unroll
-        for (int i = 0; i < T::PB; ++i) {
+    auto lds_store_item = [&](int q, int buf, const f4 *ga, const f4 *gb, unsigned aMask) __attribute__((always_inline)) {
+        if (q < T::PA) {
+            float *a = As + buf * T::A_STAGE;
+            *reinterpret_cast<f4 *>(a + (aRow + 32 * q) * LDA + aSeg * 4) = (aMask & (1u << q)) ? ga[q] : zero4;
+        } else {
+            const int i = q - T::PA;
+            float *b = Bs + buf * T::B_STAGE;
             const int r = bRow + T::B_RPP * i;
-            if (r < T::B_ROWS) *reinterpret_cast<f4 *>(b + r * T::LDB + bSeg * 4) = gb[i];
+            if (T::B_ROWS % T::B_RPP == 0 || r < T::B_ROWS)
+                *reinterpret_cast<f4 *>(b + r * T::LDB + bSeg * 4) = (bMask & (1u << i)) ? gb[i] : zero4;
         }
+    };
+    auto lds_store = [&](int buf, const f4 *ga, const f4 *gb, unsigned aMask) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < kItems; ++q) lds_store_item(q, buf, ga, gb, aMask);
     };
 
     // ---- accumulators -------------------------------------------------------------------
@@ -275,55 +296,96 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     const int wm = wave / T::WAVES_N, wn = wave % T::WAVES_N;
     const int l32 = lane & 31, lh = lane >> 5;
 
-    auto compute = [&](int buf) __attribute__((always_inline)) {
+    // LDS -> register fragments for reduction group jj (8 k values: 4 per half-wave)
+    auto load_frag = [&](const float *a, const float *b, int jj, f4 *fa, f4 *fb) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < T::MB; ++i) fa[i] = *reinterpret_cast<const f4 *>(a + i * 32 * LDA + jj * 8);
+#pragma unroll
+        for (int j = 0; j < T::NB; ++j) {
+            if (BWD) {
+                const float *q = b + (jj * 8) * T::LDB + j * 32;
+                fb[j] = f4{q[0], q[T::LDB], q[2 * T::LDB], q[3 * T::LDB]};
+            } else {
+                fb[j] = *reinterpret_cast<const f4 *>(b + j * 32 * T::LDB + jj * 8);
+            }
+        }
+    };
+
+    // One stage.  MFMAs run from LDS buffer `buf` in kGroups groups of 8 reduction elements.
+    // Before the MFMAs of group jj are issued the wave requests the fragments of group jj+1
+    // and issues its share (items q with q % kGroups == jj) of
+    //   - the global loads of the stage two ahead, into register set `ld` (when doLoad),
+    //   - the LDS stores of the next stage, from register set `st` into the other buffer
+    //     (when doStore),
+    // so memory instructions are spread between MFMAs instead of starving the matrix pipe in
+    // a burst at the stage boundary.
+    auto stage = [&](int buf, bool doLoad, int ld, bool doStore, int st) __attribute__((always_inline)) {
         const float *a = As + buf * T::A_STAGE + (wm * T::WTM + l32) * LDA + lh * 4;
         const float *b = BWD ? Bs + buf * T::B_STAGE + (lh * 4) * T::LDB + wn * T::WTN + l32
                              : Bs + buf * T::B_STAGE + (wn * T::WTN + l32) * T::LDB + lh * 4;
+        // the largest tile has no registers left for a second fragment set
+        constexpr bool kTwoFrags = BM * BN < 128 * 128;
+        f4 fa[kTwoFrags ? 2 : 1][T::MB], fb[kTwoFrags ? 2 : 1][T::NB];
+        if (kTwoFrags) load_frag(a, b, 0, fa[0], fb[0]);
+        if (doLoad) aMaskS[ld] = aValid;
 #pragma unroll
-        for (int jj = 0; jj < kBK / 8; ++jj) {
-            f4 fa[T::MB], fb[T::NB];
-#pragma unroll
-            for (int i = 0; i < T::MB; ++i)
-                fa[i] = *reinterpret_cast<const f4 *>(a + i * 32 * LDA + jj * 8);
-#pragma unroll
-            for (int j = 0; j < T::NB; ++j) {
-                if (BWD) {
-                    const float *q = b + (jj * 8) * T::LDB + j * 32;
-                    fb[j] = f4{q[0], q[T::LDB], q[2 * T::LDB], q[3 * T::LDB]};
-                } else {
-                    fb[j] = *reinterpret_cast<const f4 *>(b + j * 32 * T::LDB + jj * 8);
-                }
+        for (int jj = 0; jj < kGroups; ++jj) {
+            const int cur = kTwoFrags ? (jj & 1) : 0;
+            if (kTwoFrags) {
+                if (jj + 1 < kGroups) load_frag(a, b, jj + 1, fa[cur ^ 1], fb[cur ^ 1]);
+            } else {
+                load_frag(a, b, jj, fa[0], fb[0]);
             }
+#pragma unroll
+            for (int q = 0; q < kItems; ++q)
+                if (q % kGroups == jj) {
+                    if (doLoad) gload_item(q, gaS[ld], gbS[ld]);
+                    if (doStore) lds_store_item(q, buf ^ 1, gaS[st], gbS[st], aMaskS[st]);
+                }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
 #pragma unroll
                 for (int i = 0; i < T::MB; ++i)
 #pragma unroll
-                    for (int j = 0; j < T::NB; ++j) {
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t], fb[j][t], acc[i][j], 0, 0, 0);
-                    }
+                    for (int j = 0; j < T::NB; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[cur][i][t], fb[cur][j][t], acc[i][j], 0, 0, 0);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
+        if (doLoad) advance();
     };
 
     // ---- main loop ----------------------------------------------------------------------
+    // Stage t is multiplied from LDS buffer t&1.  Register set t&1 (whose data went to LDS one
+    // stage ago) receives the global loads of stage t+2; register set (t+1)&1, loaded one stage
+    // ago, moves to the other LDS buffer.  One barrier per stage.
     if (it0 < it1) {
+        const int n = it1 - it0;
         set_tap();
-        gload();
+        gload(gaS[0], gbS[0], aMaskS[0]);
         advance();
-        lds_store(0);
+        if (n > 1) {
+            gload(gaS[1], gbS[1], aMaskS[1]);
+            advance();
+        }
+        lds_store(0, gaS[0], gbS[0], aMaskS[0]);
         __syncthreads();
-        int buf = 0;
-        for (int it = it0; it < it1; ++it) {
-            const bool more = it + 1 < it1;
-            if (more) {
-                gload();
-                advance();
-            }
-            compute(buf);
-            if (more) lds_store(buf ^ 1);
+        int t = 0;
+        // steady state: no branch around memory instructions, so every wait is an exact count
+        for (; t + 3 < n; t += 2) {
+            stage(0, true, 0, true, 1);
             __syncthreads();
-            buf ^= 1;
+            stage(1, true, 1, true, 0);
+            __syncthreads();
+        }
+        // tail: at most three stages left
+        for (; t < n; t += 2) {
+            stage(0, t + 2 < n, 0, t + 1 < n, 1);
+            __syncthreads();
+            if (t + 1 >= n) break;
+            stage(1, t + 3 < n, 1, t + 2 < n, 0);
+            __syncthreads();
         }
     }
 

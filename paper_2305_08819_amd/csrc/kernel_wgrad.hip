@@ -185,27 +185,38 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_kernel(const WgradParams p)
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
 
+    auto load_frag = [&](const float *g, const float *x, int jj, f4 *fa, f4 *fb) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < T::MB; ++i) {
+            const float *q = g + (jj * 8) * T::LDG + i * 32;
+            fa[i] = f4{q[0], q[T::LDG], q[2 * T::LDG], q[3 * T::LDG]};
+        }
+#pragma unroll
+        for (int j = 0; j < T::NB; ++j) {
+            const float *q = x + (jj * 8) * T::LDX + j * 32;
+            fb[j] = f4{q[0], q[T::LDX], q[2 * T::LDX], q[3 * T::LDX]};
+        }
+    };
+
+    // fragments of group jj+1 are requested before the MFMAs of group jj are issued
     auto compute = [&](int buf) __attribute__((always_inline)) {
         const float *g = Gs + buf * T::G_STAGE + (lh * 4) * T::LDG + wm * T::WTM + l32;
         const float *x = Xs + buf * T::X_STAGE + (lh * 4) * T::LDX + wn * T::WTN + l32;
+        f4 fa[2][T::MB], fb[2][T::NB];
+        load_frag(g, x, 0, fa[0], fb[0]);
 #pragma unroll
         for (int jj = 0; jj < kBK / 8; ++jj) {
-            float fa[T::MB][4], fb[T::NB][4];
-#pragma unroll
-            for (int i = 0; i < T::MB; ++i)
-#pragma unroll
-                for (int t = 0; t < 4; ++t) fa[i][t] = g[(jj * 8 + t) * T::LDG + i * 32];
-#pragma unroll
-            for (int j = 0; j < T::NB; ++j)
-#pragma unroll
-                for (int t = 0; t < 4; ++t) fb[j][t] = x[(jj * 8 + t) * T::LDX + j * 32];
+            const int cur = jj & 1;
+            if (jj + 1 < kBK / 8) load_frag(g, x, jj + 1, fa[cur ^ 1], fb[cur ^ 1]);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int t = 0; t < 4; ++t)
 #pragma unroll
                 for (int i = 0; i < T::MB; ++i)
 #pragma unroll
                     for (int j = 0; j < T::NB; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t], fb[j][t], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[cur][i][t], fb[cur][j][t], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
     auto flush = [&]() __attribute__((always_inline)) {
