@@ -27,6 +27,7 @@ struct Plan {
     int bm = 0, bn = 0;
     int split = 1;
     int posMajor = 0;
+    int elem = 0;          // element-wise loader (channel counts the 16-byte loader cannot take)
     int grid = 0;
     int tilesM = 0, tilesN = 0;
     int flushChunks = 16;
@@ -178,6 +179,37 @@ int resolve_order(int wanted, bool allowed)
     return wanted && allowed;
 }
 
+// Tile and slice count for the element-wise gather kernel (tiles 128x64, 64x64, 128x32).
+void plan_elem_tiles(Plan &pl, long long rows, int cols, double stages)
+{
+    int fbm = 0, fbn = 0;
+    const bool haveForced = forced_tile(&fbm, &fbn, true) && !(fbm == 128 && fbn == 128);
+    double best = 1e300;
+    for (const TileCand &c0 : kGatherTiles) {
+        TileCand c = c0;
+        if (c.bm == 128 && c.bn == 128) continue;
+        if (haveForced) {
+            if (c.bm != fbm || c.bn != fbn) continue;
+        } else {
+            if (c.bn > 32 && c.bn / 2 >= cols) continue;
+            if (c.bn == 32 && cols > 32) continue;
+        }
+        c.eff *= 0.5;   // 4-byte loads, single LDS buffer
+        const long long tiles = (long long)ceil_div(rows, c.bm) * ceil_div(cols, c.bn);
+        int sp = 1;
+        const double t = best_split(kGatherCost, c, tiles, stages, stages, pl.outElems, &sp);
+        if (t < best) {
+            best = t;
+            pl.bm = c.bm;
+            pl.bn = c.bn;
+            pl.split = sp;
+        }
+    }
+    pl.posMajor = 0;
+    pl.tilesM = ceil_div(rows, pl.bm);
+    pl.tilesN = ceil_div(cols, pl.bn);
+}
+
 // Taps of a padded filter that land inside a map of `in` pixels for output index o.
 int taps_in_range(int o, int stride, int pad, int f, int in)
 {
@@ -191,11 +223,22 @@ Plan plan_fwd(const Shape &s)
     Plan pl;
     pl.outElems = (long long)s.N * s.OH * s.OW * s.OC;
     const int forced = g_forceVariant.load();
-    const bool eligible = s.IC % kBK == 0 && s.FH * s.FW <= kMaxTaps &&
-                          offsets_fit_32bit((long long)s.N * s.IH * s.IW * s.IC, s, s.IW, s.IC);
-    if (forced == MI355CONV_VARIANT_DIRECT || !eligible) return pl;
+    const bool fits = offsets_fit_32bit((long long)s.N * s.IH * s.IW * s.IC, s, s.IW, s.IC);
+    const bool chunked = s.IC % kBK == 0 && s.FH * s.FW <= kMaxTaps;
+    if (forced == MI355CONV_VARIANT_DIRECT || !fits) return pl;
     pl.variant = MI355CONV_VARIANT_MFMA;
     const long long M = (long long)s.N * s.OH * s.OW;
+    if (!chunked) {   // element-wise loader: flat reduction range, no tap skipping
+        pl.elem = 1;
+        const double stages = (double)ceil_div((long long)s.FH * s.FW * s.IC, kBK);
+        plan_elem_tiles(pl, M, s.OC, stages);
+        pl.nPhases = 1;
+        pl.phaseTileStart[1] = pl.tilesM;
+        pl.phaseDH[0] = s.OH;
+        pl.phaseDW[0] = s.OW;
+        finish_plan(pl, pl.split);
+        return pl;
+    }
     const int chunksPerTap = s.IC / kBK;
     // taps per output position (what a position-major tile walks)
     double avgTapsPos = 0;
@@ -302,12 +345,26 @@ Plan plan_bwd_data(const Shape &s)
     Plan pl;
     pl.outElems = (long long)s.N * s.IH * s.IW * s.IC;
     const int forced = g_forceVariant.load();
-    const bool eligible = s.OC % kBK == 0 && s.IC % 4 == 0 && s.FH * s.FW <= kMaxTaps &&
-                          s.sh * s.sw <= kMaxPhases &&
-                          offsets_fit_32bit((long long)s.N * s.OH * s.OW * s.OC, s, s.OW, s.OC) &&
-                          pl.outElems < kMaxElems;
-    if (forced == MI355CONV_VARIANT_DIRECT || !eligible) return pl;
+    const bool fits = s.sh * s.sw <= kMaxPhases &&
+                      offsets_fit_32bit((long long)s.N * s.OH * s.OW * s.OC, s, s.OW, s.OC) &&
+                      pl.outElems < kMaxElems;
+    const bool chunked = s.OC % kBK == 0 && s.IC % 4 == 0 && s.FH * s.FW <= kMaxTaps;
+    if (forced == MI355CONV_VARIANT_DIRECT || !fits) return pl;
     pl.variant = MI355CONV_VARIANT_MFMA;
+    if (!chunked) {
+        pl.elem = 1;
+        // every phase walks the whole flat (tap, oc) range; taps of other phases multiply zeros
+        const double stages = (double)ceil_div((long long)s.FH * s.FW * s.OC, kBK);
+        plan_elem_tiles(pl, (long long)s.N * s.IH * s.IW, s.IC, stages);
+        double avgTaps = 0;
+        int maxTaps = 0;
+        pl.tilesM = build_phases(s, pl.bm, pl, &avgTaps, &maxTaps);
+        int sp = 1;
+        TileCand c = {pl.bm, pl.bn, 0.35, 2};
+        best_split(kGatherCost, c, (long long)pl.tilesM * pl.tilesN, stages, stages, pl.outElems, &sp);
+        finish_plan(pl, sp);
+        return pl;
+    }
     const int chunksPerTap = s.OC / kBK;
     const bool unitStride = s.sh == 1 && s.sw == 1;
     // stride 1: taps reaching input position (ih, iw) = taps of the flipped filter with pad F-1-p
@@ -371,14 +428,14 @@ Plan plan_bwd_weight(const Shape &s)
     pl.outElems = (long long)s.OC * s.FH * s.FW * s.IC;
     const int forced = g_forceVariant.load();
     const long long M = (long long)s.N * s.OH * s.OW;
-    const bool eligible = s.IC % 4 == 0 && s.OC % 4 == 0 && M < kMaxElems - kBK &&
-                          (long long)s.N * s.IH * s.IW < kMaxElems;
+    const bool eligible = s.OC % 4 == 0 && M < kMaxElems - kBK && (long long)s.N * s.IH * s.IW < kMaxElems;
     if (forced == MI355CONV_VARIANT_DIRECT || !eligible) return pl;
     pl.variant = MI355CONV_VARIANT_MFMA;
+    pl.elem = s.IC % 4 != 0;
     const long long Ktot = (long long)s.FH * s.FW * s.IC;
     const int chunks = ceil_div(M, kBK);
     const bool smallMap = (s.ph > 0 || s.pw > 0) && s.OH * s.OW <= kSmallMapPixels;
-    const int posMajor = resolve_order(smallMap, s.N % kBK == 0);
+    const int posMajor = resolve_order(smallMap, s.N % kBK == 0 && !pl.elem);
     // fraction of (position, tap) pairs inside the image = share of stages a tile keeps
     double live = 1.0;
     if (posMajor) {
@@ -392,7 +449,8 @@ Plan plan_bwd_weight(const Shape &s)
     const bool haveForced = forced_tile(&fbm, &fbn, false);
     double best = 1e300;
     for (const TileCand &c : kWgradTiles) {
-        if (haveForced) {
+        if (pl.elem && c.bn != 64) continue;   // element-wise X loader is compiled for 64-wide tiles
+        if (haveForced && !(pl.elem && fbn != 64)) {
             if (c.bm != fbm || c.bn != fbn) continue;
         } else {
             if (c.bm > 64 && c.bm / 2 >= s.OC) continue;
@@ -483,7 +541,8 @@ int run_gather(const float *A, const float *B, float *out, const Shape &s, const
     g.FH = s.FH; g.FW = s.FW;
     g.sh = s.sh; g.sw = s.sw; g.ph = s.ph; g.pw = s.pw;
     fill_gather_params(g, pl);
-    hipError_t e = launch_gather_gemm(g, bwd, pl.bm, pl.bn, pl.grid, st);
+    hipError_t e = pl.elem ? launch_gather_elem(g, bwd, pl.bm, pl.bn, pl.grid, st)
+                           : launch_gather_gemm(g, bwd, pl.bm, pl.bn, pl.grid, st);
     if (e != hipSuccess) return hip_fail(e);
     if (pl.split > 1) {
         e = launch_slice_reduce(static_cast<const float *>(ws), out, pl.outElems, pl.split, pl.sliceStride, st);
@@ -615,7 +674,7 @@ int conv2d_bwd_weight(const float *X, const float *dY, float *dW, const conv2d_d
     w.xcdUnit = pl.tilesN;   // the column tiles of one slice read the same G and X rows
     w.M = s.N * s.OH * s.OW;
     w.flushChunks = pl.flushChunks;
-    hipError_t e = launch_wgrad(w, pl.bm, pl.bn, pl.grid, st);
+    hipError_t e = launch_wgrad(w, pl.bm, pl.bn, pl.elem != 0, pl.grid, st);
     if (e != hipSuccess) return hip_fail(e);
     if (pl.split > 1) {
         e = launch_slice_reduce(static_cast<const float *>(ws), dW, pl.outElems, pl.split, pl.sliceStride, st);

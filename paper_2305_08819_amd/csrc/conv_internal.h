@@ -89,6 +89,8 @@ hipError_t launch_slice_reduce(const float *ws, float *out, long long count, int
 // bm/bn select the compiled tile; returns hipErrorInvalidValue for an unknown pair.
 hipError_t launch_gather_gemm(const GatherGemmParams &p, bool bwdData, int bm, int bn, int grid,
                               hipStream_t st);
-hipError_t launch_wgrad(const WgradParams &p, int bm, int bn, int grid, hipStream_t st);
+// same tiles (except 128x128), element-wise loader: any channel counts
+hipError_t launch_gather_elem(const GatherGemmParams &p, bool bwdData, int bm, int bn, int grid, hipStream_t st);
+hipError_t launch_wgrad(const WgradParams &p, int bm, int bn, bool xElem, int grid, hipStream_t st);
 
 }  // namespace mi355conv

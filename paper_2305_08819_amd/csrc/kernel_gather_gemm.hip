@@ -23,40 +23,9 @@
 // D[i = 8*(r/4) + 4*(l/32) + r%4][j = l%32].  The order in which reduction elements are fed
 // is free as long as A and B agree, so a lane reads FOUR consecutive k (one 16-byte LDS
 // read at k = 8*jj + 4*(l/32)) and uses them in four successive MFMAs.
-#include "conv_internal.h"
+#include "gather_common.h"
 
 namespace mi355conv {
-
-typedef float float16v __attribute__((ext_vector_type(16)));
-typedef float f4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers
-
-namespace {
-
-constexpr int LDA = kBK + 4;   // LDS row pitch (floats) of a [row][k] tile: 16-byte aligned, bank-skewed
-
-template <int BM, int BN, int WAVES_M, bool BWD>
-struct GG {
-    static constexpr int WAVES_N = 4 / WAVES_M;
-    static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;   // wave tile
-    static constexpr int MB = WTM / 32, NB = WTN / 32;             // 32x32 MFMA blocks per wave
-    static constexpr int PA = BM / 32;                             // A loader passes (32 rows each)
-    // forward: B tile is [BN cols][kBK] (k contiguous, like A); backward-data: [kBK][BN] (col contiguous)
-    static constexpr int LDB = BWD ? (BN + 8) : LDA;
-    static constexpr int B_TPR = BWD ? BN / 4 : 8;                 // threads per B tile row
-    static constexpr int B_RPP = kThreads / B_TPR;                 // B rows per pass
-    static constexpr int B_ROWS = BWD ? kBK : BN;
-    static constexpr int PB = (B_ROWS + B_RPP - 1) / B_RPP;
-    static constexpr int A_STAGE = BM * LDA;
-    static constexpr int B_STAGE = B_ROWS * LDB;
-    static constexpr int TABLE_INTS = 4 * BM + 4;
-    static constexpr size_t SMEM_BYTES = (2 * (A_STAGE + B_STAGE) + TABLE_INTS) * sizeof(float);
-    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be whole 32x32 blocks");
-    static_assert(B_ROWS % B_RPP == 0 || B_ROWS < B_RPP, "B loader passes");
-};
-
-constexpr int kInvalidCoord = -(1 << 28);
-
-}  // namespace
 
 template <int BM, int BN, int WAVES_M, bool BWD>
 __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGemmParams p)
@@ -76,98 +45,10 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     const int lane = tid & 63;
     const int wave = tid >> 6;
 
-    // ---- which tile / slice / phase --------------------------------------------------
-    int bid = xcd_remap(blockIdx.x, gridDim.x, p.xcdUnit);
-    const int tn = bid % p.tilesN;
-    bid /= p.tilesN;
-    const int slice = bid % p.split;
-    const int tmGlobal = bid / p.split;
-    int phase = 0;
-    while (phase + 1 < p.nPhases && tmGlobal >= p.phaseTileStart[phase + 1]) ++phase;
-    const int tmLocal = tmGlobal - p.phaseTileStart[phase];
-    const int ra = p.phaseRa[phase], rb = p.phaseRb[phase];
-    const int PY0 = p.phaseY0[phase], PX0 = p.phaseX0[phase];
-    const int PDH = p.phaseDH[phase], PDW = p.phaseDW[phase];
-    const int Mphase = p.Nimg * PDH * PDW;
-    const int n0 = tn * BN;
+    const GatherTile tile = gather_tile_setup<BM, BN, BWD>(p, rowBase, rowY, rowX, outRow, tapMaskS);
+    const int slice = tile.slice, n0 = tile.n0;
 
-    if (tid < 2) tapMaskS[tid] = 0u;
-    __syncthreads();
-
-    // ---- row tables: one thread per tile row ------------------------------------------
-    if (tid < BM) {
-        const int m = tmLocal * BM + tid;
-        int base = 0, y0 = kInvalidCoord, x0 = kInvalidCoord, orow = -1;
-        if (m < Mphase) {
-            int n, i, j;
-            if (p.posMajor) {
-                n = m % p.Nimg;
-                const int pos = m / p.Nimg;
-                i = pos / PDW;
-                j = pos - i * PDW;
-            } else {
-                const int hw = PDH * PDW;
-                n = m / hw;
-                const int r = m - n * hw;
-                i = r / PDW;
-                j = r - i * PDW;
-            }
-            int dyc, dxc;
-            if (BWD) {
-                dyc = PY0 + i * p.sh;
-                dxc = PX0 + j * p.sw;
-                y0 = (PY0 + p.ph) / p.sh + i;
-                x0 = (PX0 + p.pw) / p.sw + j;
-            } else {
-                dyc = i;
-                dxc = j;
-                y0 = i * p.sh - p.ph;
-                x0 = j * p.sw - p.pw;
-            }
-            orow = (n * p.DH + dyc) * p.DW + dxc;
-            base = ((n * p.SH + y0) * p.SW + x0) * p.SC;
-        }
-        unsigned lo = 0u, hi = 0u;
-        int t = 0;
-        for (int fh = 0; fh < p.FH; ++fh) {
-            bool okh;
-            int sy;
-            if (BWD) {
-                okh = (fh % p.sh) == ra;
-                sy = y0 - fh / p.sh;
-            } else {
-                okh = true;
-                sy = y0 + fh;
-            }
-            okh = okh && (unsigned)sy < (unsigned)p.SH;
-            for (int fw = 0; fw < p.FW; ++fw, ++t) {
-                bool okw;
-                int sx;
-                if (BWD) {
-                    okw = (fw % p.sw) == rb;
-                    sx = x0 - fw / p.sw;
-                } else {
-                    okw = true;
-                    sx = x0 + fw;
-                }
-                okw = okw && (unsigned)sx < (unsigned)p.SW;
-                if (okh && okw) {
-                    if (t < 32) lo |= 1u << t;
-                    else hi |= 1u << (t - 32);
-                }
-            }
-        }
-        if (lo) atomicOr(&tapMaskS[0], lo);
-        if (hi) atomicOr(&tapMaskS[1], hi);
-        rowBase[tid] = base;
-        rowY[tid] = y0;
-        rowX[tid] = x0;
-        outRow[tid] = orow;
-    }
-    __syncthreads();
-
-    const unsigned long long tapMask =
-        (unsigned long long)tapMaskS[0] | ((unsigned long long)tapMaskS[1] << 32);
+    const unsigned long long tapMask = tile.tapMask;
     const int chunksPerTap = p.SC / kBK;
     const int nIter = __popcll(tapMask) * chunksPerTap;
     const int it0 = (int)((long long)slice * nIter / p.split);
@@ -389,26 +270,14 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
         }
     }
 
-    // ---- epilogue: rows of a 32x32 block are spread over registers, columns over lanes ----
-    float *C = p.C + (long long)slice * p.sliceStride;
-#pragma unroll
-    for (int i = 0; i < T::MB; ++i)
-#pragma unroll
-        for (int j = 0; j < T::NB; ++j) {
-            const int col = n0 + wn * T::WTN + j * 32 + l32;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = wm * T::WTM + i * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
-                const int orow = outRow[row];
-                if (orow >= 0 && col < p.DC) C[(long long)orow * p.DC + col] = acc[i][j][r];
-            }
-        }
+    gather_tile_store<T>(p, slice, n0, outRow, acc, wm, wn, l32, lh);
 }
 
 template <int BM, int BN, int WAVES_M, bool BWD>
 static hipError_t launch_one(const GatherGemmParams &p, int grid, hipStream_t st)
 {
     using T = GG<BM, BN, WAVES_M, BWD>;
+    constexpr size_t kSmemBytes = (2 * (T::A_STAGE + T::B_STAGE) + T::TABLE_INTS) * sizeof(float);
     auto kern = gather_gemm_kernel<BM, BN, WAVES_M, BWD>;
     static bool attrSet[16] = {};
     int dev = 0;
@@ -416,11 +285,11 @@ static hipError_t launch_one(const GatherGemmParams &p, int grid, hipStream_t st
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= 16 || !attrSet[dev]) {
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)T::SMEM_BYTES);
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmemBytes);
         if (e != hipSuccess) return e;
         if (dev >= 0 && dev < 16) attrSet[dev] = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), T::SMEM_BYTES, st, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kSmemBytes, st, p);
     return hipGetLastError();
 }
 

@@ -36,7 +36,10 @@ struct WG {
 };
 }  // namespace
 
-template <int BM, int BN>
+// XELEM: the input-channel count is not a multiple of 4, so a 4-column segment of the X tile
+// can straddle filter taps; its four elements are then fetched one by one, each with its own
+// tap.  (Row order must be (n,oh,ow) in that mode.)
+template <int BM, int BN, bool XELEM>
 __global__ __launch_bounds__(kThreads, 2) void wgrad_kernel(const WgradParams p)
 {
     using T = WG<BM, BN>;
@@ -67,6 +70,17 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_kernel(const WgradParams p)
     const int xTap = xOk ? xCol / p.IC : 0;
     const int xIc = xCol - xTap * p.IC;
     const int xFh = xTap / p.FW, xFw = xTap - xFh * p.FW;
+    int eFh[4], eFw[4], eIc[4];   // XELEM: tap and channel of each of the four columns
+    bool eOk[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int col = xCol + e;
+        eOk[e] = col < Ktot;
+        const int tap = eOk[e] ? col / p.IC : 0;
+        eIc[e] = col - tap * p.IC;
+        eFh[e] = tap / p.FW;
+        eFw[e] = tap - eFh[e] * p.FW;
+    }
     const int ohow = p.OH * p.OW;
 
     // taps covered by this tile (for the stage-skip test)
@@ -153,10 +167,19 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_kernel(const WgradParams p)
 #pragma unroll
             for (int i = 0; i < T::PX; ++i) {
                 gx[i] = zero4;
-                const int ih = rh[i] * p.sh - p.ph + xFh, iw = rw[i] * p.sw - p.pw + xFw;
-                if (xOk && rn[i] < p.N && (unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW)
-                    gx[i] = *reinterpret_cast<const f4 *>(
-                        p.X + ((long long)(rn[i] * p.IH + ih) * p.IW + iw) * p.IC + xIc);
+                if (XELEM) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int ih = rh[i] * p.sh - p.ph + eFh[e], iw = rw[i] * p.sw - p.pw + eFw[e];
+                        if (eOk[e] && rn[i] < p.N && (unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW)
+                            gx[i][e] = p.X[((long long)(rn[i] * p.IH + ih) * p.IW + iw) * p.IC + eIc[e]];
+                    }
+                } else {
+                    const int ih = rh[i] * p.sh - p.ph + xFh, iw = rw[i] * p.sw - p.pw + xFw;
+                    if (xOk && rn[i] < p.N && (unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW)
+                        gx[i] = *reinterpret_cast<const f4 *>(
+                            p.X + ((long long)(rn[i] * p.IH + ih) * p.IW + iw) * p.IC + xIc);
+                }
             }
             step_rows();
         }
@@ -268,11 +291,11 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_kernel(const WgradParams p)
         }
 }
 
-template <int BM, int BN>
+template <int BM, int BN, bool XELEM>
 static hipError_t launch_one(const WgradParams &p, int grid, hipStream_t st)
 {
     using T = WG<BM, BN>;
-    auto kern = wgrad_kernel<BM, BN>;
+    auto kern = wgrad_kernel<BM, BN, XELEM>;
     static bool attrSet[16] = {};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -287,12 +310,17 @@ static hipError_t launch_one(const WgradParams &p, int grid, hipStream_t st)
     return hipGetLastError();
 }
 
-hipError_t launch_wgrad(const WgradParams &p, int bm, int bn, int grid, hipStream_t st)
+hipError_t launch_wgrad(const WgradParams &p, int bm, int bn, bool xElem, int grid, hipStream_t st)
 {
-    if (bm == 128 && bn == 128) return launch_one<128, 128>(p, grid, st);
-    if (bm == 64 && bn == 128) return launch_one<64, 128>(p, grid, st);
-    if (bm == 64 && bn == 64) return launch_one<64, 64>(p, grid, st);
-    if (bm == 128 && bn == 64) return launch_one<128, 64>(p, grid, st);
+    if (xElem) {   // narrow-channel layers: small tiles only
+        if (bm == 64 && bn == 64) return launch_one<64, 64, true>(p, grid, st);
+        if (bm == 128 && bn == 64) return launch_one<128, 64, true>(p, grid, st);
+        return hipErrorInvalidValue;
+    }
+    if (bm == 128 && bn == 128) return launch_one<128, 128, false>(p, grid, st);
+    if (bm == 64 && bn == 128) return launch_one<64, 128, false>(p, grid, st);
+    if (bm == 64 && bn == 64) return launch_one<64, 64, false>(p, grid, st);
+    if (bm == 128 && bn == 64) return launch_one<128, 64, false>(p, grid, st);
     return hipErrorInvalidValue;
 }
 

@@ -66,7 +66,10 @@ def test_workspace_errors(lib):
 
 def test_plans(lib):
     q = mc.conv2d_query_plan
+    # 3 input channels: element-wise MFMA variant; odd output channels: backward-weight goes direct
     p = q(mc.OP_FWD, mc.make_desc(4, 8, 8, 3, 16, 3, 3, 1, 1))
+    assert p.variant == mc.VARIANT_MFMA and p.tile_n == 32
+    p = q(mc.OP_BWD_WEIGHT, mc.make_desc(4, 8, 8, 3, 15, 3, 3, 1, 1))
     assert p.variant == mc.VARIANT_DIRECT and p.workspace_bytes == 0
     p = q(mc.OP_FWD, mc.make_desc(128, 32, 32, 64, 128, 3, 3, 2, 1))
     assert p.variant == mc.VARIANT_MFMA and p.split == 1 and p.grid >= 256

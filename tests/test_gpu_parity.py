@@ -38,8 +38,12 @@ def small_inputs(desc, seed):
     return X, W, G
 
 
-# N, IH, IW, IC, OC, FH, FW, stride, pad  -- shapes only the direct variant can take
+# N, IH, IW, IC, OC, FH, FW, stride, pad  -- channel counts the 16-byte loaders cannot take
 ODD_SHAPES = [
+    (5, 12, 12, 3, 64, 3, 3, 1, 1),        # first-layer shape, several row tiles
+    (2, 9, 7, 24, 40, 3, 3, 2, 1),         # IC % 4 == 0 but not % 32; ragged columns; two phases
+    (3, 6, 6, 48, 20, 5, 5, 1, 2),         # more than one reduction stage per tap
+    (1, 9, 9, 2, 8, 9, 9, 1, 4),           # 81 taps: beyond the tap-mask width
     (4, 8, 8, 3, 16, 3, 3, 1, 1),          # configuration 1
     (1, 5, 7, 1, 1, 3, 3, 1, 1),
     (3, 9, 6, 5, 2, 3, 2, (2, 1), (0, 1)),
@@ -57,6 +61,18 @@ def test_direct_variant_odd_shapes(shp):
     say("direct %s" % (shp,))
     d = mc.make_desc(*shp)
     mc.conv2d_set_tuning(mc.VARIANT_DIRECT, 0)
+    gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), label=str(shp))
+
+
+@pytest.mark.parametrize("split", [0, 2])
+@pytest.mark.parametrize("shp", ODD_SHAPES)
+def test_elementwise_mfma_variant_odd_shapes(shp, split):
+    """Channel counts outside the 16-byte loader's reach go through the element-wise MFMA kernels."""
+    say("elem %s split=%d" % (shp, split))
+    d = mc.make_desc(*shp)
+    mc.conv2d_set_tuning(mc.VARIANT_MFMA, split)
+    assert mc.conv2d_query_plan(mc.OP_FWD, d).variant == mc.VARIANT_MFMA
+    assert mc.conv2d_query_plan(mc.OP_BWD_DATA, d).variant == mc.VARIANT_MFMA
     gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), label=str(shp))
 
 
