@@ -36,9 +36,7 @@ struct Plan {
     size_t wsBytes = 0;
     // backward-data phase table
     int nPhases = 1;
-    int phaseTileStart[kMaxPhases + 1] = {};
-    short phaseRa[kMaxPhases] = {}, phaseRb[kMaxPhases] = {}, phaseY0[kMaxPhases] = {}, phaseX0[kMaxPhases] = {};
-    int phaseDH[kMaxPhases] = {}, phaseDW[kMaxPhases] = {};
+    GatherPhase phase[kMaxPhases] = {};
 };
 
 int out_extent(int in, int pad, int f, int stride)
@@ -179,6 +177,20 @@ int resolve_order(int wanted, bool allowed)
     return wanted && allowed;
 }
 
+// Forward convolution has a single "phase": all output pixels, all taps.
+void set_forward_phase(Plan &pl, const Shape &s)
+{
+    pl.nPhases = 1;
+    GatherPhase &g = pl.phase[0];
+    g = GatherPhase{};
+    g.dh = s.OH;
+    g.dw = s.OW;
+    g.nU = s.FH;
+    g.nV = s.FW;
+    g.divHW = make_fastdiv((unsigned)(s.OH * s.OW));
+    g.divW = make_fastdiv((unsigned)s.OW);
+}
+
 // Tile and slice count for the element-wise gather kernel (tiles 128x64, 64x64, 128x32).
 void plan_elem_tiles(Plan &pl, long long rows, int cols, double stages)
 {
@@ -224,7 +236,7 @@ Plan plan_fwd(const Shape &s)
     pl.outElems = (long long)s.N * s.OH * s.OW * s.OC;
     const int forced = g_forceVariant.load();
     const bool fits = offsets_fit_32bit((long long)s.N * s.IH * s.IW * s.IC, s, s.IW, s.IC);
-    const bool chunked = s.IC % kBK == 0 && s.FH * s.FW <= kMaxTaps;
+    const bool chunked = s.IC % kBK == 0;
     if (forced == MI355CONV_VARIANT_DIRECT || !fits) return pl;
     pl.variant = MI355CONV_VARIANT_MFMA;
     const long long M = (long long)s.N * s.OH * s.OW;
@@ -232,10 +244,7 @@ Plan plan_fwd(const Shape &s)
         pl.elem = 1;
         const double stages = (double)ceil_div((long long)s.FH * s.FW * s.IC, kBK);
         plan_elem_tiles(pl, M, s.OC, stages);
-        pl.nPhases = 1;
-        pl.phaseTileStart[1] = pl.tilesM;
-        pl.phaseDH[0] = s.OH;
-        pl.phaseDW[0] = s.OW;
+        set_forward_phase(pl, s);
         finish_plan(pl, pl.split);
         return pl;
     }
@@ -284,11 +293,7 @@ Plan plan_fwd(const Shape &s)
     }
     pl.tilesN = ceil_div(s.OC, pl.bn);
     pl.tilesM = ceil_div(M, pl.bm);
-    pl.nPhases = 1;
-    pl.phaseTileStart[0] = 0;
-    pl.phaseTileStart[1] = pl.tilesM;
-    pl.phaseDH[0] = s.OH;
-    pl.phaseDW[0] = s.OW;
+    set_forward_phase(pl, s);
     finish_plan(pl, pl.split);
     return pl;
 }
@@ -321,20 +326,25 @@ int build_phases(const Shape &s, int bm, Plan &pl, double *avgTaps, int *maxTaps
         const int dh = y0 < s.IH ? (s.IH - 1 - y0) / s.sh + 1 : 0;
         const int dw = x0 < s.IW ? (s.IW - 1 - x0) / s.sw + 1 : 0;
         if (dh == 0 || dw == 0) continue;
-        pl.phaseRa[k] = (short)ph[i].ra;
-        pl.phaseRb[k] = (short)ph[i].rb;
-        pl.phaseY0[k] = (short)y0;
-        pl.phaseX0[k] = (short)x0;
-        pl.phaseDH[k] = dh;
-        pl.phaseDW[k] = dw;
-        pl.phaseTileStart[k] = tiles;
+        GatherPhase &g = pl.phase[k];
+        g = GatherPhase{};
+        g.tileStart = tiles;
+        g.ra = ph[i].ra;
+        g.rb = ph[i].rb;
+        g.y0 = y0;
+        g.x0 = x0;
+        g.dh = dh;
+        g.dw = dw;
+        g.nU = ph[i].ra < s.FH ? (s.FH - 1 - ph[i].ra) / s.sh + 1 : 0;
+        g.nV = ph[i].rb < s.FW ? (s.FW - 1 - ph[i].rb) / s.sw + 1 : 0;
+        g.divHW = make_fastdiv((unsigned)(dh * dw));
+        g.divW = make_fastdiv((unsigned)dw);
         const int t = ceil_div((long long)s.N * dh * dw, bm);
         tiles += t;
         tapTiles += (double)t * ph[i].taps;
         if (ph[i].taps > *maxTaps) *maxTaps = ph[i].taps;
         ++k;
     }
-    pl.phaseTileStart[k] = tiles;
     pl.nPhases = k;
     *avgTaps = tiles ? tapTiles / tiles : 0;
     return tiles;
@@ -348,7 +358,7 @@ Plan plan_bwd_data(const Shape &s)
     const bool fits = s.sh * s.sw <= kMaxPhases &&
                       offsets_fit_32bit((long long)s.N * s.OH * s.OW * s.OC, s, s.OW, s.OC) &&
                       pl.outElems < kMaxElems;
-    const bool chunked = s.OC % kBK == 0 && s.IC % 4 == 0 && s.FH * s.FW <= kMaxTaps;
+    const bool chunked = s.OC % kBK == 0 && s.IC % 4 == 0;
     if (forced == MI355CONV_VARIANT_DIRECT || !fits) return pl;
     pl.variant = MI355CONV_VARIANT_MFMA;
     if (!chunked) {
@@ -511,15 +521,7 @@ void fill_gather_params(GatherGemmParams &g, const Plan &pl)
     g.tilesN = pl.tilesN;
     g.xcdUnit = pl.tilesN * pl.split * 2;   // both column tiles, all slices, two neighbouring row tiles
     g.nPhases = pl.nPhases;
-    for (int i = 0; i <= kMaxPhases; ++i) g.phaseTileStart[i] = pl.phaseTileStart[i];
-    for (int i = 0; i < kMaxPhases; ++i) {
-        g.phaseRa[i] = pl.phaseRa[i];
-        g.phaseRb[i] = pl.phaseRb[i];
-        g.phaseY0[i] = pl.phaseY0[i];
-        g.phaseX0[i] = pl.phaseX0[i];
-        g.phaseDH[i] = pl.phaseDH[i];
-        g.phaseDW[i] = pl.phaseDW[i];
-    }
+    for (int i = 0; i < kMaxPhases; ++i) g.phase[i] = pl.phase[i];
 }
 
 int run_gather(const float *A, const float *B, float *out, const Shape &s, const Plan &pl, bool bwd,
@@ -540,6 +542,7 @@ int run_gather(const float *A, const float *B, float *out, const Shape &s, const
     }
     g.FH = s.FH; g.FW = s.FW;
     g.sh = s.sh; g.sw = s.sw; g.ph = s.ph; g.pw = s.pw;
+    g.divN = make_fastdiv((unsigned)s.N);
     fill_gather_params(g, pl);
     hipError_t e = pl.elem ? launch_gather_elem(g, bwd, pl.bm, pl.bn, pl.grid, st)
                            : launch_gather_gemm(g, bwd, pl.bm, pl.bn, pl.grid, st);

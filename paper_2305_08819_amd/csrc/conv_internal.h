@@ -14,15 +14,47 @@ struct Shape {
 
 constexpr int kThreads = 256;     // every MFMA kernel runs 4 wavefronts per workgroup
 constexpr int kBK = 32;           // reduction elements staged per LDS stage
-constexpr int kMaxTaps = 64;      // FH*FW limit of the MFMA variants (tap set is a 64-bit mask)
 constexpr int kMaxPhases = 16;    // sh*sw limit of the MFMA backward-data variant
+
+// Division by a launch-invariant divisor with one multiply-high and two shifts (round-up
+// method of Granlund & Montgomery, "Division by invariant integers using multiplication").
+// Exact for every 32-bit unsigned n and 1 <= d < 2^31.
+struct FastDiv {
+    unsigned mul, sh1, sh2, d;
+};
+inline FastDiv make_fastdiv(unsigned d)
+{
+    unsigned l = 0;
+    while ((1ull << l) < d) ++l;                               // ceil(log2 d)
+    FastDiv f;
+    f.mul = (unsigned)(((1ull << 32) * ((1ull << l) - d)) / d + 1);
+    f.sh1 = l < 1 ? l : 1;
+    f.sh2 = l > 1 ? l - 1 : 0;
+    f.d = d;
+    return f;
+}
+__device__ __forceinline__ unsigned fast_div(unsigned n, const FastDiv &f)
+{
+    const unsigned t = __umulhi(f.mul, n);
+    return (t + ((n - t) >> f.sh1)) >> f.sh2;
+}
 
 // ---- gather-GEMM (forward and backward-data) ------------------------------------------
 // C[row, col] = sum over taps t of the tile's tap set, channels c:
 //                 A[n, y0(row)+dy(t), x0(row)+dx(t), c] * Wt(t, c, col)
-// Forward : A = X,  rows = output pixels,  cols = oc, c = ic, dy = fh,      phases = 1.
-// Bwd-data: A = dY, rows = input pixels of one stride phase, cols = ic, c = oc,
-//           dy = -(fh / sh) for the taps with fh % sh == phase residue.
+// Forward : A = X,  rows = output pixels,  cols = oc, c = ic, taps (u,v) = (fh,fw), dy = u.
+// Bwd-data: A = dY, rows = input pixels of one stride phase (ra,rb), cols = ic, c = oc,
+//           taps fh = ra + sh*u, fw = rb + sw*v, dy = -u, dx = -v.
+struct GatherPhase {
+    int tileStart;        // first row tile of the phase
+    int ra, rb;           // residues of (ih+ph) % sh, (iw+pw) % sw   (0 for forward)
+    int y0, x0;           // first destination row / column of the phase
+    int dh, dw;           // destination rows / columns in the phase
+    int nU, nV;           // taps of the phase along h and w
+    int pad_[3];
+    FastDiv divHW, divW;  // by dh*dw and by dw
+};
+
 struct GatherGemmParams {
     const float *A;
     const float *B;
@@ -38,11 +70,8 @@ struct GatherGemmParams {
     int tilesN;
     int xcdUnit;          // consecutive logical workgroup ids kept on one XCD
     int nPhases;
-    int phaseTileStart[kMaxPhases + 1];
-    // per phase: residues, first destination row/col, destination rows/cols in the phase
-    short phaseRa[kMaxPhases], phaseRb[kMaxPhases];
-    short phaseY0[kMaxPhases], phaseX0[kMaxPhases];
-    int phaseDH[kMaxPhases], phaseDW[kMaxPhases];
+    FastDiv divN;         // by Nimg
+    GatherPhase phase[kMaxPhases];
 };
 
 // ---- backward-weight ---------------------------------------------------------------------

@@ -2,6 +2,9 @@
 // element-wise loader): tile geometry, per-tile row tables, fragment reads + MFMAs, epilogue.
 #pragma once
 #include "conv_internal.h"
+#ifndef STAMP
+#define STAMP(i) do {} while (0)
+#endif
 
 namespace mi355conv {
 
@@ -34,15 +37,21 @@ struct GatherTile {
     int slice;                  // reduction slice of this workgroup
     int n0;                     // first output column
     int ra, rb;                 // stride-phase residues (backward-data)
-    unsigned long long tapMask; // taps that land inside the source image for at least one row
+    int uLo, uHi, vLo, vHi;     // bounding rectangle of the taps (u,v) that land inside the
+                                // source image for at least one row; empty if uHi < uLo
 };
 
-// Decodes the workgroup id into (row tile, column tile, slice, phase), fills the per-row
-// tables (source base offset, source y0/x0, destination pixel index or -1) and ORs the rows'
-// in-range tap sets.  All threads must call it; it contains two barriers.
+// Decodes the workgroup id into (row tile, column tile, slice, phase) and fills the per-row
+// tables (source base offset, source y0/x0, destination pixel index or -1).  The tile's tap
+// rectangle is computed from the tile's first and last row alone (uniform, no cross-thread
+// reduction): a row's valid taps along each axis form an interval whose ends are monotone in
+// the row's source coordinate, and the rows of a tile are contiguous in (n,y,x) or (y,x,n)
+// order.  Where a tile wraps over image rows or images the rectangle is widened to the full
+// range, which only adds taps whose operands load as zeros.  All threads must call it; it
+// contains one barrier.
 template <int BM, int BN, bool BWD>
 __device__ __forceinline__ GatherTile gather_tile_setup(const GatherGemmParams &p, int *rowBase, int *rowY,
-                                                        int *rowX, int *outRow, unsigned *tapMaskS)
+                                                        int *rowX, int *outRow)
 {
     const int tid = threadIdx.x;
     int bid = xcd_remap(blockIdx.x, gridDim.x, p.xcdUnit);
@@ -51,15 +60,17 @@ __device__ __forceinline__ GatherTile gather_tile_setup(const GatherGemmParams &
     const int slice = bid % p.split;
     const int tmGlobal = bid / p.split;
     int phase = 0;
-    while (phase + 1 < p.nPhases && tmGlobal >= p.phaseTileStart[phase + 1]) ++phase;
-    const int tmLocal = tmGlobal - p.phaseTileStart[phase];
-    const int ra = p.phaseRa[phase], rb = p.phaseRb[phase];
-    const int PY0 = p.phaseY0[phase], PX0 = p.phaseX0[phase];
-    const int PDH = p.phaseDH[phase], PDW = p.phaseDW[phase];
-    const int Mphase = p.Nimg * PDH * PDW;
-
-    if (tid < 2) tapMaskS[tid] = 0u;
-    __syncthreads();
+    if (BWD) {   // tile starts are ascending: the phase is the number of starts not above this tile
+#pragma unroll
+        for (int i = 1; i < kMaxPhases; ++i) phase += (i < p.nPhases && tmGlobal >= p.phase[i].tileStart) ? 1 : 0;
+    }
+    const GatherPhase ph = p.phase[phase];
+    const int tmLocal = tmGlobal - ph.tileStart;
+    const int hw = ph.dh * ph.dw;
+    const int Mphase = p.Nimg * hw;
+    const int yBase = BWD ? (ph.y0 + p.ph) / p.sh : -p.ph;   // source y of destination index i = 0
+    const int xBase = BWD ? (ph.x0 + p.pw) / p.sw : -p.pw;
+    const int yStep = BWD ? 1 : p.sh, xStep = BWD ? 1 : p.sw;
 
     if (tid < BM) {   // one thread per tile row
         const int m = tmLocal * BM + tid;
@@ -67,99 +78,111 @@ __device__ __forceinline__ GatherTile gather_tile_setup(const GatherGemmParams &
         if (m < Mphase) {
             int n, i, j;
             if (p.posMajor) {
-                n = m % p.Nimg;
-                const int pos = m / p.Nimg;
-                i = pos / PDW;
-                j = pos - i * PDW;
+                const int pos = (int)fast_div((unsigned)m, p.divN);
+                n = m - pos * p.Nimg;
+                i = (int)fast_div((unsigned)pos, ph.divW);
+                j = pos - i * ph.dw;
             } else {
-                const int hw = PDH * PDW;
-                n = m / hw;
+                n = (int)fast_div((unsigned)m, ph.divHW);
                 const int r = m - n * hw;
-                i = r / PDW;
-                j = r - i * PDW;
+                i = (int)fast_div((unsigned)r, ph.divW);
+                j = r - i * ph.dw;
             }
-            int dyc, dxc;
-            if (BWD) {
-                dyc = PY0 + i * p.sh;
-                dxc = PX0 + j * p.sw;
-                y0 = (PY0 + p.ph) / p.sh + i;
-                x0 = (PX0 + p.pw) / p.sw + j;
-            } else {
-                dyc = i;
-                dxc = j;
-                y0 = i * p.sh - p.ph;
-                x0 = j * p.sw - p.pw;
-            }
+            const int dyc = BWD ? ph.y0 + i * p.sh : i;
+            const int dxc = BWD ? ph.x0 + j * p.sw : j;
+            y0 = yBase + i * yStep;
+            x0 = xBase + j * xStep;
             orow = (n * p.DH + dyc) * p.DW + dxc;
             base = ((n * p.SH + y0) * p.SW + x0) * p.SC;
         }
-        unsigned lo = 0u, hi = 0u;
-        int t = 0;
-        for (int fh = 0; fh < p.FH; ++fh) {
-            bool okh;
-            int sy;
-            if (BWD) {
-                okh = (fh % p.sh) == ra;
-                sy = y0 - fh / p.sh;
-            } else {
-                okh = true;
-                sy = y0 + fh;
-            }
-            okh = okh && (unsigned)sy < (unsigned)p.SH;
-            for (int fw = 0; fw < p.FW; ++fw, ++t) {
-                bool okw;
-                int sx;
-                if (BWD) {
-                    okw = (fw % p.sw) == rb;
-                    sx = x0 - fw / p.sw;
-                } else {
-                    okw = true;
-                    sx = x0 + fw;
-                }
-                okw = okw && (unsigned)sx < (unsigned)p.SW;
-                if (okh && okw && t < kMaxTaps) {
-                    if (t < 32) lo |= 1u << t;
-                    else hi |= 1u << (t - 32);
-                }
-            }
-        }
-        if (lo) atomicOr(&tapMaskS[0], lo);
-        if (hi) atomicOr(&tapMaskS[1], hi);
         rowBase[tid] = base;
         rowY[tid] = y0;
         rowX[tid] = x0;
         outRow[tid] = orow;
     }
-    __syncthreads();
 
+    // ---- tap rectangle from the first and last row of the tile (uniform) ----------------
     GatherTile t;
     t.slice = slice;
     t.n0 = tn * BN;
-    t.ra = ra;
-    t.rb = rb;
-    t.tapMask = (unsigned long long)tapMaskS[0] | ((unsigned long long)tapMaskS[1] << 32);
+    t.ra = ph.ra;
+    t.rb = ph.rb;
+    t.uLo = t.vLo = 0;
+    t.uHi = t.vHi = -1;
+    const int m0 = tmLocal * BM;
+    if (m0 < Mphase) {
+        const int m1 = (m0 + BM < Mphase ? m0 + BM : Mphase) - 1;
+        int i0, i1, j0, j1;
+        bool wrap;
+        int r0, r1;
+        if (p.posMajor) {
+            r0 = (int)fast_div((unsigned)m0, p.divN);
+            r1 = (int)fast_div((unsigned)m1, p.divN);
+            wrap = false;
+        } else {
+            const int n0 = (int)fast_div((unsigned)m0, ph.divHW), n1 = (int)fast_div((unsigned)m1, ph.divHW);
+            r0 = m0 - n0 * hw;
+            r1 = m1 - n1 * hw;
+            wrap = n0 != n1;
+        }
+        if (wrap) {
+            i0 = 0; i1 = ph.dh - 1; j0 = 0; j1 = ph.dw - 1;
+        } else {
+            i0 = (int)fast_div((unsigned)r0, ph.divW);
+            i1 = (int)fast_div((unsigned)r1, ph.divW);
+            j0 = r0 - i0 * ph.dw;
+            j1 = r1 - i1 * ph.dw;
+            if (i0 != i1) { j0 = 0; j1 = ph.dw - 1; }
+        }
+        const int yMin = yBase + i0 * yStep, yMax = yBase + i1 * yStep;
+        const int xMin = xBase + j0 * xStep, xMax = xBase + j1 * xStep;
+        if (BWD) {   // source row y - u in [0, SH): u in [max(0, y-SH+1), min(nU-1, y)], both rising with y
+            t.uLo = max(0, yMin - p.SH + 1);
+            t.uHi = min(ph.nU - 1, yMax);
+            t.vLo = max(0, xMin - p.SW + 1);
+            t.vHi = min(ph.nV - 1, xMax);
+        } else {     // source row y + u in [0, SH): u in [max(0, -y), min(nU-1, SH-1-y)], both falling with y
+            t.uLo = max(0, -yMax);
+            t.uHi = min(ph.nU - 1, p.SH - 1 - yMin);
+            t.vLo = max(0, -xMax);
+            t.vHi = min(ph.nV - 1, p.SW - 1 - xMin);
+        }
+        if (t.uHi < t.uLo || t.vHi < t.vLo) { t.uHi = -1; t.uLo = 0; t.vHi = -1; t.vLo = 0; }
+    }
+    STAMP(6);
+    __syncthreads();
+    STAMP(7);
     return t;
 }
 
 // Epilogue: rows of a 32x32 block are spread over accumulator registers, columns over lanes.
+// The 16 destination-pixel indices of a block are fetched with four 16-byte LDS reads; output
+// offsets fit 32 bits because every tensor holds fewer than 2^31 elements.
 template <class T>
 __device__ __forceinline__ void gather_tile_store(const GatherGemmParams &p, int slice, int n0, const int *outRow,
                                                   const float16v (&acc)[T::MB][T::NB], int wm, int wn, int l32,
                                                   int lh)
 {
+    typedef int i4 __attribute__((ext_vector_type(4)));
     float *C = p.C + (long long)slice * p.sliceStride;
 #pragma unroll
-    for (int i = 0; i < T::MB; ++i)
+    for (int i = 0; i < T::MB; ++i) {
+        i4 orow[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            orow[g] = *reinterpret_cast<const i4 *>(outRow + wm * T::WTM + i * 32 + 8 * g + 4 * lh);
 #pragma unroll
         for (int j = 0; j < T::NB; ++j) {
             const int col = n0 + wn * T::WTN + j * 32 + l32;
+            if (col < p.DC) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = wm * T::WTM + i * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
-                const int orow = outRow[row];
-                if (orow >= 0 && col < p.DC) C[(long long)orow * p.DC + col] = acc[i][j][r];
+                for (int r = 0; r < 16; ++r) {
+                    const int o = orow[r / 4][r % 4];
+                    if (o >= 0) C[o * p.DC + col] = acc[i][j][r];
+                }
             }
         }
+    }
 }
 
 }  // namespace mi355conv

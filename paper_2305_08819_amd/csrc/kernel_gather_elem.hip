@@ -21,10 +21,9 @@ __global__ __launch_bounds__(kThreads, 2) void gather_elem_kernel(const GatherGe
     int *rowY = rowBase + BM;
     int *rowX = rowY + BM;
     int *outRow = rowX + BM;
-    unsigned *tapMaskS = reinterpret_cast<unsigned *>(outRow + BM);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const GatherTile tile = gather_tile_setup<BM, BN, BWD>(p, rowBase, rowY, rowX, outRow, tapMaskS);
+    const GatherTile tile = gather_tile_setup<BM, BN, BWD>(p, rowBase, rowY, rowX, outRow);
     const int slice = tile.slice, n0 = tile.n0;
 
     const int Ktot = p.FH * p.FW * p.SC;

@@ -23,6 +23,13 @@
 // D[i = 8*(r/4) + 4*(l/32) + r%4][j = l%32].  The order in which reduction elements are fed
 // is free as long as A and B agree, so a lane reads FOUR consecutive k (one 16-byte LDS
 // read at k = 8*jj + 4*(l/32)) and uses them in four successive MFMAs.
+#include <hip/hip_runtime.h>
+#if defined(EXP_STAMPS)
+namespace mi355conv { __device__ unsigned long long g_stamps[8192 * 8]; }
+#define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) mi355conv::g_stamps[blockIdx.x * 8 + (i)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define STAMP(i) do {} while (0)
+#endif
 #include "gather_common.h"
 
 namespace mi355conv {
@@ -30,6 +37,7 @@ namespace mi355conv {
 template <int BM, int BN, int WAVES_M, bool BWD>
 __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGemmParams p)
 {
+    STAMP(0);
     using T = GG<BM, BN, WAVES_M, BWD>;
     extern __shared__ f4 smem_raw[];
     float *smem = reinterpret_cast<float *>(smem_raw);
@@ -39,18 +47,20 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     int *rowY = rowBase + BM;
     int *rowX = rowY + BM;
     int *outRow = rowX + BM;
-    unsigned *tapMaskS = reinterpret_cast<unsigned *>(outRow + BM);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
 
-    const GatherTile tile = gather_tile_setup<BM, BN, BWD>(p, rowBase, rowY, rowX, outRow, tapMaskS);
+    const GatherTile tile = gather_tile_setup<BM, BN, BWD>(p, rowBase, rowY, rowX, outRow);
     const int slice = tile.slice, n0 = tile.n0;
+    STAMP(1);
 
-    const unsigned long long tapMask = tile.tapMask;
+    // taps walked by this tile: the rectangle [uLo,uHi] x [vLo,vHi]
+    const int uCnt = tile.uHi >= tile.uLo ? tile.uHi - tile.uLo + 1 : 0;
+    const int vCnt = tile.vHi >= tile.vLo ? tile.vHi - tile.vLo + 1 : 0;
     const int chunksPerTap = p.SC / kBK;
-    const int nIter = __popcll(tapMask) * chunksPerTap;
+    const int nIter = uCnt * vCnt * chunksPerTap;
     const int it0 = (int)((long long)slice * nIter / p.split);
     const int it1 = (int)((long long)(slice + 1) * nIter / p.split);
 
@@ -67,23 +77,29 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     const int bSeg = tid % T::B_TPR, bRow = tid / T::B_TPR;
     const long long wRowStride = (long long)p.FH * p.FW * (BWD ? p.DC : p.SC);  // floats per oc in W
 
-    // reduction cursor: remaining taps (bit set), current tap's offsets, chunk within the tap
-    unsigned long long rem = tapMask;
-    for (int k = it0 / chunksPerTap; k > 0; --k) rem &= rem - 1;
-    int chunk = it0 % chunksPerTap;
+    // reduction cursor: current tap (u,v) and chunk within the tap
+    int chunk = 0, tapU = tile.uLo, tapV = tile.vLo;
+    if (it0 < it1) {
+        const int tapIdx = it0 / chunksPerTap;
+        chunk = it0 - tapIdx * chunksPerTap;
+        const int du = tapIdx / vCnt;
+        tapU += du;
+        tapV += tapIdx - du * vCnt;
+    }
     int dy = 0, dx = 0, tapOffA = 0, tapOffB = 0;
     unsigned aValid = 0u;
 
     auto set_tap = [&]() __attribute__((always_inline)) {
-        const int t = __ffsll((long long)rem) - 1;
-        const int fh = t / p.FW, fw = t - fh * p.FW;
+        int t;
         if (BWD) {
-            dy = -(fh / p.sh);
-            dx = -(fw / p.sw);
+            dy = -tapU;
+            dx = -tapV;
+            t = (tile.ra + p.sh * tapU) * p.FW + tile.rb + p.sw * tapV;
             tapOffB = t * p.DC;
         } else {
-            dy = fh;
-            dx = fw;
+            dy = tapU;
+            dx = tapV;
+            t = tapU * p.FW + tapV;
             tapOffB = t * p.SC;
         }
         tapOffA = (dy * p.SW + dx) * p.SC;
@@ -143,8 +159,11 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     auto advance = [&]() __attribute__((always_inline)) {
         if (++chunk == chunksPerTap) {
             chunk = 0;
-            rem &= rem - 1;
-            if (rem) set_tap();
+            if (++tapV > tile.vHi) {
+                tapV = tile.vLo;
+                ++tapU;
+            }
+            if (tapU <= tile.uHi) set_tap();
         }
     };
 
@@ -250,8 +269,10 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
             gload(gaS[1], gbS[1], aMaskS[1]);
             advance();
         }
+        STAMP(2);
         lds_store(0, gaS[0], gbS[0], aMaskS[0]);
         __syncthreads();
+        STAMP(3);
         int t = 0;
         // steady state: no branch around memory instructions, so every wait is an exact count
         for (; t + 3 < n; t += 2) {
@@ -270,8 +291,17 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
         }
     }
 
+    STAMP(4);
     gather_tile_store<T>(p, slice, n0, outRow, acc, wm, wn, l32, lh);
+    STAMP(5);
 }
+
+#if defined(EXP_STAMPS)
+extern "C" int exp_read_stamps(unsigned long long *host, size_t count)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_stamps), count * sizeof(unsigned long long));
+}
+#endif
 
 template <int BM, int BN, int WAVES_M, bool BWD>
 static hipError_t launch_one(const GatherGemmParams &p, int grid, hipStream_t st)
