@@ -73,6 +73,14 @@ bool offsets_fit_32bit(long long srcElems, const Shape &s, int srcW, int srcC)
     return srcElems + halo < kMaxElems && halo < (1 << 27);
 }
 
+// Both operands of the buffer-load kernels must lie below 2^31 bytes, halo included.
+bool buffer_addressable(const Shape &s, long long srcElems, int srcW, int srcC)
+{
+    const long long halo = ((long long)(s.FH + s.ph + 1) * srcW + s.FW + s.pw + 1) * srcC;
+    const long long wElems = (long long)s.OC * s.FH * s.FW * s.IC;
+    return (srcElems + halo) * 4 < (1LL << 31) && wElems * 4 < (1LL << 31);
+}
+
 // ---- cost model ------------------------------------------------------------------------
 // Picks tile and slice count by a small analytic model instead of fixed thresholds.  Time of
 // a launch = rounds x (stages per workgroup x stage time + fixed per-workgroup cost), where a
@@ -236,7 +244,8 @@ Plan plan_fwd(const Shape &s)
     pl.outElems = (long long)s.N * s.OH * s.OW * s.OC;
     const int forced = g_forceVariant.load();
     const bool fits = offsets_fit_32bit((long long)s.N * s.IH * s.IW * s.IC, s, s.IW, s.IC);
-    const bool chunked = s.IC % kBK == 0;
+    // the 16-byte loader addresses both operands with 32-bit byte offsets
+    const bool chunked = s.IC % kBK == 0 && buffer_addressable(s, (long long)s.N * s.IH * s.IW * s.IC, s.IW, s.IC);
     if (forced == MI355CONV_VARIANT_DIRECT || !fits) return pl;
     pl.variant = MI355CONV_VARIANT_MFMA;
     const long long M = (long long)s.N * s.OH * s.OW;
@@ -358,7 +367,8 @@ Plan plan_bwd_data(const Shape &s)
     const bool fits = s.sh * s.sw <= kMaxPhases &&
                       offsets_fit_32bit((long long)s.N * s.OH * s.OW * s.OC, s, s.OW, s.OC) &&
                       pl.outElems < kMaxElems;
-    const bool chunked = s.OC % kBK == 0 && s.IC % 4 == 0;
+    const bool chunked = s.OC % kBK == 0 && s.IC % 4 == 0 &&
+                         buffer_addressable(s, (long long)s.N * s.OH * s.OW * s.OC, s.OW, s.OC);
     if (forced == MI355CONV_VARIANT_DIRECT || !fits) return pl;
     pl.variant = MI355CONV_VARIANT_MFMA;
     if (!chunked) {
@@ -543,6 +553,8 @@ int run_gather(const float *A, const float *B, float *out, const Shape &s, const
     g.FH = s.FH; g.FW = s.FW;
     g.sh = s.sh; g.sw = s.sw; g.ph = s.ph; g.pw = s.pw;
     g.divN = make_fastdiv((unsigned)s.N);
+    g.aBytes = (unsigned)((long long)g.Nimg * g.SH * g.SW * g.SC * 4);
+    g.bBytes = (unsigned)((long long)s.OC * s.FH * s.FW * s.IC * 4);
     fill_gather_params(g, pl);
     hipError_t e = pl.elem ? launch_gather_elem(g, bwd, pl.bm, pl.bn, pl.grid, st)
                            : launch_gather_gemm(g, bwd, pl.bm, pl.bn, pl.grid, st);

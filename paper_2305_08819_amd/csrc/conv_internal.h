@@ -59,6 +59,7 @@ struct GatherGemmParams {
     const float *A;
     const float *B;
     float *C;             // output tensor, or workspace base when split > 1
+    unsigned aBytes, bBytes;  // sizes of A and B in bytes (both below 2^31): buffer-load range checks
     int Nimg;
     int SH, SW, SC;       // source map height, width, channels (SC = reduction channels per tap)
     int DH, DW, DC;       // destination map height, width, channels (DC = GEMM columns)

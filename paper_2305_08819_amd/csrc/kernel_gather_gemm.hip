@@ -26,7 +26,7 @@
 #include <hip/hip_runtime.h>
 #if defined(EXP_STAMPS)
 namespace mi355conv { __device__ unsigned long long g_stamps[8192 * 8]; }
-#define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) mi355conv::g_stamps[blockIdx.x * 8 + (i)] = __builtin_readcyclecounter(); } while (0)
+#define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) mi355conv::g_stamps[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
 #else
 #define STAMP(i) do {} while (0)
 #endif
@@ -61,21 +61,40 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     const int vCnt = tile.vHi >= tile.vLo ? tile.vHi - tile.vLo + 1 : 0;
     const int chunksPerTap = p.SC / kBK;
     const int nIter = uCnt * vCnt * chunksPerTap;
-    const int it0 = (int)((long long)slice * nIter / p.split);
-    const int it1 = (int)((long long)(slice + 1) * nIter / p.split);
+    const int it0 = slice * nIter / p.split;          // nIter * split is far below 2^31
+    const int it1 = (slice + 1) * nIter / p.split;
 
     // ---- per-thread loader state --------------------------------------------------------
+    // Operands are fetched with raw buffer loads: address = base + VGPR byte offset + SGPR byte
+    // offset, and an offset past the tensor's size returns zeros.  The VGPR offsets change only
+    // when the tap changes (rows whose source pixel is padding get an out-of-range offset);
+    // the position inside the tap is the SGPR offset.  Steady-state stages therefore issue
+    // their loads with no vector-ALU instruction at all - on this chip fp32 MFMA and VALU
+    // instructions share the SIMD's issue cycles, so every VALU instruction in the loop is
+    // taken from the matrix rate.
+    const __amdgpu_buffer_rsrc_t rsrcA =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.A), 0, (int)p.aBytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcB =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.B), 0, (int)p.bBytes, 0x00020000);
+    constexpr int kOutOfRange = (int)0x80000000;   // tensors are below 2^31 bytes
     const int aSeg = tid & 7, aRow = tid >> 3;
     int rBase[T::PA], rY[T::PA], rX[T::PA];
 #pragma unroll
     for (int i = 0; i < T::PA; ++i) {
         const int r = aRow + 32 * i;
-        rBase[i] = rowBase[r] + aSeg * 4;
+        rBase[i] = (rowBase[r] + aSeg * 4) * 4;   // bytes; may be negative before the tap offset is added
         rY[i] = rowY[r];
         rX[i] = rowX[r];
     }
     const int bSeg = tid % T::B_TPR, bRow = tid / T::B_TPR;
-    const long long wRowStride = (long long)p.FH * p.FW * (BWD ? p.DC : p.SC);  // floats per oc in W
+    const int wRowStride = p.FH * p.FW * (BWD ? p.DC : p.SC);  // floats per oc in W
+    int bOff[T::PB];   // fixed for the whole kernel
+#pragma unroll
+    for (int i = 0; i < T::PB; ++i) {
+        const int r = bRow + T::B_RPP * i;
+        if (BWD) bOff[i] = (r < kBK && n0 + bSeg * 4 < p.DC) ? (r * wRowStride + n0 + bSeg * 4) * 4 : kOutOfRange;
+        else bOff[i] = (r < BN && n0 + r < p.DC) ? ((n0 + r) * wRowStride + bSeg * 4) * 4 : kOutOfRange;
+    }
 
     // reduction cursor: current tap (u,v) and chunk within the tap
     int chunk = 0, tapU = tile.uLo, tapV = tile.vLo;
@@ -86,11 +105,11 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
         tapU += du;
         tapV += tapIdx - du * vCnt;
     }
-    int dy = 0, dx = 0, tapOffA = 0, tapOffB = 0;
-    unsigned aValid = 0u;
+    int tapOffB = 0;      // floats, uniform
+    int aOff[T::PA];      // byte offsets of this thread's A rows for the current tap
 
     auto set_tap = [&]() __attribute__((always_inline)) {
-        int t;
+        int t, dy, dx;
         if (BWD) {
             dy = -tapU;
             dx = -tapV;
@@ -102,56 +121,31 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
             t = tapU * p.FW + tapV;
             tapOffB = t * p.SC;
         }
-        tapOffA = (dy * p.SW + dx) * p.SC;
-        aValid = 0u;
+        const int tapBytesA = (dy * p.SW + dx) * p.SC * 4;
 #pragma unroll
-        for (int i = 0; i < T::PA; ++i)
-            if ((unsigned)(rY[i] + dy) < (unsigned)p.SH && (unsigned)(rX[i] + dx) < (unsigned)p.SW)
-                aValid |= 1u << i;
+        for (int i = 0; i < T::PA; ++i) {
+            const bool ok = (unsigned)(rY[i] + dy) < (unsigned)p.SH && (unsigned)(rX[i] + dx) < (unsigned)p.SW;
+            aOff[i] = ok ? rBase[i] + tapBytesA : kOutOfRange;
+        }
     };
 
     // two register sets: the loads of stage t+2 are in flight while stage t is multiplied
     f4 gaS[2][T::PA], gbS[2][T::PB];
-    const f4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
-    // Loads are unconditional (rows or columns outside the problem read element 0 instead) and
-    // the zeros are selected when the registers move to LDS: no branch sits between the loads
-    // of different stages, so they stay in flight across a whole stage.
-    unsigned aMaskS[2] = {0u, 0u};
-    unsigned bMask = 0u;
-#pragma unroll
-    for (int i = 0; i < T::PB; ++i) {
-        const int r = bRow + T::B_RPP * i;
-        const bool ok = BWD ? (r < kBK && n0 + bSeg * 4 < p.DC) : (r < BN && n0 + r < p.DC);
-        if (ok) bMask |= 1u << i;
-    }
     // item q of a stage: q < PA is A-tile pass q, otherwise B-tile pass q - PA
     constexpr int kItems = T::PA + T::PB;
     constexpr int kGroups = kBK / 8;
     auto gload_item = [&](int q, f4 *ga, f4 *gb) __attribute__((always_inline)) {
         const int c0 = chunk * kBK;
         if (q < T::PA) {
-#if defined(EXP_SAMEADDR)
-            const int off = (aValid & (1u << q)) ? (aRow + 32 * q) * 32 + aSeg * 4 + (c0 & 0) : 0;
-#else
-            const int off = (aValid & (1u << q)) ? rBase[q] + tapOffA + c0 : 0;
-#endif
-            ga[q] = *reinterpret_cast<const f4 *>(p.A + (long long)off);
+            ga[q] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrcA, aOff[q], c0 * 4, 0));
         } else {
             const int i = q - T::PA;
-            const int r = bRow + T::B_RPP * i;
-            long long off;
-            if (BWD) off = (long long)(c0 + r) * wRowStride + tapOffB + n0 + bSeg * 4;
-            else off = (long long)(n0 + r) * wRowStride + tapOffB + c0 + bSeg * 4;
-            if (!(bMask & (1u << i))) off = 0;
-#if defined(EXP_SAMEADDR)
-            off = (r * 8 + bSeg) * 4;
-#endif
-            gb[i] = *reinterpret_cast<const f4 *>(p.B + off);
+            const int soff = BWD ? (c0 * wRowStride + tapOffB) * 4 : (tapOffB + c0) * 4;
+            gb[i] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrcB, bOff[i], soff, 0));
         }
     };
-    auto gload = [&](f4 *ga, f4 *gb, unsigned &aMask) __attribute__((always_inline)) {
-        aMask = aValid;
+    auto gload = [&](f4 *ga, f4 *gb) __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < kItems; ++q) gload_item(q, ga, gb);
     };
@@ -167,21 +161,20 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
         }
     };
 
-    auto lds_store_item = [&](int q, int buf, const f4 *ga, const f4 *gb, unsigned aMask) __attribute__((always_inline)) {
+    auto lds_store_item = [&](int q, int buf, const f4 *ga, const f4 *gb) __attribute__((always_inline)) {
         if (q < T::PA) {
             float *a = As + buf * T::A_STAGE;
-            *reinterpret_cast<f4 *>(a + (aRow + 32 * q) * LDA + aSeg * 4) = (aMask & (1u << q)) ? ga[q] : zero4;
+            *reinterpret_cast<f4 *>(a + (aRow + 32 * q) * LDA + aSeg * 4) = ga[q];
         } else {
             const int i = q - T::PA;
             float *b = Bs + buf * T::B_STAGE;
             const int r = bRow + T::B_RPP * i;
-            if (T::B_ROWS % T::B_RPP == 0 || r < T::B_ROWS)
-                *reinterpret_cast<f4 *>(b + r * T::LDB + bSeg * 4) = (bMask & (1u << i)) ? gb[i] : zero4;
+            if (T::B_ROWS % T::B_RPP == 0 || r < T::B_ROWS) *reinterpret_cast<f4 *>(b + r * T::LDB + bSeg * 4) = gb[i];
         }
     };
-    auto lds_store = [&](int buf, const f4 *ga, const f4 *gb, unsigned aMask) __attribute__((always_inline)) {
+    auto lds_store = [&](int buf, const f4 *ga, const f4 *gb) __attribute__((always_inline)) {
 #pragma unroll
-        for (int q = 0; q < kItems; ++q) lds_store_item(q, buf, ga, gb, aMask);
+        for (int q = 0; q < kItems; ++q) lds_store_item(q, buf, ga, gb);
     };
 
     // ---- accumulators -------------------------------------------------------------------
@@ -227,7 +220,6 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
         constexpr bool kTwoFrags = BM * BN < 128 * 128;
         f4 fa[kTwoFrags ? 2 : 1][T::MB], fb[kTwoFrags ? 2 : 1][T::NB];
         if (kTwoFrags) load_frag(a, b, 0, fa[0], fb[0]);
-        if (doLoad) aMaskS[ld] = aValid;
 #pragma unroll
         for (int jj = 0; jj < kGroups; ++jj) {
             const int cur = kTwoFrags ? (jj & 1) : 0;
@@ -240,9 +232,11 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
             for (int q = 0; q < kItems; ++q)
                 if (q % kGroups == jj) {
                     if (doLoad) gload_item(q, gaS[ld], gbS[ld]);
-                    if (doStore) lds_store_item(q, buf ^ 1, gaS[st], gbS[st], aMaskS[st]);
+                    if (doStore) lds_store_item(q, buf ^ 1, gaS[st], gbS[st]);
                 }
+#if !defined(EXP_INTERLEAVE)
             __builtin_amdgcn_sched_barrier(0);
+#endif
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
 #pragma unroll
@@ -251,6 +245,16 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
                     for (int j = 0; j < T::NB; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[cur][i][t], fb[cur][j][t], acc[i][j], 0, 0, 0);
             }
+#if defined(EXP_INTERLEAVE)
+            // ask the scheduler to slot the group's memory/VALU instructions between the MFMAs
+#pragma unroll
+            for (int k = 0; k < 4 * T::MB * T::NB; ++k) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);   // a few VALU
+                __builtin_amdgcn_sched_group_barrier(0x300, 1, 0);   // one LDS op
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
+            }
+#endif
             __builtin_amdgcn_sched_barrier(0);
         }
         if (doLoad) advance();
@@ -263,14 +267,14 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     if (it0 < it1) {
         const int n = it1 - it0;
         set_tap();
-        gload(gaS[0], gbS[0], aMaskS[0]);
+        gload(gaS[0], gbS[0]);
         advance();
         if (n > 1) {
-            gload(gaS[1], gbS[1], aMaskS[1]);
+            gload(gaS[1], gbS[1]);
             advance();
         }
         STAMP(2);
-        lds_store(0, gaS[0], gbS[0], aMaskS[0]);
+        lds_store(0, gaS[0], gbS[0]);
         __syncthreads();
         STAMP(3);
         int t = 0;
