@@ -20,7 +20,7 @@ thread_local char t_hipError[256] = "";
 
 constexpr long long kMaxElems = (1LL << 31) - 1;
 constexpr int kSmallMapPixels = 64;      // maps of at most 8x8 outputs use position-major rows
-constexpr int kMaxSplit = 256;
+constexpr int kMaxSplit = 1024;
 
 struct Plan {
     int variant = MI355CONV_VARIANT_DIRECT;
@@ -28,6 +28,7 @@ struct Plan {
     int split = 1;
     int posMajor = 0;
     int elem = 0;          // element-wise loader (channel counts the 16-byte loader cannot take)
+    int fast = 0;          // backward-weight: aligned-map kernel without accumulator folding
     int grid = 0;
     int tilesM = 0, tilesN = 0;
     int flushChunks = 16;
@@ -96,8 +97,8 @@ struct CostParams {
     double reduceUs;       // launch + ramp of the slice-reduce kernel
     double reduceBytesPerUs;
 };
-constexpr CostParams kGatherCost = {0.55, 8.8, 5.4, 9.9e6};
-constexpr CostParams kWgradCost = {0.70, 1.0, 10.0, 8.6e6};
+constexpr CostParams kGatherCost = {0.60, 5.6, 5.1, 8.9e6};
+constexpr CostParams kWgradCost = {0.60, 3.7, 10.0, 1.0e7};
 
 constexpr double kCuFlopPerUs = 157.3e6 / 256.0;   // fp32 MFMA FLOP per microsecond per CU
 constexpr size_t kMaxWorkspace = (size_t)1 << 30;
@@ -127,21 +128,22 @@ double launch_cost(const CostParams &k, const TileCand &c, long long tiles, doub
 
 // Best slice count for one candidate; returns the cost.
 double best_split(const CostParams &k, const TileCand &c, long long tiles, double avgStages, double maxStages,
-                  long long outElems, int *splitOut)
+                  long long outElems, int *splitOut, int minS = 1)
 {
     const int forced = g_forceSplit.load();
     int maxS = (int)(avgStages / 2.0);              // keep >= 2 stages per slice on average
     if (maxS > kMaxSplit) maxS = kMaxSplit;
     const long long wsPerSlice = pad4(outElems) * 4;
     if ((long long)maxS * wsPerSlice > (long long)kMaxWorkspace) maxS = (int)(kMaxWorkspace / wsPerSlice);
-    if (maxS < 1) maxS = 1;
+    if (maxS < minS) maxS = minS;
     if (forced > 0) {
         *splitOut = forced < maxS ? forced : maxS;
+        if (*splitOut < minS) *splitOut = minS;
         return launch_cost(k, c, tiles, avgStages, maxStages, *splitOut, outElems);
     }
     double best = 1e300;
     int bestS = 1;
-    for (int sp = 1; sp <= maxS; ++sp) {
+    for (int sp = minS; sp <= maxS; ++sp) {
         const double t = launch_cost(k, c, tiles, avgStages, maxStages, sp, outElems);
         if (t < best) { best = t; bestS = sp; }
     }
@@ -163,8 +165,8 @@ bool tile_compiled(int bm, int bn, bool gather)
     return (bm == 128 || bm == 64) && (bn == 128 || bn == 64);
 }
 
-const TileCand kGatherTiles[] = {{128, 128, 0.77, 2}, {128, 64, 0.76, 2}, {64, 64, 0.79, 4}, {128, 32, 0.60, 3}};
-const TileCand kWgradTiles[] = {{128, 128, 0.79, 2}, {64, 128, 0.68, 2}, {128, 64, 0.70, 2}, {64, 64, 0.60, 5}};
+const TileCand kGatherTiles[] = {{128, 128, 0.89, 2}, {128, 64, 0.85, 2}, {64, 64, 1.00, 4}, {128, 32, 0.70, 3}};
+const TileCand kWgradTiles[] = {{128, 128, 0.68, 1}, {64, 128, 0.82, 2}, {128, 64, 0.82, 2}, {64, 64, 0.86, 5}};
 
 bool forced_tile(int *bm, int *bn, bool gather)
 {
@@ -452,10 +454,19 @@ Plan plan_bwd_weight(const Shape &s)
     if (forced == MI355CONV_VARIANT_DIRECT || !eligible) return pl;
     pl.variant = MI355CONV_VARIANT_MFMA;
     pl.elem = s.IC % 4 != 0;
+    const int chunksAll = ceil_div(M, kBK);
+    const int ohow = s.OH * s.OW;
+    // fast kernel: rows of a 32-row stage always sit at the same place relative to its first pixel
+    const bool aligned = kBK % s.OW == 0 && (ohow % kBK == 0 || kBK % ohow == 0);
+    const int minSlices = ceil_div(chunksAll, kWgradFastStages);   // keeps fp32 chains at 512 products
+    pl.fast = !pl.elem && aligned && minSlices <= kMaxSplit &&
+              (long long)s.N * s.IH * s.IW * s.IC * 4 < (1LL << 31) && M * s.OC * 4 < (1LL << 31) &&
+              (long long)minSlices * pad4(pl.outElems) * 4 <= (long long)kMaxWorkspace;
+    // the fast kernel keeps 64-bit row/column validity masks in (oh,ow,n) order
+    const bool smallMap = (s.ph > 0 || s.pw > 0) && s.OH * s.OW <= kSmallMapPixels;
+    const int posMajor = resolve_order(smallMap, s.N % kBK == 0 && !pl.elem && (!pl.fast || (s.OH <= 64 && s.OW <= 64)));
     const long long Ktot = (long long)s.FH * s.FW * s.IC;
     const int chunks = ceil_div(M, kBK);
-    const bool smallMap = (s.ph > 0 || s.pw > 0) && s.OH * s.OW <= kSmallMapPixels;
-    const int posMajor = resolve_order(smallMap, s.N % kBK == 0 && !pl.elem);
     // fraction of (position, tap) pairs inside the image = share of stages a tile keeps
     double live = 1.0;
     if (posMajor) {
@@ -478,7 +489,8 @@ Plan plan_bwd_weight(const Shape &s)
         }
         const long long tiles = (long long)ceil_div(s.OC, c.bm) * ceil_div(Ktot, c.bn);
         int sp = 1;
-        const double t = best_split(kWgradCost, c, tiles, chunks * live, (double)chunks, pl.outElems, &sp);
+        const double t = best_split(kWgradCost, c, tiles, chunks * live, (double)chunks, pl.outElems, &sp,
+                                    pl.fast ? minSlices : 1);
         if (t < best) {
             best = t;
             pl.bm = c.bm;
@@ -689,7 +701,13 @@ int conv2d_bwd_weight(const float *X, const float *dY, float *dW, const conv2d_d
     w.xcdUnit = pl.tilesN;   // the column tiles of one slice read the same G and X rows
     w.M = s.N * s.OH * s.OW;
     w.flushChunks = pl.flushChunks;
-    hipError_t e = launch_wgrad(w, pl.bm, pl.bn, pl.elem != 0, pl.grid, st);
+    w.xBytes = (unsigned)((long long)s.N * s.IH * s.IW * s.IC * 4);
+    w.gBytes = (unsigned)((long long)w.M * s.OC * 4);
+    w.divOHOW = make_fastdiv((unsigned)(s.OH * s.OW));
+    w.divOW = make_fastdiv((unsigned)s.OW);
+    w.divN = make_fastdiv((unsigned)s.N);
+    hipError_t e = pl.fast ? launch_wgrad_fast(w, pl.bm, pl.bn, pl.grid, st)
+                           : launch_wgrad(w, pl.bm, pl.bn, pl.elem != 0, pl.grid, st);
     if (e != hipSuccess) return hip_fail(e);
     if (pl.split > 1) {
         e = launch_slice_reduce(static_cast<const float *>(ws), dW, pl.outElems, pl.split, pl.sliceStride, st);

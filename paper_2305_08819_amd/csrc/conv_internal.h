@@ -91,6 +91,9 @@ struct WgradParams {
     int xcdUnit;          // consecutive logical workgroup ids kept on one XCD
     int M;                // N*OH*OW
     int flushChunks;      // fold the running accumulator into a second one every this many stages
+    // fast variant only
+    unsigned xBytes, gBytes;          // tensor sizes in bytes (below 2^31): buffer-load range checks
+    FastDiv divOHOW, divOW, divN;     // by OH*OW, OW and N
 };
 
 // MI355X spreads consecutive workgroup ids round-robin over its 8 XCDs, each with its own
@@ -122,5 +125,9 @@ hipError_t launch_gather_gemm(const GatherGemmParams &p, bool bwdData, int bm, i
 // same tiles (except 128x128), element-wise loader: any channel counts
 hipError_t launch_gather_elem(const GatherGemmParams &p, bool bwdData, int bm, int bn, int grid, hipStream_t st);
 hipError_t launch_wgrad(const WgradParams &p, int bm, int bn, bool xElem, int grid, hipStream_t st);
+// Aligned maps (OW divides 32; OH*OW divides or is a multiple of 32), IC % 4 == 0, OC % 4 == 0,
+// tensors below 2^31 bytes, at most kWgradFastStages stages per slice (no accumulator folding).
+hipError_t launch_wgrad_fast(const WgradParams &p, int bm, int bn, int grid, hipStream_t st);
+constexpr int kWgradFastStages = 16;
 
 }  // namespace mi355conv
