@@ -27,6 +27,11 @@ import workloads as wl  # noqa: E402
 PEAK_FP32_MFMA_TFLOPS = 157.3   # 256 CU x 256 FLOP/clk x 2.4 GHz (published dense fp32 matrix peak)
 PEAK_HBM_GBS = 8000.0
 OPS = ("fwd", "bwd_data", "bwd_weight")
+# HBM bytes per operator launch of the default workload (C2), from FETCH_SIZE + WRITE_SIZE scaled by a
+# 256 MiB copy (profiles/bench_C2_kernel_trace.md); bwd_weight = main kernel + slice reduce.
+MEASURED_TRAFFIC_BYTES = {"C2": {"fwd": 80.8e6, "bwd_data": 78.9e6, "bwd_weight": 115.6e6 + 21.3e6}}
+KERNEL_OF_OP = {"fwd": "gather_gemm_kernel<fwd>", "bwd_data": "gather_gemm_kernel<bwd_data>",
+                "bwd_weight": "wgrad_fast_kernel + slice_reduce_kernel"}
 
 
 def log(*a):
@@ -143,6 +148,8 @@ def main():
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--table", nargs="*", default=None, metavar="CFG")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run a plain 256 MiB device copy 5 times (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (--gpus 1); the hot path has no "
@@ -153,6 +160,16 @@ def main():
     mc.load()   # fails loudly if the HIP library is not built
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+
+    if args.calibrate_copy:
+        # known traffic: 256 MiB read + 256 MiB written per copy; used to scale FETCH_SIZE / WRITE_SIZE
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_each_way": src.numel() * 4, "copies": 5}))
+        return
 
     if args.table is not None:
         names = args.table or list(wl.CONFIGS)
@@ -195,9 +212,12 @@ def main():
                         "pct_peak": round(100 * layer.flops / per_op[op] / 1e9 / PEAK_FP32_MFMA_TFLOPS, 1),
                         "split": r.plans[op].split, "tile": [r.plans[op].tile_m, r.plans[op].tile_n]}
                    for op in OPS},
-        "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2),
-                     "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None},
+        # achieved = nominal FLOP of the slowest operator / its event-timed duration; for a sliced
+        # operator that duration includes the slice-reduce kernel, so the figure is conservative
+        "roofline": {"bound": "mfma", "kernel": KERNEL_OF_OP[dom], "operator": dom,
+                     "achieved": round(achieved, 2), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(layer.name, {}).get(dom)},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layer, r.host)
