@@ -10,6 +10,7 @@ namespace mi355conv {
 
 typedef float float16v __attribute__((ext_vector_type(16)));
 typedef float f4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers
+typedef const volatile __attribute__((address_space(3))) float *lds_cvptr;
 
 constexpr int LDA = kBK + 4;   // LDS row pitch (floats) of a [row][k] tile: 16-byte aligned, bank-skewed
 constexpr int kInvalidCoord = -(1 << 28);

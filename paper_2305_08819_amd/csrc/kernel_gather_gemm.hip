@@ -196,7 +196,9 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
 #pragma unroll
         for (int j = 0; j < T::NB; ++j) {
             if (BWD) {
-                const float *q = b + (jj * 8) * T::LDB + j * 32;
+                // volatile LDS pointer: keeps four single reads with immediate offsets; paired
+                // two-address reads would each need a VALU add, which costs matrix time
+                lds_cvptr q = (lds_cvptr)(b + (jj * 8) * T::LDB + j * 32);
                 fb[j] = f4{q[0], q[T::LDB], q[2 * T::LDB], q[3 * T::LDB]};
             } else {
                 fb[j] = *reinterpret_cast<const f4 *>(b + j * 32 * T::LDB + jj * 8);

@@ -170,7 +170,10 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : 2) void wgra
     constexpr int kItems = T::PG + T::PX;
     constexpr int kGroups = kBK / 8;
     auto gload_item = [&](int q, f4 *gg, f4 *gx) __attribute__((always_inline)) {
-        if (q < T::PG) gg[q] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrcG, gVoff[q], gSoff, 0));
+        // gSoff is uniform; saying so keeps it in an SGPR instead of a per-lane loop over its values
+        if (q < T::PG)
+            gg[q] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrcG, gVoff[q],
+                                                                                __builtin_amdgcn_readfirstlane(gSoff), 0));
         else gx[q - T::PG] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrcX, xVoff[q - T::PG], 0, 0));
     };
     auto lds_store_item = [&](int q, int buf, const f4 *gg, const f4 *gx) __attribute__((always_inline)) {
@@ -191,15 +194,17 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : 2) void wgra
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
 
+    // volatile: the compiler would otherwise pair these into two-address LDS reads, each pair
+    // needing a VALU add for its base - and VALU instructions cost matrix time, LDS reads do not
     auto load_frag = [&](const float *g, const float *x, int jj, f4 *fa, f4 *fb) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < T::MB; ++i) {
-            const float *q = g + (jj * 8) * T::LDG + i * 32;
+            lds_cvptr q = (lds_cvptr)(g + (jj * 8) * T::LDG + i * 32);
             fa[i] = f4{q[0], q[T::LDG], q[2 * T::LDG], q[3 * T::LDG]};
         }
 #pragma unroll
         for (int j = 0; j < T::NB; ++j) {
-            const float *q = x + (jj * 8) * T::LDX + j * 32;
+            lds_cvptr q = (lds_cvptr)(x + (jj * 8) * T::LDX + j * 32);
             fb[j] = f4{q[0], q[T::LDX], q[2 * T::LDX], q[3 * T::LDX]};
         }
     };
