@@ -98,7 +98,7 @@ struct CostParams {
     double reduceBytesPerUs;
 };
 constexpr CostParams kGatherCost = {0.60, 5.6, 5.1, 8.9e6};
-constexpr CostParams kWgradCost = {0.60, 3.7, 10.0, 1.0e7};
+constexpr CostParams kWgradCost = {0.74, 1.0, 7.6, 6.0e6};
 
 constexpr double kCuFlopPerUs = 157.3e6 / 256.0;   // fp32 MFMA FLOP per microsecond per CU
 constexpr size_t kMaxWorkspace = (size_t)1 << 30;
@@ -166,7 +166,7 @@ bool tile_compiled(int bm, int bn, bool gather)
 }
 
 const TileCand kGatherTiles[] = {{128, 128, 0.89, 2}, {128, 64, 0.85, 2}, {64, 64, 1.00, 4}, {128, 32, 0.70, 3}};
-const TileCand kWgradTiles[] = {{128, 128, 0.68, 1}, {64, 128, 0.82, 2}, {128, 64, 0.82, 2}, {64, 64, 0.86, 5}};
+const TileCand kWgradTiles[] = {{128, 128, 0.85, 1}, {64, 128, 0.82, 5}, {128, 64, 0.83, 5}, {64, 64, 0.84, 5}};
 
 bool forced_tile(int *bm, int *bn, bool gather)
 {
@@ -458,10 +458,8 @@ Plan plan_bwd_weight(const Shape &s)
     const int ohow = s.OH * s.OW;
     // fast kernel: rows of a 32-row stage always sit at the same place relative to its first pixel
     const bool aligned = kBK % s.OW == 0 && (ohow % kBK == 0 || kBK % ohow == 0);
-    const int minSlices = ceil_div(chunksAll, kWgradFastStages);   // keeps fp32 chains at 512 products
-    pl.fast = !pl.elem && aligned && minSlices <= kMaxSplit &&
-              (long long)s.N * s.IH * s.IW * s.IC * 4 < (1LL << 31) && M * s.OC * 4 < (1LL << 31) &&
-              (long long)minSlices * pad4(pl.outElems) * 4 <= (long long)kMaxWorkspace;
+    pl.fast = !pl.elem && aligned && chunksAll >= 1 &&
+              (long long)s.N * s.IH * s.IW * s.IC * 4 < (1LL << 31) && M * s.OC * 4 < (1LL << 31);
     // the fast kernel keeps 64-bit row/column validity masks in (oh,ow,n) order
     const bool smallMap = (s.ph > 0 || s.pw > 0) && s.OH * s.OW <= kSmallMapPixels;
     const int posMajor = resolve_order(smallMap, s.N % kBK == 0 && !pl.elem && (!pl.fast || (s.OH <= 64 && s.OW <= 64)));
@@ -489,8 +487,7 @@ Plan plan_bwd_weight(const Shape &s)
         }
         const long long tiles = (long long)ceil_div(s.OC, c.bm) * ceil_div(Ktot, c.bn);
         int sp = 1;
-        const double t = best_split(kWgradCost, c, tiles, chunks * live, (double)chunks, pl.outElems, &sp,
-                                    pl.fast ? minSlices : 1);
+        const double t = best_split(kWgradCost, c, tiles, chunks * live, (double)chunks, pl.outElems, &sp);
         if (t < best) {
             best = t;
             pl.bm = c.bm;
@@ -706,6 +703,10 @@ int conv2d_bwd_weight(const float *X, const float *dY, float *dW, const conv2d_d
     w.divOHOW = make_fastdiv((unsigned)(s.OH * s.OW));
     w.divOW = make_fastdiv((unsigned)s.OW);
     w.divN = make_fastdiv((unsigned)s.N);
+    w.divIC = make_fastdiv((unsigned)s.IC);
+    w.divFW = make_fastdiv((unsigned)s.FW);
+    w.divTilesN = make_fastdiv((unsigned)pl.tilesN);
+    w.divSplit = make_fastdiv((unsigned)pl.split);
     hipError_t e = pl.fast ? launch_wgrad_fast(w, pl.bm, pl.bn, pl.grid, st)
                            : launch_wgrad(w, pl.bm, pl.bn, pl.elem != 0, pl.grid, st);
     if (e != hipSuccess) return hip_fail(e);

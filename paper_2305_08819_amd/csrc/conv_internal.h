@@ -94,6 +94,7 @@ struct WgradParams {
     // fast variant only
     unsigned xBytes, gBytes;          // tensor sizes in bytes (below 2^31): buffer-load range checks
     FastDiv divOHOW, divOW, divN;     // by OH*OW, OW and N
+    FastDiv divIC, divFW, divTilesN, divSplit;
 };
 
 // MI355X spreads consecutive workgroup ids round-robin over its 8 XCDs, each with its own
@@ -126,8 +127,7 @@ hipError_t launch_gather_gemm(const GatherGemmParams &p, bool bwdData, int bm, i
 hipError_t launch_gather_elem(const GatherGemmParams &p, bool bwdData, int bm, int bn, int grid, hipStream_t st);
 hipError_t launch_wgrad(const WgradParams &p, int bm, int bn, bool xElem, int grid, hipStream_t st);
 // Aligned maps (OW divides 32; OH*OW divides or is a multiple of 32), IC % 4 == 0, OC % 4 == 0,
-// tensors below 2^31 bytes, at most kWgradFastStages stages per slice (no accumulator folding).
+// tensors below 2^31 bytes.
 hipError_t launch_wgrad_fast(const WgradParams &p, int bm, int bn, int grid, hipStream_t st);
-constexpr int kWgradFastStages = 16;
 
 }  // namespace mi355conv

@@ -19,8 +19,13 @@
 //    are padding for every tap of the tile are skipped (small-feature-map operator, Sec. IV).
 //  * Loads run two stages ahead through two register sets; memory instructions are spread
 //    between MFMA groups; one barrier per stage.
-// No accumulator folding: the host keeps every slice at or below kWgradFastStages stages
-// (512 products per fp32 chain) by choosing enough slices.
+// Accuracy: the accumulator is folded into a second one every `flushChunks` stages (512
+// products), so no fp32 chain is longer than that however long the slice is.
+#include <hip/hip_runtime.h>
+#if defined(EXP_STAMPS)
+namespace mi355conv { __device__ unsigned long long g_wstamps[16384 * 8]; }
+#define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 16384) mi355conv::g_wstamps[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#endif
 #include "gather_common.h"
 
 namespace mi355conv {
@@ -39,19 +44,20 @@ struct WF {
 }  // namespace
 
 template <int BM, int BN>
-__global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : 2) void wgrad_fast_kernel(const WgradParams p)
+__global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 64 * 64) ? 4 : 2) void wgrad_fast_kernel(const WgradParams p)
 {
     using T = WF<BM, BN>;
     extern __shared__ f4 smem_raw[];
     float *Gs = reinterpret_cast<float *>(smem_raw);
     float *Xs = Gs + 2 * T::G_STAGE;
 
+    STAMP(0);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int bid = xcd_remap(blockIdx.x, gridDim.x, p.xcdUnit);
-    const int tn = bid % p.tilesN;
-    bid /= p.tilesN;
-    const int slice = bid % p.split;
-    const int tmo = bid / p.split;
+    const int rest = (int)fast_div((unsigned)bid, p.divTilesN);
+    const int tn = bid - rest * p.tilesN;
+    const int tmo = (int)fast_div((unsigned)rest, p.divSplit);
+    const int slice = rest - tmo * p.split;
     const int oc0 = tmo * BM, col0 = tn * BN;
     const int Ktot = p.FH * p.FW * p.IC;
     const int ohow = p.OH * p.OW;
@@ -72,9 +78,9 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : 2) void wgra
     const int gOc = oc0 + gSeg * 4;
     const int xCol = col0 + xSeg * 4;
     const bool xOk = xCol < Ktot;
-    const int xTap = xOk ? xCol / p.IC : 0;
+    const int xTap = xOk ? (int)fast_div((unsigned)xCol, p.divIC) : 0;
     const int xIc = xCol - xTap * p.IC;
-    const int xFh = xTap / p.FW, xFw = xTap - xFh * p.FW;
+    const int xFh = (int)fast_div((unsigned)xTap, p.divFW), xFw = xTap - xFh * p.FW;
 
     int gVoff[T::PG];                       // bytes, fixed
 #pragma unroll
@@ -105,10 +111,10 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : 2) void wgra
             const int r = xRow + T::X_RPP * i;
             int dn = 0, rr = r;
             if (ohow < kBK) {
-                dn = r / ohow;
+                dn = (int)fast_div((unsigned)r, p.divOHOW);
                 rr = r - dn * ohow;
             }
-            const int doh = rr / p.OW, ow = rr - doh * p.OW;
+            const int doh = (int)fast_div((unsigned)rr, p.divOW), ow = rr - doh * p.OW;
             const int iw = ow * p.sw - p.pw + xFw;
             xHBase[i] = doh * p.sh - p.ph + xFh;
             xDn[i] = dn;
@@ -118,15 +124,15 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : 2) void wgra
     }
 
     // taps covered by this tile (for the stage-skip test)
-    const int tapLo = col0 / p.IC;
+    const int tapLo = (int)fast_div((unsigned)col0, p.divIC);
     const int lastCol = (col0 + BN - 1 < Ktot - 1) ? col0 + BN - 1 : Ktot - 1;
-    const int tapHi = lastCol / p.IC;
+    const int tapHi = (int)fast_div((unsigned)lastCol, p.divIC);
     auto stage_live = [&](int ch) __attribute__((always_inline)) -> bool {
         if (!p.posMajor) return true;
         const int pos = (int)fast_div((unsigned)(ch * kBK), p.divN);
         const int oh = (int)fast_div((unsigned)pos, p.divOW), ow = pos - oh * p.OW;
         for (int t = tapLo; t <= tapHi; ++t) {
-            const int fh = t / p.FW, fw = t - fh * p.FW;
+            const int fh = (int)fast_div((unsigned)t, p.divFW), fw = t - fh * p.FW;
             if ((unsigned)(oh * p.sh - p.ph + fh) < (unsigned)p.IH && (unsigned)(ow * p.sw - p.pw + fw) < (unsigned)p.IW)
                 return true;
         }
@@ -183,13 +189,31 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : 2) void wgra
             *reinterpret_cast<f4 *>(Xs + buf * T::X_STAGE + (xRow + T::X_RPP * (q - T::PG)) * T::LDX + xSeg * 4) = gx[q - T::PG];
     };
 
-    float16v acc[T::MB][T::NB];
+    float16v acc[T::MB][T::NB], acc2[T::MB][T::NB];
 #pragma unroll
     for (int i = 0; i < T::MB; ++i)
 #pragma unroll
         for (int j = 0; j < T::NB; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+            for (int r = 0; r < 16; ++r) {
+                acc[i][j][r] = 0.f;
+                acc2[i][j][r] = 0.f;
+            }
+    int sinceFlush = 0;
+    auto maybe_flush = [&]() __attribute__((always_inline)) {
+        if (++sinceFlush == p.flushChunks) {
+            sinceFlush = 0;
+#pragma unroll
+            for (int i = 0; i < T::MB; ++i)
+#pragma unroll
+                for (int j = 0; j < T::NB; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        acc2[i][j][r] += acc[i][j][r];
+                        acc[i][j][r] = 0.f;
+                    }
+        }
+    };
 
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
@@ -214,7 +238,7 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : 2) void wgra
     auto stage = [&](int buf, bool doLoad, int ld, bool doStore, int st) __attribute__((always_inline)) {
         const float *g = Gs + buf * T::G_STAGE + (lh * 4) * T::LDG + wm * T::WTM + l32;
         const float *x = Xs + buf * T::X_STAGE + (lh * 4) * T::LDX + wn * T::WTN + l32;
-        constexpr bool kTwoFrags = BM * BN < 128 * 128;
+        constexpr bool kTwoFrags = BM * BN < 128 * 128 && BM * BN > 64 * 64;   // register budget of the smallest and largest tile
         f4 fa[kTwoFrags ? 2 : 1][T::MB], fb[kTwoFrags ? 2 : 1][T::NB];
         if (kTwoFrags) load_frag(g, x, 0, fa[0], fb[0]);
 #pragma unroll
@@ -245,6 +269,7 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : 2) void wgra
 
     // ---- main loop over the live stages of this slice --------------------------------------------
     // c0 is multiplied now, c1 sits in registers (other set), c2 is loaded during this stage.
+    STAMP(1);
     int c0 = next_live(ch0);
     if (c0 < ch1) {
         set_stage(c0);
@@ -259,6 +284,7 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : 2) void wgra
 #pragma unroll
         for (int q = 0; q < kItems; ++q) lds_store_item(q, 0, ggS[0], gxS[0]);
         __syncthreads();
+        STAMP(2);
         for (;;) {
             // two stages per trip so that buffer and register-set indices are compile-time
             int c2 = c1 < ch1 ? next_live(c1 + 1) : ch1;
@@ -266,9 +292,11 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : 2) void wgra
             if (c3 < ch1) {   // steady state: no branch around memory instructions
                 set_stage(c2);
                 stage(0, true, 0, true, 1);
+                maybe_flush();
                 __syncthreads();
                 set_stage(c3);
                 stage(1, true, 1, true, 0);
+                maybe_flush();
                 __syncthreads();
                 c0 = c2;
                 c1 = c3;
@@ -277,9 +305,11 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : 2) void wgra
             // tail: c0 (in LDS 0), maybe c1 (registers 1), maybe c2
             if (c2 < ch1) set_stage(c2);
             stage(0, c2 < ch1, 0, c1 < ch1, 1);
+            maybe_flush();
             __syncthreads();
             if (c1 >= ch1) break;
             stage(1, false, 1, c2 < ch1, 0);
+            maybe_flush();
             __syncthreads();
             if (c2 >= ch1) break;
             stage(0, false, 0, false, 1);
@@ -287,6 +317,7 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : 2) void wgra
         }
     }
 
+    STAMP(3);
     float *C = p.C + (long long)slice * p.sliceStride;
 #pragma unroll
     for (int i = 0; i < T::MB; ++i)
@@ -296,10 +327,18 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : 2) void wgra
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int oc = oc0 + wm * T::WTM + i * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
-                if (oc < p.OC && col < Ktot) C[oc * Ktot + col] = acc[i][j][r];
+                if (oc < p.OC && col < Ktot) C[oc * Ktot + col] = acc2[i][j][r] + acc[i][j][r];
             }
         }
+    STAMP(4);
 }
+
+#if defined(EXP_STAMPS)
+extern "C" int exp_read_wstamps(unsigned long long *host, size_t count)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_wstamps), count * sizeof(unsigned long long));
+}
+#endif
 
 template <int BM, int BN>
 static hipError_t launch_fast_one(const WgradParams &p, int grid, hipStream_t st)
