@@ -77,19 +77,32 @@ class LayerRunner:
         for op in OPS:
             self.run(op)
 
-    def event_ms(self, fn, launches, warm):
-        """Average milliseconds per call of fn between two events on the launch stream."""
+    def event_ms(self, fn, launches=100, warm=20, batches=5):
+        """Median over `batches` of the average milliseconds per call of fn, each batch `launches`
+        calls between two events on the launch stream, after `warm` untimed calls."""
         torch = self.torch
         for _ in range(warm):
             fn()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(launches):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / launches
+        out = []
+        for _ in range(batches):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(launches):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            out.append(e0.elapsed_time(e1) / launches)
+        return sorted(out)[len(out) // 2]
+
+    def spin_up(self, seconds=0.2):
+        """Keep the GPU busy until its clock governor has settled: the shader clock climbs for
+        tens of milliseconds after an idle period, and kernels timed before that run 10-15 % slow."""
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < seconds:
+            for _ in range(20):
+                self.step()
+            self.torch.cuda.synchronize()
 
 
 def fwd_bytes(l):
@@ -113,7 +126,7 @@ def cpu_baseline(layer, host, repeats=3):
                       % (repeats, layer.name, dt)}
 
 
-def table(mc, torch, cfg_names, launches=30, warm=5):
+def table(mc, torch, cfg_names):
     rows = []
     seen = set()
     log("%-5s %-10s %9s %9s %7s %7s  %s" % ("layer", "op", "ms", "TFLOP/s", "%peak", "GB/s", "plan"))
@@ -123,8 +136,10 @@ def table(mc, torch, cfg_names, launches=30, warm=5):
                 continue
             seen.add(layer.name)
             r = LayerRunner(layer, mc, torch, random_fill=True)
+            if not rows:
+                r.spin_up()
             for op in OPS:
-                ms = r.event_ms(lambda: r.run(op), launches, warm)
+                ms = r.event_ms(lambda: r.run(op))
                 tf = layer.flops / ms / 1e9
                 pl = r.plans[op]
                 plan = "v%d %dx%d s%d pm%d g%d" % (pl.variant, pl.tile_m, pl.tile_n, pl.split,
@@ -143,8 +158,8 @@ def table(mc, torch, cfg_names, launches=30, warm=5):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--table", nargs="*", default=None, metavar="CFG")
@@ -180,6 +195,7 @@ def main():
     layer = {l.name: l for l in wl.all_layers()}[args.workload]
     r = LayerRunner(layer, mc, torch)
 
+    r.spin_up()          # clock governor settled before anything is timed
     for _ in range(args.warmup):
         r.step()
     torch.cuda.synchronize()
@@ -193,7 +209,7 @@ def main():
 
     # per-operator event timing (each operator alone on the launch stream); the slowest is the
     # dominant kernel of the step
-    per_op = {op: r.event_ms(lambda op=op: r.run(op), args.steps, args.warmup) for op in OPS}
+    per_op = {op: r.event_ms(lambda op=op: r.run(op)) for op in OPS}
     dom = max(per_op, key=per_op.get)
     achieved = layer.flops / per_op[dom] / 1e9
     out = {

@@ -460,9 +460,9 @@ Plan plan_bwd_weight(const Shape &s)
     const bool aligned = kBK % s.OW == 0 && (ohow % kBK == 0 || kBK % ohow == 0);
     pl.fast = !pl.elem && aligned && chunksAll >= 1 &&
               (long long)s.N * s.IH * s.IW * s.IC * 4 < (1LL << 31) && M * s.OC * 4 < (1LL << 31);
-    // the fast kernel keeps 64-bit row/column validity masks in (oh,ow,n) order
+    // the fast kernel keeps a 64-bit mask of output positions in (oh,ow,n) order
     const bool smallMap = (s.ph > 0 || s.pw > 0) && s.OH * s.OW <= kSmallMapPixels;
-    const int posMajor = resolve_order(smallMap, s.N % kBK == 0 && !pl.elem && (!pl.fast || (s.OH <= 64 && s.OW <= 64)));
+    const int posMajor = resolve_order(smallMap, s.N % kBK == 0 && !pl.elem && (!pl.fast || ohow <= 64));
     const long long Ktot = (long long)s.FH * s.FW * s.IC;
     const int chunks = ceil_div(M, kBK);
     // fraction of (position, tap) pairs inside the image = share of stages a tile keeps

@@ -14,11 +14,13 @@
 //  * G rows are consecutive in memory: fixed VGPR offset + per-stage SGPR offset, no VALU.
 //  * Loads are raw buffer loads: rows past the end or in the padding get an out-of-range
 //    offset and read zeros, so there is no branch and no zero-select.
-//  * With (oh,ow,n) row order a stage sits on one output position; each thread keeps a 64-bit
-//    mask of the positions where its filter tap is inside the image, and whole stages that
-//    are padding for every tap of the tile are skipped (small-feature-map operator, Sec. IV).
+//  * With (oh,ow,n) row order (maps of at most 64 positions) a stage sits on one output
+//    position; each thread keeps a 64-bit mask of the positions where its filter tap is inside
+//    the image, and whole stages that are padding for every tap of the tile are skipped with
+//    a find-first-set on the tile's mask (small-feature-map operator, Sec. IV).
+//  * The row order is a template parameter, so the loop carries no branch on it.
 //  * Loads run two stages ahead through two register sets; memory instructions are spread
-//    between MFMA groups; one barrier per stage.
+//    between MFMA steps; fragments are read three MFMA steps ahead; one barrier per stage.
 // Accuracy: the accumulator is folded into a second one every `flushChunks` stages (512
 // products), so no fp32 chain is longer than that however long the slice is.
 #include <hip/hip_runtime.h>
@@ -43,8 +45,13 @@ struct WF {
 };
 }  // namespace
 
-template <int BM, int BN>
-__global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 64 * 64) ? 4 : 2) void wgrad_fast_kernel(const WgradParams p)
+#ifndef WF_OCC64
+#define WF_OCC64 4
+#endif
+// PM: rows in (oh, ow, n) order with N a multiple of 32 and OH*OW <= 64, so that a stage sits on
+// one output position and positions fit 64-bit masks.
+template <int BM, int BN, bool PM>
+__global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 64 * 64) ? WF_OCC64 : 2) void wgrad_fast_kernel(const WgradParams p)
 {
     using T = WF<BM, BN>;
     extern __shared__ f4 smem_raw[];
@@ -52,6 +59,13 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
     float *Xs = Gs + 2 * T::G_STAGE;
 
     STAMP(0);
+#if defined(EXP_STAMPS)
+    if (threadIdx.x == 0 && blockIdx.x < 16384) {
+        g_wstamps[blockIdx.x * 8 + 5] = __builtin_amdgcn_s_getreg((31 << 11) | 4);    // HW_ID
+        g_wstamps[blockIdx.x * 8 + 6] = __builtin_amdgcn_s_getreg((31 << 11) | 20);   // XCC_ID
+    }
+    const long long expClk0 = clock64();
+#endif
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int bid = xcd_remap(blockIdx.x, gridDim.x, p.xcdUnit);
     const int rest = (int)fast_div((unsigned)bid, p.divTilesN);
@@ -86,25 +100,36 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
 #pragma unroll
     for (int i = 0; i < T::PG; ++i) {
         const int r = gRow + T::G_RPP * i;
-        const int pixel = p.posMajor ? r * ohow : r;   // (y,x,n) order: row r of a stage is image nb + r
+        const int pixel = PM ? r * ohow : r;   // (oh,ow,n) order: row r of a stage is image nb + r
         gVoff[i] = gOc < p.OC ? (pixel * p.OC + gOc) * 4 : kOutOfRange;
     }
-    // X: element offset of the thread's part, row-validity inputs
-    int xPart[T::PX], xHBase[T::PX], xDn[T::PX];   // xHBase = far out of range where the column is never valid
-    // (y,x,n) order: output rows / columns at which this thread's tap is inside the image
-    unsigned long long hMask = 0ull, wMask = 0ull;
-    if (p.posMajor) {
+    // X: element offset of the thread's part of the address; validity inputs.
+    // Rows past the last image need no test: their addresses lie past the end of X and of G.
+    int xPart[T::PX];
+    int xHBase[T::PX];                      // !PM: input row relative to the stage's first one; far out of range
+                                            //      where the thread's column is never inside the image
+    unsigned long long liveMask = 0ull;     // PM: positions at which this thread's tap is inside the image
+    unsigned long long tileLive = ~0ull;    // PM: positions at which any tap of the tile is (uniform)
+    if constexpr (PM) {
 #pragma unroll
         for (int i = 0; i < T::PX; ++i) {
             const int r = xRow + T::X_RPP * i;
             xPart[i] = (r * p.IH * p.IW + xFh * p.IW + xFw) * p.IC + xIc;
             xHBase[i] = 0;
-            xDn[i] = 0;
         }
-        for (int oh = 0; oh < p.OH; ++oh)
-            if ((unsigned)(oh * p.sh - p.ph + xFh) < (unsigned)p.IH) hMask |= 1ull << oh;
+        unsigned long long wMask = 0ull;
         for (int ow = 0; ow < p.OW; ++ow)
             if ((unsigned)(ow * p.sw - p.pw + xFw) < (unsigned)p.IW) wMask |= 1ull << ow;
+        for (int oh = 0; oh < p.OH; ++oh)
+            if (xOk && (unsigned)(oh * p.sh - p.ph + xFh) < (unsigned)p.IH) liveMask |= wMask << (oh * p.OW);
+        // every wave holds all column segments of the tile in its first X_TPR lanes
+        unsigned lo = 0u, hi = 0u;
+#pragma unroll
+        for (int l = 0; l < T::X_TPR; ++l) {
+            lo |= (unsigned)__builtin_amdgcn_readlane((int)(unsigned)liveMask, l);
+            hi |= (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(liveMask >> 32), l);
+        }
+        tileLive = ((unsigned long long)hi << 32) | lo;
     } else {
 #pragma unroll
         for (int i = 0; i < T::PX; ++i) {
@@ -117,64 +142,78 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
             const int doh = (int)fast_div((unsigned)rr, p.divOW), ow = rr - doh * p.OW;
             const int iw = ow * p.sw - p.pw + xFw;
             xHBase[i] = doh * p.sh - p.ph + xFh;
-            xDn[i] = dn;
             xPart[i] = ((dn * p.IH + xHBase[i]) * p.IW + iw) * p.IC + xIc;   // may be negative
             if (!(xOk && (unsigned)iw < (unsigned)p.IW)) xHBase[i] = kInvalidCoord;
         }
     }
 
-    // taps covered by this tile (for the stage-skip test)
-    const int tapLo = (int)fast_div((unsigned)col0, p.divIC);
-    const int lastCol = (col0 + BN - 1 < Ktot - 1) ? col0 + BN - 1 : Ktot - 1;
-    const int tapHi = (int)fast_div((unsigned)lastCol, p.divIC);
-    auto stage_live = [&](int ch) __attribute__((always_inline)) -> bool {
-        if (!p.posMajor) return true;
-        const int pos = (int)fast_div((unsigned)(ch * kBK), p.divN);
-        const int oh = (int)fast_div((unsigned)pos, p.divOW), ow = pos - oh * p.OW;
-        for (int t = tapLo; t <= tapHi; ++t) {
-            const int fh = (int)fast_div((unsigned)t, p.divFW), fw = t - fh * p.FW;
-            if ((unsigned)(oh * p.sh - p.ph + fh) < (unsigned)p.IH && (unsigned)(ow * p.sw - p.pw + fw) < (unsigned)p.IW)
-                return true;
-        }
-        return false;
-    };
+    // First stage at or after ch that has work for this tile (uniform, branch-free).
+    const int chunksPerPos = p.N / kBK;
     auto next_live = [&](int ch) __attribute__((always_inline)) -> int {
-        while (ch < ch1 && !stage_live(ch)) ++ch;
-        return ch;
+        if constexpr (!PM) {
+            return ch < ch1 ? ch : ch1;
+        } else {
+            int pos = (int)fast_div((unsigned)(ch * kBK), p.divN);
+            pos = pos < 63 ? pos : 63;
+            const unsigned long long rem = tileLive >> pos;
+            const int skip = rem ? __builtin_ctzll(rem) : 64;
+            const int nch = skip == 0 ? ch : (pos + skip) * chunksPerPos;
+            return nch < ch1 ? nch : ch1;
+        }
     };
 
     // ---- stage cursor for the loads: uniform part of the addresses ------------------------------
+    // Computed in four pieces, so that the steady-state loop can spread them over four MFMA steps
+    // instead of leaving one long run of ALU work between two MFMAs.
     int gSoff = 0;                 // bytes
-    int xVoff[T::PX];              // bytes, recomputed per stage (4 VALU each)
-    auto set_stage = [&](int ch) __attribute__((always_inline)) {
-        const int m0 = ch * kBK;
-        if (p.posMajor) {
-            const int pos = (int)fast_div((unsigned)m0, p.divN);
-            const int nb = m0 - pos * p.N;
-            const int oh = (int)fast_div((unsigned)pos, p.divOW), ow = pos - oh * p.OW;
-            gSoff = (nb * ohow + pos) * p.OC * 4;
-            const int uni = ((nb * p.IH + oh * p.sh - p.ph) * p.IW + ow * p.sw - p.pw) * p.IC;
-            const bool live = ((hMask >> oh) & (wMask >> ow) & 1ull) != 0;
+    int xVoff[T::PX];              // bytes, recomputed per stage
+    int curA = 0, curB = 0, curUni = 0;   // uniform intermediates handed from piece to piece
+    auto set_piece = [&](int piece, int ch) __attribute__((always_inline)) {
+        if constexpr (PM) {
+            if (piece == 0) {
+                const int m0 = ch * kBK;
+                curA = (int)fast_div((unsigned)m0, p.divN);          // output position
+                curB = m0 - curA * p.N;                               // first image of the stage
+            } else if (piece == 1) {
+                const int oh = (int)fast_div((unsigned)curA, p.divOW), ow = curA - oh * p.OW;
+                gSoff = (curB * ohow + curA) * p.OC * 4;
+                curUni = ((curB * p.IH + oh * p.sh - p.ph) * p.IW + ow * p.sw - p.pw) * p.IC;
+            } else {
+                const bool live = ((liveMask >> curA) & 1ull) != 0;
 #pragma unroll
-            for (int i = 0; i < T::PX; ++i) xVoff[i] = (live && xOk) ? (xPart[i] + uni) * 4 : kOutOfRange;
+                for (int i = 0; i < T::PX; ++i)
+                    if ((i < T::PX / 2) == (piece == 2)) {
+                        const int off = (xPart[i] + curUni) * 4;
+                        xVoff[i] = live ? off : kOutOfRange;
+                    }
+            }
         } else {
-            gSoff = m0 * p.OC * 4;
-            const int n0 = (int)fast_div((unsigned)m0, p.divOHOW);
-            const int r0 = m0 - n0 * ohow;
-            const int oh0 = (int)fast_div((unsigned)r0, p.divOW);
-            const int ohs = oh0 * p.sh;
-            const int uni = (n0 * p.IH + ohs) * p.IW * p.IC;
+            if (piece == 0) {
+                const int m0 = ch * kBK;
+                gSoff = m0 * p.OC * 4;
+                curA = (int)fast_div((unsigned)m0, p.divOHOW);       // image
+                curB = m0 - curA * ohow;                              // first output pixel inside it
+            } else if (piece == 1) {
+                const int oh0 = (int)fast_div((unsigned)curB, p.divOW);
+                curB = oh0 * p.sh;
+                curUni = (curA * p.IH + curB) * p.IW * p.IC;
+            } else {
 #pragma unroll
-            for (int i = 0; i < T::PX; ++i) {
-                const bool ok = (unsigned)(ohs + xHBase[i]) < (unsigned)p.IH && n0 + xDn[i] < p.N;
-                xVoff[i] = ok ? (xPart[i] + uni) * 4 : kOutOfRange;
+                for (int i = 0; i < T::PX; ++i)
+                    if ((i < T::PX / 2) == (piece == 2)) {
+                        const int off = (xPart[i] + curUni) * 4;
+                        xVoff[i] = (unsigned)(curB + xHBase[i]) < (unsigned)p.IH ? off : kOutOfRange;
+                    }
             }
         }
+    };
+    auto set_stage = [&](int ch) __attribute__((always_inline)) {
+#pragma unroll
+        for (int piece = 0; piece < 4; ++piece) set_piece(piece, ch);
     };
 
     f4 ggS[2][T::PG], gxS[2][T::PX];
     constexpr int kItems = T::PG + T::PX;
-    constexpr int kGroups = kBK / 8;
     auto gload_item = [&](int q, f4 *gg, f4 *gx) __attribute__((always_inline)) {
         // gSoff is uniform; saying so keeps it in an SGPR instead of a per-lane loop over its values
         if (q < T::PG)
@@ -218,51 +257,68 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
 
-    // volatile: the compiler would otherwise pair these into two-address LDS reads, each pair
+    // Fragment ring: the LDS reads of MFMA step s+kAhead are issued before the MFMAs of step s, so a
+    // wave alone on its SIMD still feeds the matrix pipe back to back.  The stage's barrier sits
+    // kAhead steps before the stage's end: by then every wave has read all of this buffer into
+    // registers and stored its share of the next one, and the last steps' MFMAs run while the
+    // first fragments of the next buffer arrive.
+    // volatile: the compiler would otherwise pair the reads into two-address LDS reads, each pair
     // needing a VALU add for its base - and VALU instructions cost matrix time, LDS reads do not
-    auto load_frag = [&](const float *g, const float *x, int jj, f4 *fa, f4 *fb) __attribute__((always_inline)) {
+    constexpr int kSteps = kBK / 2, kRing = 4, kAhead = kRing - 1;
+    static_assert(kSteps % kRing == 0, "ring slots must line up across stages");
+    float fa[kRing][T::MB], fb[kRing][T::NB];
+    const float *gFrag = Gs + (lh * 4) * T::LDG + wm * T::WTM + l32;
+    const float *xFrag = Xs + (lh * 4) * T::LDX + wn * T::WTN + l32;
+    auto read_step = [&](int buf, int s, float *a, float *b) __attribute__((always_inline)) {
+        const int row = (s / 4) * 8 + s % 4;   // the lane's upper half adds 4: both operands use the same rows
+        lds_cvptr g = (lds_cvptr)(gFrag + buf * T::G_STAGE + row * T::LDG);
+        lds_cvptr x = (lds_cvptr)(xFrag + buf * T::X_STAGE + row * T::LDX);
 #pragma unroll
-        for (int i = 0; i < T::MB; ++i) {
-            lds_cvptr q = (lds_cvptr)(g + (jj * 8) * T::LDG + i * 32);
-            fa[i] = f4{q[0], q[T::LDG], q[2 * T::LDG], q[3 * T::LDG]};
-        }
+        for (int i = 0; i < T::MB; ++i) a[i] = g[i * 32];
 #pragma unroll
-        for (int j = 0; j < T::NB; ++j) {
-            lds_cvptr q = (lds_cvptr)(x + (jj * 8) * T::LDX + j * 32);
-            fb[j] = f4{q[0], q[T::LDX], q[2 * T::LDX], q[3 * T::LDX]};
-        }
+        for (int j = 0; j < T::NB; ++j) b[j] = x[j * 32];
     };
 
-    // One stage: MFMAs from LDS buffer `buf`; between MFMA groups the wave issues its share of
-    // the loads of chunk `chLoad` (register set ld) and of the LDS stores of set st.
-    auto stage = [&](int buf, bool doLoad, int ld, bool doStore, int st) __attribute__((always_inline)) {
-        const float *g = Gs + buf * T::G_STAGE + (lh * 4) * T::LDG + wm * T::WTM + l32;
-        const float *x = Xs + buf * T::X_STAGE + (lh * 4) * T::LDX + wn * T::WTN + l32;
-        constexpr bool kTwoFrags = BM * BN < 128 * 128 && BM * BN > 64 * 64;   // register budget of the smallest and largest tile
-        f4 fa[kTwoFrags ? 2 : 1][T::MB], fb[kTwoFrags ? 2 : 1][T::NB];
-        if (kTwoFrags) load_frag(g, x, 0, fa[0], fb[0]);
+    // One stage: MFMAs from LDS buffer `buf`; between MFMA steps the wave issues its share of
+    // the loads of the chunk two stages ahead (register set ld) and of the LDS stores of set st.
+    // Ends with the fragments of the first kAhead steps of buffer buf^1 in flight.
+    constexpr int kSlots = kSteps - kAhead;   // memory items go before the barrier
+    static_assert(kItems <= kSlots, "one memory item per MFMA step");
+    // With adv, the last four steps also move the load cursor to chunk advCh (the loads of this
+    // stage have been issued by then).
+    constexpr int kAdvStep = kSteps - 4;
+    static_assert((kItems - 1) * kSlots / kItems < kAdvStep, "cursor pieces come after the last load");
+    int advCh = 0;
+    auto stage = [&](int buf, bool doLoad, int ld, bool doStore, int st, bool adv) __attribute__((always_inline)) {
 #pragma unroll
-        for (int jj = 0; jj < kGroups; ++jj) {
-            const int cur = kTwoFrags ? (jj & 1) : 0;
-            if (kTwoFrags) {
-                if (jj + 1 < kGroups) load_frag(g, x, jj + 1, fa[cur ^ 1], fb[cur ^ 1]);
-            } else {
-                load_frag(g, x, jj, fa[0], fb[0]);
-            }
+        for (int s = 0; s < kSteps; ++s) {
+#if !defined(EXP_NOBAR)
+            if (s == kSlots) __syncthreads();
+#endif
+            const int sp = s + kAhead;
+#if !defined(EXP_NOFRAG)
+            if (sp < kSteps) read_step(buf, sp, fa[sp % kRing], fb[sp % kRing]);
+            else read_step(buf ^ 1, sp - kSteps, fa[sp % kRing], fb[sp % kRing]);
+#endif
 #pragma unroll
             for (int q = 0; q < kItems; ++q)
-                if (q % kGroups == jj) {
+                if (q * kSlots / kItems == s) {
+#if !defined(EXP_NOGLOAD)
                     if (doLoad) gload_item(q, ggS[ld], gxS[ld]);
+#endif
+#if !defined(EXP_NOLSTORE)
                     if (doStore) lds_store_item(q, buf ^ 1, ggS[st], gxS[st]);
+#endif
                 }
+#if !defined(EXP_NOSET)
+            if (adv && s >= kAdvStep) set_piece(s - kAdvStep, advCh);
+#endif
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+            for (int i = 0; i < T::MB; ++i)
 #pragma unroll
-                for (int i = 0; i < T::MB; ++i)
-#pragma unroll
-                    for (int j = 0; j < T::NB; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[cur][i][t], fb[cur][j][t], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < T::NB; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[s % kRing][i], fb[s % kRing][j], acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -284,35 +340,38 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
 #pragma unroll
         for (int q = 0; q < kItems; ++q) lds_store_item(q, 0, ggS[0], gxS[0]);
         __syncthreads();
+#pragma unroll
+        for (int s = 0; s < kAhead; ++s) read_step(0, s, fa[s], fb[s]);
         STAMP(2);
+        // c0 is in LDS buffer 0, c1 in register set 1, c2 is the chunk the next stage loads (its
+        // offsets are set), c3 the one after.
+        int c2 = next_live(c1 + 1);
+        if (c2 < ch1) set_stage(c2);
+        int c3 = next_live(c2 + 1);
         for (;;) {
             // two stages per trip so that buffer and register-set indices are compile-time
-            int c2 = c1 < ch1 ? next_live(c1 + 1) : ch1;
-            int c3 = c2 < ch1 ? next_live(c2 + 1) : ch1;
             if (c3 < ch1) {   // steady state: no branch around memory instructions
-                set_stage(c2);
-                stage(0, true, 0, true, 1);
+                const int c4 = next_live(c3 + 1);
+                advCh = c3;
+                stage(0, true, 0, true, 1, true);    // loads c2, then moves the cursor to c3
                 maybe_flush();
-                __syncthreads();
-                set_stage(c3);
-                stage(1, true, 1, true, 0);
+                advCh = c4;                          // past the end: offsets nobody loads from
+                stage(1, true, 1, true, 0, true);    // loads c3
                 maybe_flush();
-                __syncthreads();
-                c0 = c2;
                 c1 = c3;
+                c2 = c4;
+                c3 = next_live(c4 + 1);
                 continue;
             }
             // tail: c0 (in LDS 0), maybe c1 (registers 1), maybe c2
             if (c2 < ch1) set_stage(c2);
-            stage(0, c2 < ch1, 0, c1 < ch1, 1);
+            stage(0, c2 < ch1, 0, c1 < ch1, 1, false);
             maybe_flush();
-            __syncthreads();
             if (c1 >= ch1) break;
-            stage(1, false, 1, c2 < ch1, 0);
+            stage(1, false, 1, c2 < ch1, 0, false);
             maybe_flush();
-            __syncthreads();
             if (c2 >= ch1) break;
-            stage(0, false, 0, false, 1);
+            stage(0, false, 0, false, 1, false);
             break;
         }
     }
@@ -331,6 +390,9 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
             }
         }
     STAMP(4);
+#if defined(EXP_STAMPS)
+    if (threadIdx.x == 0 && blockIdx.x < 16384) g_wstamps[blockIdx.x * 8 + 7] = clock64() - expClk0;
+#endif
 }
 
 #if defined(EXP_STAMPS)
@@ -340,11 +402,11 @@ extern "C" int exp_read_wstamps(unsigned long long *host, size_t count)
 }
 #endif
 
-template <int BM, int BN>
+template <int BM, int BN, bool PM>
 static hipError_t launch_fast_one(const WgradParams &p, int grid, hipStream_t st)
 {
     using T = WF<BM, BN>;
-    auto kern = wgrad_fast_kernel<BM, BN>;
+    auto kern = wgrad_fast_kernel<BM, BN, PM>;
     static bool attrSet[16] = {};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -361,10 +423,16 @@ static hipError_t launch_fast_one(const WgradParams &p, int grid, hipStream_t st
 
 hipError_t launch_wgrad_fast(const WgradParams &p, int bm, int bn, int grid, hipStream_t st)
 {
-    if (bm == 128 && bn == 128) return launch_fast_one<128, 128>(p, grid, st);
-    if (bm == 64 && bn == 128) return launch_fast_one<64, 128>(p, grid, st);
-    if (bm == 64 && bn == 64) return launch_fast_one<64, 64>(p, grid, st);
-    if (bm == 128 && bn == 64) return launch_fast_one<128, 64>(p, grid, st);
+    if (p.posMajor && (p.N % kBK != 0 || p.OH * p.OW > 64)) return hipErrorInvalidValue;
+#define MI355CONV_WF(BM_, BN_)                                                        \
+    if (bm == BM_ && bn == BN_)                                                       \
+        return p.posMajor ? launch_fast_one<BM_, BN_, true>(p, grid, st)              \
+                          : launch_fast_one<BM_, BN_, false>(p, grid, st);
+    MI355CONV_WF(128, 128)
+    MI355CONV_WF(64, 128)
+    MI355CONV_WF(64, 64)
+    MI355CONV_WF(128, 64)
+#undef MI355CONV_WF
     return hipErrorInvalidValue;
 }
 
