@@ -5,8 +5,8 @@
 // its channels, reduction = (filter tap, source channel).  A workgroup owns a BM x BN
 // output tile and walks the reduction in stages of kBK source channels of one tap:
 //   global (NHWC, 16-byte loads along the channel axis) -> registers -> LDS -> MFMA.
-// The next stage's global loads are issued before the current stage's MFMAs and land in
-// the other LDS buffer afterwards, so one barrier per stage suffices.
+// Global loads run two stages ahead through two register sets and land in the other LDS
+// buffer one stage later; one barrier per stage.
 //
 // Two things make it a small-feature-map operator (paper Sec. IV: special conv\deconv
 // operators that cut the work more the smaller the map is):
@@ -134,7 +134,6 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
 
     // item q of a stage: q < PA is A-tile pass q, otherwise B-tile pass q - PA
     constexpr int kItems = T::PA + T::PB;
-    constexpr int kGroups = kBK / 8;
     auto gload_item = [&](int q, f4 *ga, f4 *gb) __attribute__((always_inline)) {
         const int c0 = chunk * kBK;
         if (q < T::PA) {
@@ -189,83 +188,81 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     const int wm = wave / T::WAVES_N, wn = wave % T::WAVES_N;
     const int l32 = lane & 31, lh = lane >> 5;
 
-    // LDS -> register fragments for reduction group jj (8 k values: 4 per half-wave)
-    auto load_frag = [&](const float *a, const float *b, int jj, f4 *fa, f4 *fb) __attribute__((always_inline)) {
+    // LDS -> register fragments.  A group is kGK MFMA steps: each half-wave reads kGK consecutive
+    // reduction elements with one LDS read per 32 tile rows (16 bytes; 8 bytes for the largest
+    // tile, whose registers only hold two small fragment sets).
+    constexpr int kGK = BM * BN >= 128 * 128 ? 2 : 4;
+    constexpr int kGroups = kBK / (2 * kGK);
+    static_assert(kGroups % 2 == 0, "fragment sets alternate across stages");
+    typedef float fragv __attribute__((ext_vector_type(kGK)));
+    fragv fa[2][T::MB], fb[2][T::NB];
+    const float *aFrag = As + (wm * T::WTM + l32) * LDA + lh * kGK;
+    const float *bFrag = BWD ? Bs + (lh * kGK) * T::LDB + wn * T::WTN + l32
+                             : Bs + (wn * T::WTN + l32) * T::LDB + lh * kGK;
+    auto read_group = [&](int buf, int g, fragv *ra, fragv *rb) __attribute__((always_inline)) {
+        const float *a = aFrag + buf * T::A_STAGE + g * 2 * kGK;
 #pragma unroll
-        for (int i = 0; i < T::MB; ++i) fa[i] = *reinterpret_cast<const f4 *>(a + i * 32 * LDA + jj * 8);
+        for (int i = 0; i < T::MB; ++i) ra[i] = *reinterpret_cast<const fragv *>(a + i * 32 * LDA);
 #pragma unroll
         for (int j = 0; j < T::NB; ++j) {
             if (BWD) {
-                // volatile LDS pointer: keeps four single reads with immediate offsets; paired
+                // volatile LDS pointer: keeps single reads with immediate offsets; paired
                 // two-address reads would each need a VALU add, which costs matrix time
-                lds_cvptr q = (lds_cvptr)(b + (jj * 8) * T::LDB + j * 32);
-                fb[j] = f4{q[0], q[T::LDB], q[2 * T::LDB], q[3 * T::LDB]};
+                lds_cvptr q = (lds_cvptr)(bFrag + buf * T::B_STAGE + (g * 2 * kGK) * T::LDB + j * 32);
+#pragma unroll
+                for (int t = 0; t < kGK; ++t) rb[j][t] = q[t * T::LDB];
             } else {
-                fb[j] = *reinterpret_cast<const f4 *>(b + j * 32 * T::LDB + jj * 8);
+                rb[j] = *reinterpret_cast<const fragv *>(bFrag + buf * T::B_STAGE + j * 32 * T::LDB + g * 2 * kGK);
             }
         }
     };
 
-    // One stage.  MFMAs run from LDS buffer `buf` in kGroups groups of 8 reduction elements.
-    // Before the MFMAs of group jj are issued the wave requests the fragments of group jj+1
-    // and issues its share (items q with q % kGroups == jj) of
+    // One stage.  MFMAs run from LDS buffer `buf` in kGroups groups.  Before the MFMAs of group
+    // g are issued the wave requests the fragments of group g+1 and issues its share of
     //   - the global loads of the stage two ahead, into register set `ld` (when doLoad),
     //   - the LDS stores of the next stage, from register set `st` into the other buffer
     //     (when doStore),
     // so memory instructions are spread between MFMAs instead of starving the matrix pipe in
-    // a burst at the stage boundary.
+    // a burst at the stage boundary.  The stage's barrier sits before its LAST group: by then
+    // every wave holds that group's fragments in registers and has stored its share of the
+    // next buffer, so the first fragments of the next stage are requested right after the
+    // barrier and arrive while the last group is multiplied - a wave alone on its SIMD does
+    // not wait for LDS at the stage boundary.
+    constexpr int kSlots = kGroups - 1;
     auto stage = [&](int buf, bool doLoad, int ld, bool doStore, int st) __attribute__((always_inline)) {
-        const float *a = As + buf * T::A_STAGE + (wm * T::WTM + l32) * LDA + lh * 4;
-        const float *b = BWD ? Bs + buf * T::B_STAGE + (lh * 4) * T::LDB + wn * T::WTN + l32
-                             : Bs + buf * T::B_STAGE + (wn * T::WTN + l32) * T::LDB + lh * 4;
-        // the largest tile has no registers left for a second fragment set
-        constexpr bool kTwoFrags = BM * BN < 128 * 128;
-        f4 fa[kTwoFrags ? 2 : 1][T::MB], fb[kTwoFrags ? 2 : 1][T::NB];
-        if (kTwoFrags) load_frag(a, b, 0, fa[0], fb[0]);
 #pragma unroll
-        for (int jj = 0; jj < kGroups; ++jj) {
-            const int cur = kTwoFrags ? (jj & 1) : 0;
-            if (kTwoFrags) {
-                if (jj + 1 < kGroups) load_frag(a, b, jj + 1, fa[cur ^ 1], fb[cur ^ 1]);
+        for (int g = 0; g < kGroups; ++g) {
+            const int cur = g & 1;
+            if (g + 1 < kGroups) {
+                read_group(buf, g + 1, fa[cur ^ 1], fb[cur ^ 1]);
             } else {
-                load_frag(a, b, jj, fa[0], fb[0]);
+                __syncthreads();
+                read_group(buf ^ 1, 0, fa[cur ^ 1], fb[cur ^ 1]);
             }
 #pragma unroll
             for (int q = 0; q < kItems; ++q)
-                if (q % kGroups == jj) {
+                if (q % kSlots == g) {
                     if (doLoad) gload_item(q, gaS[ld], gbS[ld]);
                     if (doStore) lds_store_item(q, buf ^ 1, gaS[st], gbS[st]);
                 }
-#if !defined(EXP_INTERLEAVE)
+            if (g + 1 == kGroups && doLoad) advance();
             __builtin_amdgcn_sched_barrier(0);
-#endif
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
+            for (int t = 0; t < kGK; ++t) {
 #pragma unroll
                 for (int i = 0; i < T::MB; ++i)
 #pragma unroll
                     for (int j = 0; j < T::NB; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[cur][i][t], fb[cur][j][t], acc[i][j], 0, 0, 0);
             }
-#if defined(EXP_INTERLEAVE)
-            // ask the scheduler to slot the group's memory/VALU instructions between the MFMAs
-#pragma unroll
-            for (int k = 0; k < 4 * T::MB * T::NB; ++k) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);   // a few VALU
-                __builtin_amdgcn_sched_group_barrier(0x300, 1, 0);   // one LDS op
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
-            }
-#endif
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (doLoad) advance();
     };
 
     // ---- main loop ----------------------------------------------------------------------
     // Stage t is multiplied from LDS buffer t&1.  Register set t&1 (whose data went to LDS one
     // stage ago) receives the global loads of stage t+2; register set (t+1)&1, loaded one stage
-    // ago, moves to the other LDS buffer.  One barrier per stage.
+    // ago, moves to the other LDS buffer.  One barrier per stage (inside it).
     if (it0 < it1) {
         const int n = it1 - it0;
         set_tap();
@@ -278,22 +275,19 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
         STAMP(2);
         lds_store(0, gaS[0], gbS[0]);
         __syncthreads();
+        read_group(0, 0, fa[0], fb[0]);
         STAMP(3);
         int t = 0;
         // steady state: no branch around memory instructions, so every wait is an exact count
         for (; t + 3 < n; t += 2) {
             stage(0, true, 0, true, 1);
-            __syncthreads();
             stage(1, true, 1, true, 0);
-            __syncthreads();
         }
         // tail: at most three stages left
         for (; t < n; t += 2) {
             stage(0, t + 2 < n, 0, t + 1 < n, 1);
-            __syncthreads();
             if (t + 1 >= n) break;
             stage(1, t + 3 < n, 1, t + 2 < n, 0);
-            __syncthreads();
         }
     }
 
