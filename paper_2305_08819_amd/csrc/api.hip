@@ -83,22 +83,27 @@ bool buffer_addressable(const Shape &s, long long srcElems, int srcW, int srcC)
 }
 
 // ---- cost model ------------------------------------------------------------------------
-// Picks tile and slice count by a small analytic model instead of fixed thresholds.  Time of
-// a launch = rounds x (stages per workgroup x stage time + fixed per-workgroup cost), where a
-// round is one set of co-resident workgroups on the 256 CUs, plus the reduce pass when the
-// reduction is sliced.  Constants were fitted to sweeps on MI355X; only ratios matter.
+// Picks tile and slice count by a small analytic model instead of fixed thresholds.  A launch
+// whose workgroups are all resident at once lasts as long as its busiest CU (the grid is
+// quantised to the 256 CUs); a larger one divides its work evenly over the CUs and then
+// drains; the reduce pass is added when the reduction is sliced.  Only ratios matter.
 struct TileCand { int bm, bn; double eff; int resident; };
 
-// Constants of the model, fitted by least squares to tile x split x row-order sweeps of the
-// benchmark layers on MI355X (separately for the gather-GEMM and the backward-weight kernel).
+// Constants of the model, chosen to minimise the regret of the planner's pick over tile x split
+// x row-order sweeps of the benchmark layers on MI355X (separately for the gather-GEMM and the
+// backward-weight kernel).
 struct CostParams {
     double loneEff;        // efficiency factor when a workgroup has a CU to itself
-    double fixedUs;        // prologue + epilogue + ramp of one round of workgroups
+    double fewEff;         // ... when two or three share it
+    double refillEff;      // ... when finished workgroups are replaced by waiting ones (desynchronised)
+    double mix;            // weight of the other workgroups on the busiest CU (they are not all the longest)
+    double tail;           // drain of the last workgroups, in units of one resident set
+    double fixedUs;        // launch + prologue + epilogue
     double reduceUs;       // launch + ramp of the slice-reduce kernel
     double reduceBytesPerUs;
 };
-constexpr CostParams kGatherCost = {0.60, 5.6, 5.1, 8.9e6};
-constexpr CostParams kWgradCost = {0.74, 1.0, 7.6, 6.0e6};
+constexpr CostParams kGatherCost = {0.96, 1.0, 1.0, 1.0, 0.12, 9.0, 0.5, 5.7e6};
+constexpr CostParams kWgradCost = {0.80, 0.95, 1.05, 0.56, 0.20, 4.0, 10.0, 6.2e6};
 
 constexpr double kCuFlopPerUs = 157.3e6 / 256.0;   // fp32 MFMA FLOP per microsecond per CU
 constexpr size_t kMaxWorkspace = (size_t)1 << 30;
@@ -108,20 +113,24 @@ double launch_cost(const CostParams &k, const TileCand &c, long long tiles, doub
 {
     const long long grid = tiles * split;
     const int cus = 256;
-    long long residentNow = (grid + cus - 1) / cus;
-    if (residentNow > c.resident) residentNow = c.resident;
-    // a lone workgroup on a CU cannot hide its own load latency and barriers
-    const double eff = residentNow >= 2 ? c.eff : c.eff * k.loneEff;
-    const double stageUs = (double)residentNow * (2.0 * c.bm * c.bn * kBK) / (kCuFlopPerUs * eff);
     const long long slots = (long long)cus * c.resident;
-    const double rounds = (double)((grid + slots - 1) / slots);
-    const double avgWg = avgStages / split * stageUs + k.fixedUs;
-    const double maxWg = maxStages / split * stageUs + k.fixedUs;
-    // one round lasts as long as its longest workgroup, but co-resident short ones free the
-    // matrix pipe early: take the middle between the longest and the average
-    double t = rounds * avgWg;
-    const double longest = 0.5 * (maxWg + avgWg);
-    if (longest > t) t = longest;
+    // time of one workgroup that has the CU's matrix pipes to itself at full efficiency
+    const double unit = (2.0 * c.bm * c.bn * kBK) / kCuFlopPerUs;
+    const double avgWg = avgStages / split * unit, maxWg = maxStages / split * unit;
+    double t;
+    if (grid <= slots) {
+        // everything is resident at once: the busiest CU holds ceil(grid / 256) workgroups
+        const long long perCu = (grid + cus - 1) / cus;
+        const double eff = c.eff * (perCu == 1 ? k.loneEff : perCu <= 3 ? k.fewEff : 1.0);
+        double busiest = (double)perCu * avgWg;
+        const double withLongest = maxWg + (double)(perCu - 1) * avgWg * k.mix;
+        if (withLongest > busiest) busiest = withLongest;
+        t = busiest / eff;
+    } else {
+        // finished workgroups are replaced at once: work divides evenly, plus the drain
+        t = ((double)grid / cus * avgWg + k.tail * c.resident * avgWg) / (c.eff * k.refillEff);
+    }
+    t += k.fixedUs;
     if (split > 1) t += k.reduceUs + (2.0 * split + 1.0) * (double)outElems * 4.0 / k.reduceBytesPerUs;
     return t;
 }
@@ -165,8 +174,8 @@ bool tile_compiled(int bm, int bn, bool gather)
     return (bm == 128 || bm == 64) && (bn == 128 || bn == 64);
 }
 
-const TileCand kGatherTiles[] = {{128, 128, 0.89, 2}, {128, 64, 0.85, 2}, {64, 64, 1.00, 4}, {128, 32, 0.70, 3}};
-const TileCand kWgradTiles[] = {{128, 128, 0.85, 1}, {64, 128, 0.82, 5}, {128, 64, 0.83, 5}, {64, 64, 0.84, 5}};
+const TileCand kGatherTiles[] = {{128, 128, 0.93, 2}, {128, 64, 0.92, 2}, {64, 64, 0.945, 4}, {128, 32, 0.66, 3}};
+const TileCand kWgradTiles[] = {{128, 128, 0.80, 1}, {64, 128, 0.93, 2}, {128, 64, 0.94, 2}, {64, 64, 0.98, 4}};
 
 bool forced_tile(int *bm, int *bn, bool gather)
 {
@@ -369,7 +378,8 @@ Plan plan_bwd_data(const Shape &s)
     const bool fits = s.sh * s.sw <= kMaxPhases &&
                       offsets_fit_32bit((long long)s.N * s.OH * s.OW * s.OC, s, s.OW, s.OC) &&
                       pl.outElems < kMaxElems;
-    const bool chunked = s.OC % kBK == 0 && s.IC % 4 == 0 &&
+    // up to 32 input channels of any count go through the narrow tile with 4-byte filter loads
+    const bool chunked = s.OC % kBK == 0 && (s.IC % 4 == 0 || s.IC <= 32) &&
                          buffer_addressable(s, (long long)s.N * s.OH * s.OW * s.OC, s.OW, s.OC);
     if (forced == MI355CONV_VARIANT_DIRECT || !fits) return pl;
     pl.variant = MI355CONV_VARIANT_MFMA;
@@ -410,7 +420,9 @@ Plan plan_bwd_data(const Shape &s)
     double best = 1e300;
     for (const TileCand &c0 : kGatherTiles) {
         TileCand c = c0;
-        if (haveForced) {
+        if (s.IC % 4 != 0) {   // 4-byte filter loads exist for the narrow tile only
+            if (c.bn != 32) continue;
+        } else if (haveForced) {
             if (c.bm != fbm || c.bn != fbn) continue;
         } else {
             if (c.bn > 32 && c.bn / 2 >= s.IC) continue;

@@ -34,7 +34,10 @@ namespace mi355conv { __device__ unsigned long long g_stamps[8192 * 8]; }
 
 namespace mi355conv {
 
-template <int BM, int BN, int WAVES_M, bool BWD>
+// BELEM (backward-data only): the destination channel count is not a multiple of 4, so a
+// 16-byte load of four filter columns would be misaligned; the B tile is fetched with four
+// 4-byte loads per thread instead (e.g. the first layer's dX with 3 channels).
+template <int BM, int BN, int WAVES_M, bool BWD, bool BELEM = false>
 __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGemmParams p)
 {
     STAMP(0);
@@ -88,12 +91,21 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     }
     const int bSeg = tid % T::B_TPR, bRow = tid / T::B_TPR;
     const int wRowStride = p.FH * p.FW * (BWD ? p.DC : p.SC);  // floats per oc in W
+    static_assert(!BELEM || BWD, "element-wise B loads exist for backward-data only");
     int bOff[T::PB];   // fixed for the whole kernel
+    int bOffE[BELEM ? T::PB : 1][4];
 #pragma unroll
     for (int i = 0; i < T::PB; ++i) {
         const int r = bRow + T::B_RPP * i;
         if (BWD) bOff[i] = (r < kBK && n0 + bSeg * 4 < p.DC) ? (r * wRowStride + n0 + bSeg * 4) * 4 : kOutOfRange;
         else bOff[i] = (r < BN && n0 + r < p.DC) ? ((n0 + r) * wRowStride + bSeg * 4) * 4 : kOutOfRange;
+        if (BELEM) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int col = n0 + bSeg * 4 + e;
+                bOffE[i][e] = (r < kBK && col < p.DC) ? (r * wRowStride + col) * 4 : kOutOfRange;
+            }
+        }
     }
 
     // reduction cursor: current tap (u,v) and chunk within the tap
@@ -141,7 +153,13 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
         } else {
             const int i = q - T::PA;
             const int soff = BWD ? (c0 * wRowStride + tapOffB) * 4 : (tapOffB + c0) * 4;
-            gb[i] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrcB, bOff[i], soff, 0));
+            if (BELEM) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    gb[i][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrcB, bOffE[i][e], soff, 0));
+            } else {
+                gb[i] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrcB, bOff[i], soff, 0));
+            }
         }
     };
     auto gload = [&](f4 *ga, f4 *gb) __attribute__((always_inline)) {
@@ -303,12 +321,12 @@ extern "C" int exp_read_stamps(unsigned long long *host, size_t count)
 }
 #endif
 
-template <int BM, int BN, int WAVES_M, bool BWD>
+template <int BM, int BN, int WAVES_M, bool BWD, bool BELEM = false>
 static hipError_t launch_one(const GatherGemmParams &p, int grid, hipStream_t st)
 {
     using T = GG<BM, BN, WAVES_M, BWD>;
     constexpr size_t kSmemBytes = (2 * (T::A_STAGE + T::B_STAGE) + T::TABLE_INTS) * sizeof(float);
-    auto kern = gather_gemm_kernel<BM, BN, WAVES_M, BWD>;
+    auto kern = gather_gemm_kernel<BM, BN, WAVES_M, BWD, BELEM>;
     static bool attrSet[16] = {};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -326,6 +344,10 @@ static hipError_t launch_one(const GatherGemmParams &p, int grid, hipStream_t st
 hipError_t launch_gather_gemm(const GatherGemmParams &p, bool bwdData, int bm, int bn, int grid,
                               hipStream_t st)
 {
+    if (p.DC % 4 != 0) {   // only backward-data into few channels, on the narrow tile
+        if (bwdData && bm == 128 && bn == 32) return launch_one<128, 32, 4, true, true>(p, grid, st);
+        return hipErrorInvalidValue;
+    }
 #define MI355_GG_CASE(BM_, BN_, WM_)                                                    \
     if (bm == BM_ && bn == BN_)                                                          \
         return bwdData ? launch_one<BM_, BN_, WM_, true>(p, grid, st)                    \

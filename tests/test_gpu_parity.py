@@ -76,6 +76,27 @@ def test_elementwise_mfma_variant_odd_shapes(shp, split):
     gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), label=str(shp))
 
 
+# backward-data into few channels of any count (not a multiple of 4) with OC a multiple of 32:
+# 16-byte loads of dY, 4-byte loads of the filter (the first layer of the VGG stack is the type)
+FEW_CHANNEL_SHAPES = [
+    (2, 9, 9, 5, 32, 3, 3, 2, 1),
+    (3, 8, 8, 7, 64, 5, 5, 1, 2),
+    (2, 6, 6, 30, 32, 3, 3, 1, 1),
+    (4, 10, 7, 1, 96, 3, 2, (1, 2), (1, 0)),
+]
+
+
+@pytest.mark.parametrize("split", [0, 3])
+@pytest.mark.parametrize("shp", FEW_CHANNEL_SHAPES)
+def test_bwd_data_few_channels(shp, split):
+    say("few-channel %s split=%d" % (shp, split))
+    d = mc.make_desc(*shp)
+    mc.conv2d_set_tuning(mc.VARIANT_MFMA, split)
+    pl = mc.conv2d_query_plan(mc.OP_BWD_DATA, d)
+    assert pl.variant == mc.VARIANT_MFMA and (pl.tile_m, pl.tile_n) == (128, 32)
+    gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), label=str(shp))
+
+
 # shapes the MFMA variants accept, chosen to give ragged row tiles, ragged column tiles,
 # several stride phases, non-square filters/strides/pads and more than 32 taps
 MFMA_SHAPES = [
