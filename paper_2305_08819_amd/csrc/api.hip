@@ -5,6 +5,7 @@
 #include "../../include/mi355conv.h"
 #include "conv_internal.h"
 
+#include <algorithm>
 #include <atomic>
 #include <cstdio>
 #include <cstring>
@@ -555,6 +556,40 @@ void fill_gather_params(GatherGemmParams &g, const Plan &pl)
     for (int i = 0; i < kMaxPhases; ++i) g.phase[i] = pl.phase[i];
 }
 
+// (y,x,n) row order on a small map: order the positions by the number of taps inside the image
+// (= stages of their tiles), most first.  Only for the single-phase cases (forward, unit-stride
+// backward-data), where a row tile lies on one position.
+void set_balance(GatherGemmParams &g, const Shape &s, const Plan &pl, bool bwd)
+{
+    g.balance = 0;
+    if (!pl.posMajor || pl.elem || pl.nPhases != 1 || s.N % pl.bm != 0) return;
+    if (bwd && (s.sh != 1 || s.sw != 1)) return;
+    const int dh = bwd ? s.IH : s.OH, dw = bwd ? s.IW : s.OW;
+    const int nPos = dh * dw;
+    if (nPos > kMaxBalancedPositions || pl.grid < 512) return;
+    int taps[kMaxBalancedPositions];
+    int lo = 1 << 30, hi = 0;
+    for (int i = 0; i < dh; ++i)
+        for (int j = 0; j < dw; ++j) {
+            int th = 0, tw = 0;
+            for (int f = 0; f < s.FH; ++f)
+                th += bwd ? (unsigned)(i + s.ph - f) < (unsigned)s.OH : (unsigned)(i * s.sh - s.ph + f) < (unsigned)s.IH;
+            for (int f = 0; f < s.FW; ++f)
+                tw += bwd ? (unsigned)(j + s.pw - f) < (unsigned)s.OW : (unsigned)(j * s.sw - s.pw + f) < (unsigned)s.IW;
+            const int t = th * tw;
+            taps[i * dw + j] = t;
+            if (t < lo) lo = t;
+            if (t > hi) hi = t;
+        }
+    if (lo == hi) return;
+    int order[kMaxBalancedPositions];
+    for (int i = 0; i < nPos; ++i) order[i] = i;
+    std::stable_sort(order, order + nPos, [&](int a, int b) { return taps[a] > taps[b]; });
+    for (int i = 0; i < nPos; ++i) g.posOrder[i] = (unsigned char)order[i];
+    g.rowTilesPerPos = s.N / pl.bm;
+    g.balance = 1;
+}
+
 int run_gather(const float *A, const float *B, float *out, const Shape &s, const Plan &pl, bool bwd,
                void *ws, hipStream_t st)
 {
@@ -577,6 +612,7 @@ int run_gather(const float *A, const float *B, float *out, const Shape &s, const
     g.aBytes = (unsigned)((long long)g.Nimg * g.SH * g.SW * g.SC * 4);
     g.bBytes = (unsigned)((long long)s.OC * s.FH * s.FW * s.IC * 4);
     fill_gather_params(g, pl);
+    set_balance(g, s, pl, bwd);
     hipError_t e = pl.elem ? launch_gather_elem(g, bwd, pl.bm, pl.bn, pl.grid, st)
                            : launch_gather_gemm(g, bwd, pl.bm, pl.bn, pl.grid, st);
     if (e != hipSuccess) return hip_fail(e);

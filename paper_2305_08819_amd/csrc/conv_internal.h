@@ -15,6 +15,7 @@ struct Shape {
 constexpr int kThreads = 256;     // every MFMA kernel runs 4 wavefronts per workgroup
 constexpr int kBK = 32;           // reduction elements staged per LDS stage
 constexpr int kMaxPhases = 16;    // sh*sw limit of the MFMA backward-data variant
+constexpr int kMaxBalancedPositions = 256;
 
 // Division by a launch-invariant divisor with one multiply-high and two shifts (round-up
 // method of Granlund & Montgomery, "Division by invariant integers using multiplication").
@@ -71,8 +72,16 @@ struct GatherGemmParams {
     int tilesN;
     int xcdUnit;          // consecutive logical workgroup ids kept on one XCD
     int nPhases;
+    // Load balancing for (y,x,n) row order on small maps, where a tile's work is the number of
+    // taps inside the image at its position (4, 6 or 9 of 9 for a padded 3x3 filter): row tiles
+    // are taken position by position in posOrder (most taps first) and the workgroup ids of
+    // every second lap of 256 run backwards, so that the workgroups that end up on one CU
+    // (ids 256 apart) mix long and short tiles.  0 = off.
+    int balance;
+    int rowTilesPerPos;   // Nimg / BM
     FastDiv divN;         // by Nimg
     GatherPhase phase[kMaxPhases];
+    unsigned char posOrder[kMaxBalancedPositions];
 };
 
 // ---- backward-weight ---------------------------------------------------------------------
@@ -102,6 +111,16 @@ struct WgradParams {
 // that share operand tiles) run on one XCD, while units are still dealt round-robin so every
 // XCD gets the same mix of long and short tiles.  Ids past the last whole group of 8 units
 // keep their value.  A bijection on [0, grid).
+// Workgroup ids 256 apart share a CU when the whole grid is resident.  Reverse every second lap
+// of 256 ids (whole laps only): with work sorted in descending order along the ids, a CU then
+// gets one long and one short item per pair of laps.  A bijection on [0, grid).
+__device__ __forceinline__ int lap_snake(int bid, int grid)
+{
+    const int lap = bid >> 8;
+    if ((lap & 1) == 0 || (lap + 1) * 256 > grid) return bid;
+    return (lap << 8) + 255 - (bid & 255);
+}
+
 __device__ __forceinline__ int xcd_remap(int bid, int grid, int unit)
 {
     constexpr int kXcds = 8;

@@ -55,11 +55,15 @@ __device__ __forceinline__ GatherTile gather_tile_setup(const GatherGemmParams &
                                                         int *rowX, int *outRow)
 {
     const int tid = threadIdx.x;
-    int bid = xcd_remap(blockIdx.x, gridDim.x, p.xcdUnit);
+    int bid = p.balance ? lap_snake(blockIdx.x, gridDim.x) : xcd_remap(blockIdx.x, gridDim.x, p.xcdUnit);
     const int tn = bid % p.tilesN;
     bid /= p.tilesN;
     const int slice = bid % p.split;
-    const int tmGlobal = bid / p.split;
+    int tmGlobal = bid / p.split;
+    if (p.balance) {   // row tiles are enumerated by position rank
+        const int rank = tmGlobal / p.rowTilesPerPos;
+        tmGlobal = p.posOrder[rank] * p.rowTilesPerPos + (tmGlobal - rank * p.rowTilesPerPos);
+    }
     int phase = 0;
     if (BWD) {   // tile starts are ascending: the phase is the number of starts not above this tile
 #pragma unroll
