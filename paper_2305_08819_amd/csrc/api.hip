@@ -9,6 +9,7 @@
 #include <atomic>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 using namespace mi355conv;
 
@@ -39,6 +40,11 @@ struct Plan {
     // backward-data phase table
     int nPhases = 1;
     GatherPhase phase[kMaxPhases] = {};
+    // load balancing of unequal tiles (small maps in position-major order)
+    int balance = 0;
+    int itemsPerClassUnit = 0;   // workgroups per position (gather) / per tap (backward-weight)
+    BalanceRuns runs = {};
+    unsigned char order[256] = {};   // rank -> position (gather) or tap (backward-weight)
 };
 
 int out_extent(int in, int pad, int f, int stride)
@@ -103,14 +109,15 @@ struct CostParams {
     double reduceUs;       // launch + ramp of the slice-reduce kernel
     double reduceBytesPerUs;
 };
-constexpr CostParams kGatherCost = {0.96, 1.0, 1.0, 1.0, 0.12, 9.0, 0.5, 5.7e6};
+constexpr CostParams kGatherCost = {0.85, 0.95, 1.0, 1.0, 0.10, 5.0, 0.5, 8.0e6};
 constexpr CostParams kWgradCost = {0.80, 0.95, 1.05, 0.56, 0.20, 4.0, 10.0, 6.2e6};
 
 constexpr double kCuFlopPerUs = 157.3e6 / 256.0;   // fp32 MFMA FLOP per microsecond per CU
 constexpr size_t kMaxWorkspace = (size_t)1 << 30;
 
+// balanced: long and short workgroups are dealt evenly to the CUs (see GatherGemmParams::balance)
 double launch_cost(const CostParams &k, const TileCand &c, long long tiles, double avgStages, double maxStages,
-                   int split, long long outElems)
+                   int split, long long outElems, bool balanced = false)
 {
     const long long grid = tiles * split;
     const int cus = 256;
@@ -124,7 +131,9 @@ double launch_cost(const CostParams &k, const TileCand &c, long long tiles, doub
         const long long perCu = (grid + cus - 1) / cus;
         const double eff = c.eff * (perCu == 1 ? k.loneEff : perCu <= 3 ? k.fewEff : 1.0);
         double busiest = (double)perCu * avgWg;
-        const double withLongest = maxWg + (double)(perCu - 1) * avgWg * k.mix;
+        const double withLongest = balanced && grid >= 2 * cus
+                                       ? busiest + (maxWg - avgWg) * 2.0 / (double)perCu   // what pairing cannot even out
+                                       : maxWg + (double)(perCu - 1) * avgWg * k.mix;
         if (withLongest > busiest) busiest = withLongest;
         t = busiest / eff;
     } else {
@@ -138,7 +147,7 @@ double launch_cost(const CostParams &k, const TileCand &c, long long tiles, doub
 
 // Best slice count for one candidate; returns the cost.
 double best_split(const CostParams &k, const TileCand &c, long long tiles, double avgStages, double maxStages,
-                  long long outElems, int *splitOut, int minS = 1)
+                  long long outElems, int *splitOut, int minS = 1, bool balanced = false)
 {
     const int forced = g_forceSplit.load();
     int maxS = (int)(avgStages / 2.0);              // keep >= 2 stages per slice on average
@@ -149,12 +158,12 @@ double best_split(const CostParams &k, const TileCand &c, long long tiles, doubl
     if (forced > 0) {
         *splitOut = forced < maxS ? forced : maxS;
         if (*splitOut < minS) *splitOut = minS;
-        return launch_cost(k, c, tiles, avgStages, maxStages, *splitOut, outElems);
+        return launch_cost(k, c, tiles, avgStages, maxStages, *splitOut, outElems, balanced);
     }
     double best = 1e300;
     int bestS = 1;
     for (int sp = minS; sp <= maxS; ++sp) {
-        const double t = launch_cost(k, c, tiles, avgStages, maxStages, sp, outElems);
+        const double t = launch_cost(k, c, tiles, avgStages, maxStages, sp, outElems, balanced);
         if (t < best) { best = t; bestS = sp; }
     }
     *splitOut = bestS;
@@ -175,7 +184,7 @@ bool tile_compiled(int bm, int bn, bool gather)
     return (bm == 128 || bm == 64) && (bn == 128 || bn == 64);
 }
 
-const TileCand kGatherTiles[] = {{128, 128, 0.93, 2}, {128, 64, 0.92, 2}, {64, 64, 0.945, 4}, {128, 32, 0.66, 3}};
+const TileCand kGatherTiles[] = {{128, 128, 0.88, 2}, {128, 64, 0.945, 2}, {64, 64, 0.945, 4}, {128, 32, 0.66, 3}};
 const TileCand kWgradTiles[] = {{128, 128, 0.80, 1}, {64, 128, 0.93, 2}, {128, 64, 0.94, 2}, {64, 64, 0.98, 4}};
 
 bool forced_tile(int *bm, int *bn, bool gather)
@@ -302,7 +311,8 @@ Plan plan_fwd(const Shape &s)
             const double avgStages = (order ? avgTapsPos : s.FH * s.FW) * chunksPerTap;
             const double maxStages = (order ? maxTapsPos : s.FH * s.FW) * chunksPerTap;
             int sp = 1;
-            const double t = best_split(kGatherCost, c, tiles, avgStages, maxStages, pl.outElems, &sp);
+            const bool balanced = order && s.OH * s.OW <= kMaxBalancedPositions;
+            const double t = best_split(kGatherCost, c, tiles, avgStages, maxStages, pl.outElems, &sp, 1, balanced);
             if (t < best) {
                 best = t;
                 pl.bm = c.bm;
@@ -440,7 +450,9 @@ Plan plan_bwd_data(const Shape &s)
             const double a = order && unitStride ? avgTapsPos : avgTaps;
             const double m = order && unitStride ? (double)maxTapsPos : (double)maxTaps;
             int sp = 1;
-            const double t = best_split(kGatherCost, c, tiles, a * chunksPerTap, m * chunksPerTap, pl.outElems, &sp);
+            const bool balanced = order && unitStride && s.IH * s.IW <= kMaxBalancedPositions;
+            const double t = best_split(kGatherCost, c, tiles, a * chunksPerTap, m * chunksPerTap, pl.outElems, &sp, 1,
+                                        balanced);
             if (t < best) {
                 best = t;
                 trial.bm = c.bm;
@@ -516,16 +528,6 @@ Plan plan_bwd_weight(const Shape &s)
     return pl;
 }
 
-int make_plan(int op, const Shape &s, Plan *pl)
-{
-    switch (op) {
-    case MI355CONV_OP_FWD: *pl = plan_fwd(s); return MI355CONV_OK;
-    case MI355CONV_OP_BWD_DATA: *pl = plan_bwd_data(s); return MI355CONV_OK;
-    case MI355CONV_OP_BWD_WEIGHT: *pl = plan_bwd_weight(s); return MI355CONV_OK;
-    default: return MI355CONV_ERR_UNSUPPORTED;
-    }
-}
-
 int hip_fail(hipError_t e)
 {
     snprintf(t_hipError, sizeof t_hipError, "%s", hipGetErrorString(e));
@@ -556,17 +558,135 @@ void fill_gather_params(GatherGemmParams &g, const Plan &pl)
     for (int i = 0; i < kMaxPhases; ++i) g.phase[i] = pl.phase[i];
 }
 
-// (y,x,n) row order on a small map: order the positions by the number of taps inside the image
+// Longest-first dealing of a launch's workgroups to the 256 CUs.  unitWork[u] is the length of
+// the workgroups of unit u (a position or a tap), each unit holding perUnit workgroups; units
+// come ranked by descending length.  While the whole grid is resident, workgroup ids 256 apart
+// share a CU, so CU c holds ids c, c + 256, ...: every item goes to the least loaded CU that
+// still has a free id, CUs with equal contents are made neighbours, and the permutation comes
+// out as a few runs.  Returns false (identity order, still longest first) when the grid is
+// not resident at once or the runs do not fit.
+bool build_balance_runs(const int *unitWork, int nUnits, int perUnit, int grid, int resident, BalanceRuns *out)
+{
+    out->n = 0;
+    constexpr int cus = 256;
+    if (grid <= cus || grid > cus * resident || resident > 8 || nUnits > 256) return false;
+    const int laps = grid / cus, extra = grid % cus;
+    struct Deal {
+        int load[cus], cnt[cus];
+        short cls[cus][8];
+        int worst;
+    };
+    // items of unit u go, heaviest unit first, to the least loaded column in [c0, c1) with a free
+    // place (capacity cap); take[u] items of each unit
+    auto lpt = [&](Deal &d, const int *take, int c0, int c1, int cap) -> bool {
+        for (int u = 0; u < nUnits; ++u)
+            for (int j = 0; j < take[u]; ++j) {
+                int best = -1;
+                for (int c = c0; c < c1; ++c)
+                    if (d.cnt[c] < cap && (best < 0 || d.load[c] < d.load[best])) best = c;
+                if (best < 0) return false;
+                d.cls[best][d.cnt[best]++] = (short)u;
+                d.load[best] += unitWork[u];
+            }
+        return true;
+    };
+    auto fresh = [&](Deal &d) {
+        for (int c = 0; c < cus; ++c) {
+            d.load[c] = 0;
+            d.cnt[c] = 0;
+            for (int l = 0; l < 8; ++l) d.cls[c][l] = -1;
+        }
+    };
+    auto finish = [&](Deal &d) {
+        d.worst = 0;
+        for (int c = 0; c < cus; ++c)
+            if (d.load[c] > d.worst) d.worst = d.load[c];
+    };
+    // Two dealings, the better one is kept.  The first `extra` columns hold one item more than
+    // the others: (a) give them the lightest items up front, then deal the rest to the other
+    // columns; (b) deal everything to all columns, the roomier ones last among equals.
+    static thread_local Deal a, bdeal;
+    int light[256], heavy[256];
+    {
+        long long need = (long long)(laps + 1) * extra;
+        for (int u = nUnits - 1; u >= 0; --u) {
+            const int t = (int)(need < perUnit ? need : perUnit);
+            light[u] = t;
+            heavy[u] = perUnit - t;
+            need -= t;
+        }
+    }
+    fresh(a);
+    bool okA = lpt(a, light, 0, extra, laps + 1) && lpt(a, heavy, extra, cus, laps);
+    if (okA) finish(a);
+    fresh(bdeal);
+    bool okB = true;
+    {
+        int all[256];
+        for (int u = 0; u < nUnits; ++u) all[u] = perUnit;
+        // columns with the smaller capacity first among equal loads: scan them first
+        Deal &d = bdeal;
+        for (int u = 0; u < nUnits && okB; ++u)
+            for (int j = 0; j < all[u]; ++j) {
+                int best = -1;
+                for (int k = 0; k < cus; ++k) {
+                    const int c = (k + extra) % cus;   // order: extra .. 255, then 0 .. extra-1
+                    const int cap = laps + (c < extra ? 1 : 0);
+                    if (d.cnt[c] < cap && (best < 0 || d.load[c] < d.load[best])) best = c;
+                }
+                if (best < 0) { okB = false; break; }
+                d.cls[best][d.cnt[best]++] = (short)u;
+                d.load[best] += unitWork[u];
+            }
+    }
+    if (okB) finish(bdeal);
+    if (!okA && !okB) return false;
+    Deal &d = (okA && (!okB || a.worst <= bdeal.worst)) ? a : bdeal;
+    short (*cls)[8] = d.cls;
+    // neighbours with equal contents: sort each capacity group by its list of units
+    int col[cus];
+    for (int c = 0; c < cus; ++c) col[c] = c;
+    auto less = [&](int x, int y) {
+        for (int l = 0; l < 8; ++l)
+            if (cls[x][l] != cls[y][l]) return cls[x][l] < cls[y][l];
+        return false;
+    };
+    std::stable_sort(col, col + extra, less);
+    std::stable_sort(col + extra, col + cus, less);
+    // emit runs lap by lap; items of one unit are interchangeable
+    int emitted[256];
+    for (int u = 0; u < nUnits && u < 256; ++u) emitted[u] = 0;
+    int n = 0, prevUnit = -1;
+    for (int l = 0; l <= laps; ++l) {
+        const int width = l < laps ? cus : extra;
+        for (int c = 0; c < width; ++c) {
+            const int u = cls[col[c]][l];
+            if (u < 0) return false;
+            if (u != prevUnit) {
+                if (n == kMaxBalanceRuns) { out->n = 0; return false; }
+                out->idStart[n] = l * cus + c;
+                out->rankStart[n] = u * perUnit + emitted[u];
+                ++n;
+                prevUnit = u;
+            }
+            ++emitted[u];
+        }
+    }
+    out->n = n;
+    return true;
+}
+
+// (y,x,n) row order on a small map: rank the positions by the number of taps inside the image
 // (= stages of their tiles), most first.  Only for the single-phase cases (forward, unit-stride
 // backward-data), where a row tile lies on one position.
-void set_balance(GatherGemmParams &g, const Shape &s, const Plan &pl, bool bwd)
+void plan_balance_gather(const Shape &s, Plan &pl, bool bwd)
 {
-    g.balance = 0;
+    pl.balance = 0;
     if (!pl.posMajor || pl.elem || pl.nPhases != 1 || s.N % pl.bm != 0) return;
     if (bwd && (s.sh != 1 || s.sw != 1)) return;
     const int dh = bwd ? s.IH : s.OH, dw = bwd ? s.IW : s.OW;
     const int nPos = dh * dw;
-    if (nPos > kMaxBalancedPositions || pl.grid < 512) return;
+    if (nPos > kMaxBalancedPositions || pl.grid <= 256) return;
     int taps[kMaxBalancedPositions];
     int lo = 1 << 30, hi = 0;
     for (int i = 0; i < dh; ++i)
@@ -585,9 +705,108 @@ void set_balance(GatherGemmParams &g, const Shape &s, const Plan &pl, bool bwd)
     int order[kMaxBalancedPositions];
     for (int i = 0; i < nPos; ++i) order[i] = i;
     std::stable_sort(order, order + nPos, [&](int a, int b) { return taps[a] > taps[b]; });
-    for (int i = 0; i < nPos; ++i) g.posOrder[i] = (unsigned char)order[i];
-    g.rowTilesPerPos = s.N / pl.bm;
-    g.balance = 1;
+    int work[kMaxBalancedPositions];
+    for (int i = 0; i < nPos; ++i) {
+        pl.order[i] = (unsigned char)order[i];
+        work[i] = taps[order[i]];
+    }
+    pl.itemsPerClassUnit = (s.N / pl.bm) * pl.tilesN * pl.split;
+    const int resident = pl.bm * pl.bn <= 64 * 64 ? 4 : 2;
+    build_balance_runs(work, nPos, pl.itemsPerClassUnit, pl.grid, resident, &pl.runs);
+    pl.balance = 1;
+}
+
+// Backward-weight in (oh,ow,n) order: rank the taps by the number of output positions at which
+// they are inside the image.
+void plan_balance_wgrad(const Shape &s, Plan &pl)
+{
+    pl.balance = 0;
+    const int nTaps = s.FH * s.FW;
+    if (!pl.posMajor || !pl.fast || s.IC % pl.bn != 0 || nTaps > kMaxBalancedTaps || pl.grid <= 256) return;
+    int live[kMaxBalancedTaps];
+    int lo = 1 << 30, hi = 0;
+    for (int fh = 0; fh < s.FH; ++fh)
+        for (int fw = 0; fw < s.FW; ++fw) {
+            int lh = 0, lw = 0;
+            for (int oh = 0; oh < s.OH; ++oh) lh += (unsigned)(oh * s.sh - s.ph + fh) < (unsigned)s.IH;
+            for (int ow = 0; ow < s.OW; ++ow) lw += (unsigned)(ow * s.sw - s.pw + fw) < (unsigned)s.IW;
+            const int t = lh * lw;
+            live[fh * s.FW + fw] = t;
+            if (t < lo) lo = t;
+            if (t > hi) hi = t;
+        }
+    if (lo == hi) return;
+    int order[kMaxBalancedTaps];
+    for (int i = 0; i < nTaps; ++i) order[i] = i;
+    std::stable_sort(order, order + nTaps, [&](int a, int b) { return live[a] > live[b]; });
+    int work[kMaxBalancedTaps];
+    for (int i = 0; i < nTaps; ++i) {
+        pl.order[i] = (unsigned char)order[i];
+        work[i] = live[order[i]];
+    }
+    pl.itemsPerClassUnit = (s.IC / pl.bn) * pl.tilesM * pl.split;
+    const int resident = pl.bm * pl.bn <= 64 * 64 ? 4 : pl.bm * pl.bn >= 128 * 128 ? 1 : 2;
+    build_balance_runs(work, nTaps, pl.itemsPerClassUnit, pl.grid, resident, &pl.runs);
+    pl.balance = 1;
+}
+
+// Plans depend on the descriptor and the tuning overrides only; the last ones are kept in a small
+// direct-mapped table so that the enqueue path does not repeat the search (and the
+// longest-first dealing) on every call.
+struct PlanKey {
+    int v[17];
+    bool operator==(const PlanKey &o) const { return memcmp(v, o.v, sizeof v) == 0; }
+};
+struct PlanSlot {
+    bool used = false;
+    PlanKey key;
+    Plan plan;
+};
+constexpr int kPlanSlots = 256;
+std::mutex g_planMutex;
+PlanSlot *g_planTable = nullptr;   // allocated on first use, never freed
+
+int make_plan(int op, const Shape &s, Plan *pl)
+{
+    if (op != MI355CONV_OP_FWD && op != MI355CONV_OP_BWD_DATA && op != MI355CONV_OP_BWD_WEIGHT)
+        return MI355CONV_ERR_UNSUPPORTED;
+    PlanKey k;
+    const int vals[17] = {op, s.N, s.IH, s.IW, s.IC, s.OC, s.FH, s.FW, s.sh, s.sw, s.ph, s.pw,
+                          g_forceVariant.load(), g_forceSplit.load(), g_forceBM.load(), g_forceBN.load(),
+                          g_forcePosMajor.load()};
+    memcpy(k.v, vals, sizeof vals);
+    unsigned h = 2166136261u;
+    for (int i = 0; i < 17; ++i) h = (h ^ (unsigned)k.v[i]) * 16777619u;
+    const int slot = (int)(h % kPlanSlots);
+    {
+        std::lock_guard<std::mutex> lock(g_planMutex);
+        if (g_planTable && g_planTable[slot].used && g_planTable[slot].key == k) {
+            *pl = g_planTable[slot].plan;
+            return MI355CONV_OK;
+        }
+    }
+    switch (op) {
+    case MI355CONV_OP_FWD:
+        *pl = plan_fwd(s);
+        if (pl->variant == MI355CONV_VARIANT_MFMA) plan_balance_gather(s, *pl, false);
+        break;
+    case MI355CONV_OP_BWD_DATA:
+        *pl = plan_bwd_data(s);
+        if (pl->variant == MI355CONV_VARIANT_MFMA) plan_balance_gather(s, *pl, true);
+        break;
+    default:
+        *pl = plan_bwd_weight(s);
+        if (pl->variant == MI355CONV_VARIANT_MFMA) plan_balance_wgrad(s, *pl);
+        break;
+    }
+    {
+        std::lock_guard<std::mutex> lock(g_planMutex);
+        if (!g_planTable) g_planTable = new PlanSlot[kPlanSlots];
+        g_planTable[slot].key = k;
+        g_planTable[slot].plan = *pl;
+        g_planTable[slot].used = true;
+    }
+    return MI355CONV_OK;
 }
 
 int run_gather(const float *A, const float *B, float *out, const Shape &s, const Plan &pl, bool bwd,
@@ -612,7 +831,12 @@ int run_gather(const float *A, const float *B, float *out, const Shape &s, const
     g.aBytes = (unsigned)((long long)g.Nimg * g.SH * g.SW * g.SC * 4);
     g.bBytes = (unsigned)((long long)s.OC * s.FH * s.FW * s.IC * 4);
     fill_gather_params(g, pl);
-    set_balance(g, s, pl, bwd);
+    g.balance = pl.balance;
+    if (pl.balance) {
+        g.rowTilesPerPos = s.N / pl.bm;
+        g.runs = pl.runs;
+        memcpy(g.posOrder, pl.order, sizeof g.posOrder);
+    }
     hipError_t e = pl.elem ? launch_gather_elem(g, bwd, pl.bm, pl.bn, pl.grid, st)
                            : launch_gather_gemm(g, bwd, pl.bm, pl.bn, pl.grid, st);
     if (e != hipSuccess) return hip_fail(e);
@@ -682,7 +906,8 @@ int conv2d_fwd(const float *X, const float *W, float *Y, const conv2d_desc *d, v
     Plan pl;
     int rc = check_desc(d, &s);
     if (rc != MI355CONV_OK) return rc;
-    pl = plan_fwd(s);
+    rc = make_plan(MI355CONV_OP_FWD, s, &pl);
+    if (rc != MI355CONV_OK) return rc;
     rc = check_buffers(X, W, Y, pl, ws, ws_bytes);
     if (rc != MI355CONV_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -700,7 +925,8 @@ int conv2d_bwd_data(const float *dY, const float *W, float *dX, const conv2d_des
     Plan pl;
     int rc = check_desc(d, &s);
     if (rc != MI355CONV_OK) return rc;
-    pl = plan_bwd_data(s);
+    rc = make_plan(MI355CONV_OP_BWD_DATA, s, &pl);
+    if (rc != MI355CONV_OK) return rc;
     rc = check_buffers(dY, W, dX, pl, ws, ws_bytes);
     if (rc != MI355CONV_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -724,7 +950,8 @@ int conv2d_bwd_weight(const float *X, const float *dY, float *dW, const conv2d_d
     Plan pl;
     int rc = check_desc(d, &s);
     if (rc != MI355CONV_OK) return rc;
-    pl = plan_bwd_weight(s);
+    rc = make_plan(MI355CONV_OP_BWD_WEIGHT, s, &pl);
+    if (rc != MI355CONV_OK) return rc;
     rc = check_buffers(X, dY, dW, pl, ws, ws_bytes);
     if (rc != MI355CONV_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -755,6 +982,15 @@ int conv2d_bwd_weight(const float *X, const float *dY, float *dW, const conv2d_d
     w.divFW = make_fastdiv((unsigned)s.FW);
     w.divTilesN = make_fastdiv((unsigned)pl.tilesN);
     w.divSplit = make_fastdiv((unsigned)pl.split);
+    w.balance = pl.balance;
+    w.tilesM = pl.tilesM;
+    if (pl.balance) {
+        w.tilesPerTap = s.IC / pl.bn;
+        w.divTilesPerTap = make_fastdiv((unsigned)w.tilesPerTap);
+        w.divPerTap = make_fastdiv((unsigned)(w.tilesPerTap * pl.tilesM * pl.split));
+        w.runs = pl.runs;
+        memcpy(w.tapOrder, pl.order, sizeof w.tapOrder);
+    }
     hipError_t e = pl.fast ? launch_wgrad_fast(w, pl.bm, pl.bn, pl.grid, st)
                            : launch_wgrad(w, pl.bm, pl.bn, pl.elem != 0, pl.grid, st);
     if (e != hipSuccess) return hip_fail(e);

@@ -16,6 +16,20 @@ constexpr int kThreads = 256;     // every MFMA kernel runs 4 wavefronts per wor
 constexpr int kBK = 32;           // reduction elements staged per LDS stage
 constexpr int kMaxPhases = 16;    // sh*sw limit of the MFMA backward-data variant
 constexpr int kMaxBalancedPositions = 256;
+constexpr int kMaxBalancedTaps = 128;
+constexpr int kMaxBalanceRuns = 48;
+
+// Load balancing for launches whose workgroups differ in length (small maps in (y,x,n) order,
+// where a tile's stage count is the number of filter taps / output positions inside the
+// image).  Work items are ranked by descending length; the host deals them to the 256 CUs
+// longest-first (workgroup ids 256 apart share a CU while the whole grid is resident) and
+// writes the resulting permutation as runs: ids [idStart[r], idStart[r+1]) take the ranks
+// rankStart[r], rankStart[r]+1, ...  n = 0 means the identity.
+struct BalanceRuns {
+    int n;
+    int idStart[kMaxBalanceRuns];
+    int rankStart[kMaxBalanceRuns];
+};
 
 // Division by a launch-invariant divisor with one multiply-high and two shifts (round-up
 // method of Granlund & Montgomery, "Division by invariant integers using multiplication").
@@ -73,14 +87,14 @@ struct GatherGemmParams {
     int xcdUnit;          // consecutive logical workgroup ids kept on one XCD
     int nPhases;
     // Load balancing for (y,x,n) row order on small maps, where a tile's work is the number of
-    // taps inside the image at its position (4, 6 or 9 of 9 for a padded 3x3 filter): row tiles
-    // are taken position by position in posOrder (most taps first) and the workgroup ids of
-    // every second lap of 256 run backwards, so that the workgroups that end up on one CU
-    // (ids 256 apart) mix long and short tiles.  0 = off.
+    // taps inside the image at its position (4, 6 or 9 of 9 for a padded 3x3 filter): the
+    // workgroup id is mapped to a rank (runs), and ranks enumerate the row tiles position by
+    // position in posOrder (most taps first).  0 = off.
     int balance;
     int rowTilesPerPos;   // Nimg / BM
     FastDiv divN;         // by Nimg
     GatherPhase phase[kMaxPhases];
+    BalanceRuns runs;
     unsigned char posOrder[kMaxBalancedPositions];
 };
 
@@ -104,6 +118,15 @@ struct WgradParams {
     unsigned xBytes, gBytes;          // tensor sizes in bytes (below 2^31): buffer-load range checks
     FastDiv divOHOW, divOW, divN;     // by OH*OW, OW and N
     FastDiv divIC, divFW, divTilesN, divSplit;
+    // (oh,ow,n) order: a tile's live stages are the output positions at which its filter tap is
+    // inside the image.  With balance set (needs IC % BN == 0: one tap per tile) ranks enumerate
+    // the tiles tap by tap in tapOrder (most positions first); see BalanceRuns.
+    int balance;
+    int tilesPerTap;      // IC / BN
+    int tilesM;
+    FastDiv divTilesPerTap, divPerTap;   // by tilesPerTap and by tilesPerTap * tilesM * split
+    BalanceRuns runs;
+    unsigned char tapOrder[kMaxBalancedTaps];
 };
 
 // MI355X spreads consecutive workgroup ids round-robin over its 8 XCDs, each with its own
@@ -111,14 +134,16 @@ struct WgradParams {
 // that share operand tiles) run on one XCD, while units are still dealt round-robin so every
 // XCD gets the same mix of long and short tiles.  Ids past the last whole group of 8 units
 // keep their value.  A bijection on [0, grid).
-// Workgroup ids 256 apart share a CU when the whole grid is resident.  Reverse every second lap
-// of 256 ids (whole laps only): with work sorted in descending order along the ids, a CU then
-// gets one long and one short item per pair of laps.  A bijection on [0, grid).
-__device__ __forceinline__ int lap_snake(int bid, int grid)
+// Rank of workgroup id `bid` under the host's longest-first dealing.  Lane i looks at run i
+// (there are fewer than 64): the run is the last one that starts at or before bid.
+__device__ __forceinline__ int balanced_rank(int bid, const BalanceRuns &b)
 {
-    const int lap = bid >> 8;
-    if ((lap & 1) == 0 || (lap + 1) * 256 > grid) return bid;
-    return (lap << 8) + 255 - (bid & 255);
+    static_assert(kMaxBalanceRuns < 64, "one lane per run");
+    if (b.n == 0) return bid;
+    const int lane = threadIdx.x & 63;
+    const int start = lane < b.n ? b.idStart[lane] : 0x7fffffff;
+    const int r = __popcll(__ballot(bid >= start)) - 1;   // idStart[0] == 0
+    return b.rankStart[r] + (bid - b.idStart[r]);
 }
 
 __device__ __forceinline__ int xcd_remap(int bid, int grid, int unit)

@@ -55,7 +55,7 @@ __device__ __forceinline__ GatherTile gather_tile_setup(const GatherGemmParams &
                                                         int *rowX, int *outRow)
 {
     const int tid = threadIdx.x;
-    int bid = p.balance ? lap_snake(blockIdx.x, gridDim.x) : xcd_remap(blockIdx.x, gridDim.x, p.xcdUnit);
+    int bid = p.balance ? balanced_rank(blockIdx.x, p.runs) : xcd_remap(blockIdx.x, gridDim.x, p.xcdUnit);
     const int tn = bid % p.tilesN;
     bid /= p.tilesN;
     const int slice = bid % p.split;

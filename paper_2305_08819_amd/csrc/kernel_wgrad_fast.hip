@@ -67,11 +67,22 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
     const long long expClk0 = clock64();
 #endif
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int bid = xcd_remap(blockIdx.x, gridDim.x, p.xcdUnit);
-    const int rest = (int)fast_div((unsigned)bid, p.divTilesN);
-    const int tn = bid - rest * p.tilesN;
-    const int tmo = (int)fast_div((unsigned)rest, p.divSplit);
-    const int slice = rest - tmo * p.split;
+    int tn, tmo, slice;
+    if (PM && p.balance) {   // tiles enumerated tap by tap, taps with the most live positions first
+        const int rank = balanced_rank(blockIdx.x, p.runs);
+        const int tapRank = (int)fast_div((unsigned)rank, p.divPerTap);
+        const int inner = rank - tapRank * (p.tilesPerTap * p.tilesM * p.split);
+        const int r2 = (int)fast_div((unsigned)inner, p.divTilesPerTap);
+        tn = p.tapOrder[tapRank] * p.tilesPerTap + (inner - r2 * p.tilesPerTap);
+        tmo = (int)fast_div((unsigned)r2, p.divSplit);
+        slice = r2 - tmo * p.split;
+    } else {
+        const int bid = xcd_remap(blockIdx.x, gridDim.x, p.xcdUnit);
+        const int rest = (int)fast_div((unsigned)bid, p.divTilesN);
+        tn = bid - rest * p.tilesN;
+        tmo = (int)fast_div((unsigned)rest, p.divSplit);
+        slice = rest - tmo * p.split;
+    }
     const int oc0 = tmo * BM, col0 = tn * BN;
     const int Ktot = p.FH * p.FW * p.IC;
     const int ohow = p.OH * p.OW;
