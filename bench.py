@@ -29,7 +29,8 @@ PEAK_HBM_GBS = 8000.0
 OPS = ("fwd", "bwd_data", "bwd_weight")
 # HBM bytes per operator launch of the default workload (C2), from FETCH_SIZE + WRITE_SIZE scaled by a
 # 256 MiB copy (profiles/bench_C2_kernel_trace.md); bwd_weight = main kernel + slice reduce.
-MEASURED_TRAFFIC_BYTES = {"C2": {"fwd": 80.8e6, "bwd_data": 78.9e6, "bwd_weight": 115.6e6 + 21.3e6}}
+MEASURED_TRAFFIC_BYTES = {"C2": {"fwd": 56.3e6 + 16.8e6, "bwd_data": 40.8e6 + 33.6e6,
+                                 "bwd_weight": 84.4e6 + 8.3e6 + 8.3e6 + 0.3e6}}
 KERNEL_OF_OP = {"fwd": "gather_gemm_kernel<fwd>", "bwd_data": "gather_gemm_kernel<bwd_data>",
                 "bwd_weight": "wgrad_fast_kernel + slice_reduce_kernel"}
 
@@ -110,16 +111,21 @@ def fwd_bytes(l):
     return 4 * (l.N * l.IH * l.IW * l.IC + l.OC * l.K + l.M * l.OC)
 
 
-def cpu_baseline(layer, host, repeats=3):
-    """The oracle as it stands, timed on the host cores on the same layer (all three operators)."""
+def cpu_baseline(layer, host, min_seconds=12.0):
+    """The oracle as it stands, timed on the host cores on the same layer (all three operators),
+    repeated until about min_seconds of wall time have passed."""
     import oracle
     s, p = layer.stride, layer.pad
+    repeats = 0
     t0 = time.perf_counter()
-    for _ in range(repeats):
+    while True:
         oracle.conv2d_fwd(host["X"], host["W"], s, p)
         oracle.conv2d_bwd_data(host["G"], host["W"], (layer.IH, layer.IW), s, p)
         oracle.conv2d_bwd_weight(host["X"], host["G"], (layer.FH, layer.FW), s, p)
-    dt = time.perf_counter() - t0
+        repeats += 1
+        dt = time.perf_counter() - t0
+        if dt >= min_seconds or repeats >= 200:
+            break
     return {"value": round(3 * layer.flops * repeats / dt / 1e12, 6), "unit": "TFLOP/s",
             "cores": oracle.num_threads(), "kind": "oracle",
             "sample": "%d x (fwd+bwd_data+bwd_weight) of %s at full size, %.1f s wall"

@@ -576,20 +576,6 @@ bool build_balance_runs(const int *unitWork, int nUnits, int perUnit, int grid, 
         short cls[cus][8];
         int worst;
     };
-    // items of unit u go, heaviest unit first, to the least loaded column in [c0, c1) with a free
-    // place (capacity cap); take[u] items of each unit
-    auto lpt = [&](Deal &d, const int *take, int c0, int c1, int cap) -> bool {
-        for (int u = 0; u < nUnits; ++u)
-            for (int j = 0; j < take[u]; ++j) {
-                int best = -1;
-                for (int c = c0; c < c1; ++c)
-                    if (d.cnt[c] < cap && (best < 0 || d.load[c] < d.load[best])) best = c;
-                if (best < 0) return false;
-                d.cls[best][d.cnt[best]++] = (short)u;
-                d.load[best] += unitWork[u];
-            }
-        return true;
-    };
     auto fresh = [&](Deal &d) {
         for (int c = 0; c < cus; ++c) {
             d.load[c] = 0;
@@ -602,74 +588,102 @@ bool build_balance_runs(const int *unitWork, int nUnits, int perUnit, int grid, 
         for (int c = 0; c < cus; ++c)
             if (d.load[c] > d.worst) d.worst = d.load[c];
     };
-    // Two dealings, the better one is kept.  The first `extra` columns hold one item more than
-    // the others: (a) give them the lightest items up front, then deal the rest to the other
-    // columns; (b) deal everything to all columns, the roomier ones last among equals.
+    // Columns are slots (balance_slot): column j of the last, partial lap exists iff some id
+    // 256 * laps + c with c < extra has j as its slot in the whole laps - ids of the partial lap
+    // keep their value, so those are the columns c' with slot-inverse below `extra`.
+    bool roomy[cus];
+    for (int j = 0; j < cus; ++j) roomy[j] = false;
+    for (int c = 0; c < extra; ++c) roomy[(c & 7) * 32 + (c >> 3)] = true;
+    // Two dealings, the better one is kept.  The roomy columns hold one item more than the
+    // others: (a) give them the lightest items up front, then deal the rest to the other
+    // columns; (b) deal everything to all columns, the roomy ones last among equals.
+    auto lpt = [&](Deal &d, const int *take, int pass) -> bool {   // pass 0: roomy only, 1: others only, 2: all
+        for (int u = 0; u < nUnits; ++u)
+            for (int j = 0; j < take[u]; ++j) {
+                int best = -1;
+                for (int phase = 0; phase < 2; ++phase)     // non-roomy columns win ties
+                    for (int c = 0; c < cus; ++c) {
+                        if (roomy[c] != (phase == 1)) continue;
+                        if (pass == 0 && !roomy[c]) continue;
+                        if (pass == 1 && roomy[c]) continue;
+                        const int cap = laps + (roomy[c] ? 1 : 0);
+                        if (d.cnt[c] < cap && (best < 0 || d.load[c] < d.load[best])) best = c;
+                    }
+                if (best < 0) return false;
+                d.cls[best][d.cnt[best]++] = (short)u;
+                d.load[best] += unitWork[u];
+            }
+        return true;
+    };
     static thread_local Deal a, bdeal;
-    int light[256], heavy[256];
+    int light[256], heavy[256], all[256];
     {
         long long need = (long long)(laps + 1) * extra;
         for (int u = nUnits - 1; u >= 0; --u) {
             const int t = (int)(need < perUnit ? need : perUnit);
             light[u] = t;
             heavy[u] = perUnit - t;
+            all[u] = perUnit;
             need -= t;
         }
     }
     fresh(a);
-    bool okA = lpt(a, light, 0, extra, laps + 1) && lpt(a, heavy, extra, cus, laps);
+    const bool okA = lpt(a, light, 0) && lpt(a, heavy, 1);
     if (okA) finish(a);
     fresh(bdeal);
-    bool okB = true;
-    {
-        int all[256];
-        for (int u = 0; u < nUnits; ++u) all[u] = perUnit;
-        // columns with the smaller capacity first among equal loads: scan them first
-        Deal &d = bdeal;
-        for (int u = 0; u < nUnits && okB; ++u)
-            for (int j = 0; j < all[u]; ++j) {
-                int best = -1;
-                for (int k = 0; k < cus; ++k) {
-                    const int c = (k + extra) % cus;   // order: extra .. 255, then 0 .. extra-1
-                    const int cap = laps + (c < extra ? 1 : 0);
-                    if (d.cnt[c] < cap && (best < 0 || d.load[c] < d.load[best])) best = c;
-                }
-                if (best < 0) { okB = false; break; }
-                d.cls[best][d.cnt[best]++] = (short)u;
-                d.load[best] += unitWork[u];
-            }
-    }
+    const bool okB = lpt(bdeal, all, 2);
     if (okB) finish(bdeal);
     if (!okA && !okB) return false;
     Deal &d = (okA && (!okB || a.worst <= bdeal.worst)) ? a : bdeal;
     short (*cls)[8] = d.cls;
-    // neighbours with equal contents: sort each capacity group by its list of units
-    int col[cus];
-    for (int c = 0; c < cus; ++c) col[c] = c;
-    auto less = [&](int x, int y) {
-        for (int l = 0; l < 8; ++l)
-            if (cls[x][l] != cls[y][l]) return cls[x][l] < cls[y][l];
+    // neighbours with equal contents: within each capacity group the columns' contents are
+    // reassigned in sorted order (column j takes the contents of abstract column col[j])
+    int col[cus], idxRoomy[cus], idxPlain[cus], nr = 0, np_ = 0;
+    for (int c = 0; c < cus; ++c) (roomy[c] ? idxRoomy[nr++] : idxPlain[np_++]) = c;
+    auto less = [&](int x, int y) {   // by the lengths of the contents, longest first
+        for (int l = 0; l < 8; ++l) {
+            const int wx = cls[x][l] < 0 ? -1 : unitWork[cls[x][l]], wy = cls[y][l] < 0 ? -1 : unitWork[cls[y][l]];
+            if (wx != wy) return wx > wy;
+        }
         return false;
     };
-    std::stable_sort(col, col + extra, less);
-    std::stable_sort(col + extra, col + cus, less);
-    // emit runs lap by lap; items of one unit are interchangeable
-    int emitted[256];
-    for (int u = 0; u < nUnits && u < 256; ++u) emitted[u] = 0;
-    int n = 0, prevUnit = -1;
+    {
+        int tmp[cus];
+        for (int i = 0; i < nr; ++i) tmp[i] = idxRoomy[i];
+        std::stable_sort(tmp, tmp + nr, less);
+        for (int i = 0; i < nr; ++i) col[idxRoomy[i]] = tmp[i];
+        for (int i = 0; i < np_; ++i) tmp[i] = idxPlain[i];
+        std::stable_sort(tmp, tmp + np_, less);
+        for (int i = 0; i < np_; ++i) col[idxPlain[i]] = tmp[i];
+    }
+    // emit runs in slot order; items of units of equal length are interchangeable, and such
+    // units are neighbours in the ranking, so a class of them is one range of ranks
+    int classOf[256], classBase[256], emitted[256], nClasses = 0;
+    for (int u = 0; u < nUnits; ++u) {
+        if (u == 0 || unitWork[u] != unitWork[u - 1]) {
+            classBase[nClasses] = u * perUnit;
+            emitted[nClasses] = 0;
+            ++nClasses;
+        }
+        classOf[u] = nClasses - 1;
+    }
+    int n = 0, prevClass = -1;
     for (int l = 0; l <= laps; ++l) {
         const int width = l < laps ? cus : extra;
         for (int c = 0; c < width; ++c) {
-            const int u = cls[col[c]][l];
+            // whole laps are walked by slot; in the partial lap id c sits in column slot(c)
+            const int column = l < laps ? c : (c & 7) * 32 + (c >> 3);
+            const int u = cls[col[column]][l];
             if (u < 0) return false;
-            if (u != prevUnit) {
+            const int k = classOf[u];
+            if (k != prevClass) {
                 if (n == kMaxBalanceRuns) { out->n = 0; return false; }
                 out->idStart[n] = l * cus + c;
-                out->rankStart[n] = u * perUnit + emitted[u];
+                out->rankStart[n] = classBase[k] + emitted[k];
                 ++n;
-                prevUnit = u;
+                prevClass = k;
             }
-            ++emitted[u];
+            ++emitted[k];
         }
     }
     out->n = n;

@@ -23,8 +23,8 @@ constexpr int kMaxBalanceRuns = 48;
 // where a tile's stage count is the number of filter taps / output positions inside the
 // image).  Work items are ranked by descending length; the host deals them to the 256 CUs
 // longest-first (workgroup ids 256 apart share a CU while the whole grid is resident) and
-// writes the resulting permutation as runs: ids [idStart[r], idStart[r+1]) take the ranks
-// rankStart[r], rankStart[r]+1, ...  n = 0 means the identity.
+// writes the resulting permutation as runs: slots [idStart[r], idStart[r+1]) (see balance_slot)
+// take the ranks rankStart[r], rankStart[r]+1, ...  n = 0: no dealing, ranks in id order.
 struct BalanceRuns {
     int n;
     int idStart[kMaxBalanceRuns];
@@ -134,16 +134,28 @@ struct WgradParams {
 // that share operand tiles) run on one XCD, while units are still dealt round-robin so every
 // XCD gets the same mix of long and short tiles.  Ids past the last whole group of 8 units
 // keep their value.  A bijection on [0, grid).
+// Column of the dealing that hardware workgroup id `bid` belongs to, as an id: within every
+// whole lap of 256 ids the 32 ids that run on one XCD (bid % 8 equal) become neighbours, so
+// that a run of consecutive ranks - tiles that share operand rows - stays on one XCD and its
+// L2.  Ids of the last, partial lap keep their value.  The host uses the same function.
+__host__ __device__ __forceinline__ int balance_slot(int bid, int grid)
+{
+    const int lap = bid >> 8;
+    if ((lap + 1) * 256 > grid) return bid;
+    const int c = bid & 255;
+    return (lap << 8) + (c & 7) * 32 + (c >> 3);
+}
+
 // Rank of workgroup id `bid` under the host's longest-first dealing.  Lane i looks at run i
-// (there are fewer than 64): the run is the last one that starts at or before bid.
-__device__ __forceinline__ int balanced_rank(int bid, const BalanceRuns &b)
+// (there are fewer than 64): the run is the last one that starts at or before the slot.
+__device__ __forceinline__ int balanced_rank(int bid, int grid, const BalanceRuns &b)
 {
     static_assert(kMaxBalanceRuns < 64, "one lane per run");
-    if (b.n == 0) return bid;
+    const int slot = balance_slot(bid, grid);
     const int lane = threadIdx.x & 63;
     const int start = lane < b.n ? b.idStart[lane] : 0x7fffffff;
-    const int r = __popcll(__ballot(bid >= start)) - 1;   // idStart[0] == 0
-    return b.rankStart[r] + (bid - b.idStart[r]);
+    const int r = __popcll(__ballot(slot >= start)) - 1;   // idStart[0] == 0
+    return b.rankStart[r] + (slot - b.idStart[r]);
 }
 
 __device__ __forceinline__ int xcd_remap(int bid, int grid, int unit)

@@ -55,7 +55,8 @@ __device__ __forceinline__ GatherTile gather_tile_setup(const GatherGemmParams &
                                                         int *rowX, int *outRow)
 {
     const int tid = threadIdx.x;
-    int bid = p.balance ? balanced_rank(blockIdx.x, p.runs) : xcd_remap(blockIdx.x, gridDim.x, p.xcdUnit);
+    int bid = p.balance && p.runs.n ? balanced_rank(blockIdx.x, gridDim.x, p.runs)
+                                    : xcd_remap(blockIdx.x, gridDim.x, p.xcdUnit);
     const int tn = bid % p.tilesN;
     bid /= p.tilesN;
     const int slice = bid % p.split;

@@ -69,7 +69,7 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int tn, tmo, slice;
     if (PM && p.balance) {   // tiles enumerated tap by tap, taps with the most live positions first
-        const int rank = balanced_rank(blockIdx.x, p.runs);
+        const int rank = p.runs.n ? balanced_rank(blockIdx.x, gridDim.x, p.runs) : (int)blockIdx.x;
         const int tapRank = (int)fast_div((unsigned)rank, p.divPerTap);
         const int inner = rank - tapRank * (p.tilesPerTap * p.tilesM * p.split);
         const int r2 = (int)fast_div((unsigned)inner, p.divTilesPerTap);
