@@ -555,7 +555,12 @@ void fill_gather_params(GatherGemmParams &g, const Plan &pl)
     g.tilesN = pl.tilesN;
     g.xcdUnit = pl.tilesN * pl.split * 2;   // both column tiles, all slices, two neighbouring row tiles
     g.nPhases = pl.nPhases;
-    for (int i = 0; i < kMaxPhases; ++i) g.phase[i] = pl.phase[i];
+    for (int i = 0; i < kMaxPhases; ++i) {
+        g.phase[i] = pl.phase[i];
+        g.phaseStart[i] = i < pl.nPhases ? pl.phase[i].tileStart : 0x7fffffff;
+    }
+    g.divTilesN = make_fastdiv((unsigned)pl.tilesN);
+    g.divSplit = make_fastdiv((unsigned)pl.split);
 }
 
 // Longest-first dealing of a launch's workgroups to the 256 CUs.  unitWork[u] is the length of
@@ -842,15 +847,18 @@ int run_gather(const float *A, const float *B, float *out, const Shape &s, const
     g.FH = s.FH; g.FW = s.FW;
     g.sh = s.sh; g.sw = s.sw; g.ph = s.ph; g.pw = s.pw;
     g.divN = make_fastdiv((unsigned)s.N);
+    g.divChunksPerTap = make_fastdiv((unsigned)(g.SC / kBK > 0 ? g.SC / kBK : 1));
     g.aBytes = (unsigned)((long long)g.Nimg * g.SH * g.SW * g.SC * 4);
     g.bBytes = (unsigned)((long long)s.OC * s.FH * s.FW * s.IC * 4);
     fill_gather_params(g, pl);
     g.balance = pl.balance;
+    g.rowTilesPerPos = 1;
     if (pl.balance) {
         g.rowTilesPerPos = s.N / pl.bm;
         g.runs = pl.runs;
         memcpy(g.posOrder, pl.order, sizeof g.posOrder);
     }
+    g.divRowTilesPerPos = make_fastdiv((unsigned)g.rowTilesPerPos);
     hipError_t e = pl.elem ? launch_gather_elem(g, bwd, pl.bm, pl.bn, pl.grid, st)
                            : launch_gather_gemm(g, bwd, pl.bm, pl.bn, pl.grid, st);
     if (e != hipSuccess) return hip_fail(e);

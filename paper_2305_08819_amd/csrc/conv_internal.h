@@ -93,10 +93,55 @@ struct GatherGemmParams {
     int balance;
     int rowTilesPerPos;   // Nimg / BM
     FastDiv divN;         // by Nimg
+    FastDiv divTilesN, divSplit, divRowTilesPerPos, divChunksPerTap;   // chunks per tap = SC / kBK
+    int phaseStart[kMaxPhases];   // first row tile of each phase; INT_MAX past the last phase
     GatherPhase phase[kMaxPhases];
     BalanceRuns runs;
     unsigned char posOrder[kMaxBalancedPositions];
 };
+
+// The scalar fields of GatherGemmParams held in SGPRs from the kernel's first instructions on:
+// the compiler otherwise fetches each kernel argument where it is first used, one dependent
+// scalar load after the other all through the prologue.  Field names match GatherGemmParams, so
+// code templated on the parameter type takes either.
+struct GatherView {
+    const float *A;
+    const float *B;
+    float *C;
+    unsigned aBytes, bBytes;
+    int Nimg, SH, SW, SC, DH, DW, DC, FH, FW, sh, sw, ph, pw;
+    int posMajor, split;
+    long long sliceStride;
+    int tilesN, xcdUnit, nPhases, balance, rowTilesPerPos;
+    FastDiv divN, divTilesN, divSplit, divRowTilesPerPos, divChunksPerTap;
+    const int *phaseStart;
+    const GatherPhase *phase;
+    const BalanceRuns &runs;
+    const unsigned char *posOrder;
+};
+#if defined(__HIPCC__)
+#define MI355CONV_PIN(x) asm volatile("" : "+s"(x))
+__device__ __forceinline__ GatherView gather_view(const GatherGemmParams &p)
+{
+    GatherView v{p.A, p.B, p.C, p.aBytes, p.bBytes, p.Nimg, p.SH, p.SW, p.SC, p.DH, p.DW, p.DC, p.FH, p.FW,
+                 p.sh, p.sw, p.ph, p.pw, p.posMajor, p.split, p.sliceStride, p.tilesN, p.xcdUnit, p.nPhases,
+                 p.balance, p.rowTilesPerPos, p.divN, p.divTilesN, p.divSplit, p.divRowTilesPerPos,
+                 p.divChunksPerTap, p.phaseStart, p.phase, p.runs, p.posOrder};
+    MI355CONV_PIN(v.A); MI355CONV_PIN(v.B); MI355CONV_PIN(v.C);
+    MI355CONV_PIN(v.aBytes); MI355CONV_PIN(v.bBytes);
+    MI355CONV_PIN(v.Nimg); MI355CONV_PIN(v.SH); MI355CONV_PIN(v.SW); MI355CONV_PIN(v.SC);
+    MI355CONV_PIN(v.DH); MI355CONV_PIN(v.DW); MI355CONV_PIN(v.DC); MI355CONV_PIN(v.FH); MI355CONV_PIN(v.FW);
+    MI355CONV_PIN(v.sh); MI355CONV_PIN(v.sw); MI355CONV_PIN(v.ph); MI355CONV_PIN(v.pw);
+    MI355CONV_PIN(v.posMajor); MI355CONV_PIN(v.split); MI355CONV_PIN(v.sliceStride);
+    MI355CONV_PIN(v.tilesN); MI355CONV_PIN(v.xcdUnit); MI355CONV_PIN(v.nPhases);
+    MI355CONV_PIN(v.balance); MI355CONV_PIN(v.rowTilesPerPos);
+    MI355CONV_PIN(v.divN.mul); MI355CONV_PIN(v.divN.sh1); MI355CONV_PIN(v.divN.sh2);
+    MI355CONV_PIN(v.divTilesN.mul); MI355CONV_PIN(v.divTilesN.sh1); MI355CONV_PIN(v.divTilesN.sh2);
+    MI355CONV_PIN(v.divSplit.mul); MI355CONV_PIN(v.divSplit.sh1); MI355CONV_PIN(v.divSplit.sh2);
+    MI355CONV_PIN(v.divChunksPerTap.mul); MI355CONV_PIN(v.divChunksPerTap.sh1); MI355CONV_PIN(v.divChunksPerTap.sh2);
+    return v;
+}
+#endif
 
 // ---- backward-weight ---------------------------------------------------------------------
 // dW[oc, col] = sum over rows m=(n,oh,ow): G[m, oc] * X[n, oh*sh-ph+fh(col), ow*sw-pw+fw(col), ic(col)]

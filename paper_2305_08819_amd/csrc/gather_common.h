@@ -50,25 +50,25 @@ struct GatherTile {
 // order.  Where a tile wraps over image rows or images the rectangle is widened to the full
 // range, which only adds taps whose operands load as zeros.  All threads must call it; it
 // contains one barrier.
-template <int BM, int BN, bool BWD>
-__device__ __forceinline__ GatherTile gather_tile_setup(const GatherGemmParams &p, int *rowBase, int *rowY,
+template <int BM, int BN, bool BWD, class P>
+__device__ __forceinline__ GatherTile gather_tile_setup(const P &p, int *rowBase, int *rowY,
                                                         int *rowX, int *outRow)
 {
     const int tid = threadIdx.x;
     int bid = p.balance && p.runs.n ? balanced_rank(blockIdx.x, gridDim.x, p.runs)
                                     : xcd_remap(blockIdx.x, gridDim.x, p.xcdUnit);
-    const int tn = bid % p.tilesN;
-    bid /= p.tilesN;
-    const int slice = bid % p.split;
-    int tmGlobal = bid / p.split;
+    const int rest = (int)fast_div((unsigned)bid, p.divTilesN);
+    const int tn = bid - rest * p.tilesN;
+    int tmGlobal = (int)fast_div((unsigned)rest, p.divSplit);
+    const int slice = rest - tmGlobal * p.split;
     if (p.balance) {   // row tiles are enumerated by position rank
-        const int rank = tmGlobal / p.rowTilesPerPos;
+        const int rank = (int)fast_div((unsigned)tmGlobal, p.divRowTilesPerPos);
         tmGlobal = p.posOrder[rank] * p.rowTilesPerPos + (tmGlobal - rank * p.rowTilesPerPos);
     }
     int phase = 0;
-    if (BWD) {   // tile starts are ascending: the phase is the number of starts not above this tile
+    if (BWD) {   // phase starts are ascending: the phase is the number of starts not above this tile
 #pragma unroll
-        for (int i = 1; i < kMaxPhases; ++i) phase += (i < p.nPhases && tmGlobal >= p.phase[i].tileStart) ? 1 : 0;
+        for (int i = 1; i < kMaxPhases; ++i) phase += tmGlobal >= p.phaseStart[i] ? 1 : 0;
     }
     const GatherPhase ph = p.phase[phase];
     const int tmLocal = tmGlobal - ph.tileStart;
@@ -164,8 +164,8 @@ __device__ __forceinline__ GatherTile gather_tile_setup(const GatherGemmParams &
 // Epilogue: rows of a 32x32 block are spread over accumulator registers, columns over lanes.
 // The 16 destination-pixel indices of a block are fetched with four 16-byte LDS reads; output
 // offsets fit 32 bits because every tensor holds fewer than 2^31 elements.
-template <class T>
-__device__ __forceinline__ void gather_tile_store(const GatherGemmParams &p, int slice, int n0, const int *outRow,
+template <class T, class P>
+__device__ __forceinline__ void gather_tile_store(const P &p, int slice, int n0, const int *outRow,
                                                   const float16v (&acc)[T::MB][T::NB], int wm, int wn, int l32,
                                                   int lh)
 {

@@ -38,9 +38,10 @@ namespace mi355conv {
 // 16-byte load of four filter columns would be misaligned; the B tile is fetched with four
 // 4-byte loads per thread instead (e.g. the first layer's dX with 3 channels).
 template <int BM, int BN, int WAVES_M, bool BWD, bool BELEM = false>
-__global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGemmParams p)
+__global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGemmParams params)
 {
     STAMP(0);
+    const GatherView p = gather_view(params);
     using T = GG<BM, BN, WAVES_M, BWD>;
     extern __shared__ f4 smem_raw[];
     float *smem = reinterpret_cast<float *>(smem_raw);
@@ -64,8 +65,8 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     const int vCnt = tile.vHi >= tile.vLo ? tile.vHi - tile.vLo + 1 : 0;
     const int chunksPerTap = p.SC / kBK;
     const int nIter = uCnt * vCnt * chunksPerTap;
-    const int it0 = slice * nIter / p.split;          // nIter * split is far below 2^31
-    const int it1 = (slice + 1) * nIter / p.split;
+    const int it0 = (int)fast_div((unsigned)(slice * nIter), p.divSplit);          // nIter * split is far below 2^31
+    const int it1 = (int)fast_div((unsigned)((slice + 1) * nIter), p.divSplit);
 
     // ---- per-thread loader state --------------------------------------------------------
     // Operands are fetched with raw buffer loads: address = base + VGPR byte offset + SGPR byte
@@ -110,8 +111,8 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
 
     // reduction cursor: current tap (u,v) and chunk within the tap
     int chunk = 0, tapU = tile.uLo, tapV = tile.vLo;
-    if (it0 < it1) {
-        const int tapIdx = it0 / chunksPerTap;
+    if (it0 > 0 && it0 < it1) {   // only slices after the first start inside the tap list
+        const int tapIdx = (int)fast_div((unsigned)it0, p.divChunksPerTap);
         chunk = it0 - tapIdx * chunksPerTap;
         const int du = tapIdx / vCnt;
         tapU += du;
