@@ -174,6 +174,47 @@ struct WgradParams {
     unsigned char tapOrder[kMaxBalancedTaps];
 };
 
+// Scalar fields of WgradParams in SGPRs from the kernel's first instructions on (see GatherView).
+struct WgradView {
+    const float *X;
+    const float *G;
+    float *C;
+    int N, IH, IW, IC, OC, OH, OW, FH, FW, sh, sw, ph, pw;
+    int posMajor, split;
+    long long sliceStride;
+    int tilesN, xcdUnit, M, flushChunks;
+    unsigned xBytes, gBytes;
+    FastDiv divOHOW, divOW, divN, divIC, divFW, divTilesN, divSplit;
+    int balance, tilesPerTap, tilesM;
+    FastDiv divTilesPerTap, divPerTap;
+    const BalanceRuns &runs;
+    const unsigned char *tapOrder;
+};
+#if defined(__HIPCC__)
+__device__ __forceinline__ void pin_fastdiv(FastDiv &f)
+{
+    MI355CONV_PIN(f.mul); MI355CONV_PIN(f.sh1); MI355CONV_PIN(f.sh2);
+}
+__device__ __forceinline__ WgradView wgrad_view(const WgradParams &p)
+{
+    WgradView v{p.X, p.G, p.C, p.N, p.IH, p.IW, p.IC, p.OC, p.OH, p.OW, p.FH, p.FW, p.sh, p.sw, p.ph, p.pw,
+                p.posMajor, p.split, p.sliceStride, p.tilesN, p.xcdUnit, p.M, p.flushChunks, p.xBytes, p.gBytes,
+                p.divOHOW, p.divOW, p.divN, p.divIC, p.divFW, p.divTilesN, p.divSplit, p.balance, p.tilesPerTap,
+                p.tilesM, p.divTilesPerTap, p.divPerTap, p.runs, p.tapOrder};
+    MI355CONV_PIN(v.X); MI355CONV_PIN(v.G); MI355CONV_PIN(v.C);
+    MI355CONV_PIN(v.N); MI355CONV_PIN(v.IH); MI355CONV_PIN(v.IW); MI355CONV_PIN(v.IC); MI355CONV_PIN(v.OC);
+    MI355CONV_PIN(v.OH); MI355CONV_PIN(v.OW); MI355CONV_PIN(v.FH); MI355CONV_PIN(v.FW);
+    MI355CONV_PIN(v.sh); MI355CONV_PIN(v.sw); MI355CONV_PIN(v.ph); MI355CONV_PIN(v.pw);
+    MI355CONV_PIN(v.posMajor); MI355CONV_PIN(v.split); MI355CONV_PIN(v.sliceStride);
+    MI355CONV_PIN(v.tilesN); MI355CONV_PIN(v.xcdUnit); MI355CONV_PIN(v.M); MI355CONV_PIN(v.flushChunks);
+    MI355CONV_PIN(v.xBytes); MI355CONV_PIN(v.gBytes);
+    pin_fastdiv(v.divOHOW); pin_fastdiv(v.divOW); pin_fastdiv(v.divN); pin_fastdiv(v.divIC);
+    pin_fastdiv(v.divFW); pin_fastdiv(v.divTilesN); pin_fastdiv(v.divSplit);
+    MI355CONV_PIN(v.balance); MI355CONV_PIN(v.tilesPerTap); MI355CONV_PIN(v.tilesM);
+    return v;
+}
+#endif
+
 // MI355X spreads consecutive workgroup ids round-robin over its 8 XCDs, each with its own
 // L2.  Map the hardware id to a logical id so that `unit` consecutive logical ids (workgroups
 // that share operand tiles) run on one XCD, while units are still dealt round-robin so every

@@ -51,7 +51,7 @@ struct WF {
 // PM: rows in (oh, ow, n) order with N a multiple of 32 and OH*OW <= 64, so that a stage sits on
 // one output position and positions fit 64-bit masks.
 template <int BM, int BN, bool PM>
-__global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 64 * 64) ? WF_OCC64 : 2) void wgrad_fast_kernel(const WgradParams p)
+__global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 64 * 64) ? WF_OCC64 : 2) void wgrad_fast_kernel(const WgradParams params)
 {
     using T = WF<BM, BN>;
     extern __shared__ f4 smem_raw[];
@@ -59,6 +59,7 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
     float *Xs = Gs + 2 * T::G_STAGE;
 
     STAMP(0);
+    const WgradView p = wgrad_view(params);
 #if defined(EXP_STAMPS)
     if (threadIdx.x == 0 && blockIdx.x < 16384) {
         g_wstamps[blockIdx.x * 8 + 5] = __builtin_amdgcn_s_getreg((31 << 11) | 4);    // HW_ID
