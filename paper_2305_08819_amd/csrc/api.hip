@@ -181,11 +181,12 @@ void finish_plan(Plan &pl, int split)
 bool tile_compiled(int bm, int bn, bool gather)
 {
     if (gather) return (bm == 128 && (bn == 128 || bn == 64 || bn == 32)) || (bm == 64 && bn == 64);
-    return (bm == 128 || bm == 64) && (bn == 128 || bn == 64);
+    return ((bm == 128 || bm == 64) && (bn == 128 || bn == 64)) || (bm == 32 && bn == 128);
 }
 
 const TileCand kGatherTiles[] = {{128, 128, 0.88, 2}, {128, 64, 0.945, 2}, {64, 64, 0.945, 4}, {128, 32, 0.66, 3}};
-const TileCand kWgradTiles[] = {{128, 128, 0.80, 1}, {64, 128, 0.93, 2}, {128, 64, 0.94, 2}, {64, 64, 0.98, 4}};
+const TileCand kWgradTiles[] = {{128, 128, 0.80, 1}, {64, 128, 0.93, 2}, {128, 64, 0.94, 2}, {64, 64, 0.98, 4},
+                                {32, 128, 0.90, 3}};
 
 bool forced_tile(int *bm, int *bn, bool gather)
 {
@@ -502,22 +503,25 @@ Plan plan_bwd_weight(const Shape &s)
     int fbm = 0, fbn = 0;
     const bool haveForced = forced_tile(&fbm, &fbn, false);
     double best = 1e300;
-    for (const TileCand &c : kWgradTiles) {
-        if (pl.elem && c.bn != 64) continue;   // element-wise X loader is compiled for 64-wide tiles
-        if (haveForced && !(pl.elem && fbn != 64)) {
-            if (c.bm != fbm || c.bn != fbn) continue;
-        } else {
-            if (c.bm > 64 && c.bm / 2 >= s.OC) continue;
-            if (c.bn > 64 && c.bn / 2 >= Ktot) continue;
-        }
-        const long long tiles = (long long)ceil_div(s.OC, c.bm) * ceil_div(Ktot, c.bn);
-        int sp = 1;
-        const double t = best_split(kWgradCost, c, tiles, chunks * live, (double)chunks, pl.outElems, &sp);
-        if (t < best) {
-            best = t;
-            pl.bm = c.bm;
-            pl.bn = c.bn;
-            pl.split = sp;
+    for (int pass = 0; pass < 2 && pl.bm == 0; ++pass) {   // second pass: the forced tile does not apply here
+        for (const TileCand &c : kWgradTiles) {
+            if (pl.elem && c.bn != 64) continue;   // element-wise X loader is compiled for 64-wide tiles
+            if (c.bm == 32 && (!pl.fast || s.OC > 32)) continue;   // one block row: narrow outputs, fast kernel only
+            if (pass == 0 && haveForced && !(pl.elem && fbn != 64)) {
+                if (c.bm != fbm || c.bn != fbn) continue;
+            } else {
+                if (c.bm > 64 && c.bm / 2 >= s.OC) continue;
+                if (c.bn > 64 && c.bn / 2 >= Ktot && c.bm != 32) continue;
+            }
+            const long long tiles = (long long)ceil_div(s.OC, c.bm) * ceil_div(Ktot, c.bn);
+            int sp = 1;
+            const double t = best_split(kWgradCost, c, tiles, chunks * live, (double)chunks, pl.outElems, &sp);
+            if (t < best) {
+                best = t;
+                pl.bm = c.bm;
+                pl.bn = c.bn;
+                pl.split = sp;
+            }
         }
     }
     pl.posMajor = posMajor;

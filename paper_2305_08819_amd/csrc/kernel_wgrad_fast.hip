@@ -35,7 +35,8 @@ namespace mi355conv {
 namespace {
 template <int BM, int BN>
 struct WF {
-    static constexpr int WTM = BM / 2, WTN = BN / 2;
+    static constexpr int WAVES_M = BM >= 64 ? 2 : 1, WAVES_N = 4 / WAVES_M;   // a 32-row tile is one block row
+    static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     static constexpr int MB = WTM / 32, NB = WTN / 32;
     static constexpr int LDG = BM + 8, LDX = BN + 8;
     static constexpr int G_TPR = BM / 4, G_RPP = kThreads / G_TPR, PG = kBK / G_RPP;
@@ -266,7 +267,7 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
         }
     };
 
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / T::WAVES_N, wn = wave % T::WAVES_N;
     const int l32 = lane & 31, lh = lane >> 5;
 
     // Fragment ring: the LDS reads of MFMA step s+kAhead are issued before the MFMAs of step s, so a
@@ -444,6 +445,7 @@ hipError_t launch_wgrad_fast(const WgradParams &p, int bm, int bn, int grid, hip
     MI355CONV_WF(64, 128)
     MI355CONV_WF(64, 64)
     MI355CONV_WF(128, 64)
+    MI355CONV_WF(32, 128)
 #undef MI355CONV_WF
     return hipErrorInvalidValue;
 }

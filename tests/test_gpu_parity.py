@@ -26,8 +26,10 @@ def say(msg):
 @pytest.fixture(autouse=True)
 def _reset_tuning():
     mc.conv2d_set_tuning(mc.VARIANT_AUTO, 0)
+    mc.conv2d_set_tile(0, 0, -1)
     yield
     mc.conv2d_set_tuning(mc.VARIANT_AUTO, 0)
+    mc.conv2d_set_tile(0, 0, -1)
 
 
 def small_inputs(desc, seed):
@@ -94,6 +96,27 @@ def test_bwd_data_few_channels(shp, split):
     mc.conv2d_set_tuning(mc.VARIANT_MFMA, split)
     pl = mc.conv2d_query_plan(mc.OP_BWD_DATA, d)
     assert pl.variant == mc.VARIANT_MFMA and (pl.tile_m, pl.tile_n) == (128, 32)
+    gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), label=str(shp))
+
+
+# backward-weight with at most 32 output channels on aligned maps: the 32x128 tile (one block row)
+NARROW_OC_SHAPES = [
+    (4, 8, 8, 16, 32, 3, 3, 1, 1),
+    (2, 16, 16, 8, 24, 5, 5, 1, 2),
+    (64, 4, 4, 64, 32, 3, 3, 1, 1),      # (oh,ow,n) order with stage skipping
+    (3, 16, 16, 12, 8, 1, 1, 2, 0),
+]
+
+
+@pytest.mark.parametrize("split", [0, 1, 5])
+@pytest.mark.parametrize("shp", NARROW_OC_SHAPES)
+def test_bwd_weight_narrow_tile(shp, split):
+    say("narrow-oc %s split=%d" % (shp, split))
+    d = mc.make_desc(*shp)
+    mc.conv2d_set_tuning(mc.VARIANT_MFMA, split)
+    mc.conv2d_set_tile(32, 128, -1)     # the planner keeps small problems like these on 64x64
+    pl = mc.conv2d_query_plan(mc.OP_BWD_WEIGHT, d)
+    assert pl.variant == mc.VARIANT_MFMA and (pl.tile_m, pl.tile_n) == (32, 128)
     gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), label=str(shp))
 
 
