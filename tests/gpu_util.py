@@ -92,3 +92,31 @@ def check_all_ops(desc, X, W, G, ops=("fwd", "bwd_data", "bwd_weight"), label=""
         assert rel <= REL_L2_TOL and mx <= MAX_ABS_TOL, \
             "%s %s: rel_l2=%.3e max_abs=%.3e" % (label, op, rel, mx)
     return stats
+
+
+_VGG_CHAIN = {}
+
+
+def vgg_chain_inputs(layer):
+    """Inputs of one layer of the VGG-16 stack (configuration 5) with X taken from a forward
+    chain through the ORACLE: seeded pixels in [0,1) -> conv -> ReLU -> (2x2 max-pool at stage
+    ends) -> rounded to fp32 -> next layer.  W and G of every layer are its own seeded tensors,
+    so each layer's three operators are compared on identical (X, W, G) and errors of one layer
+    do not reach the next.  The ReLU between layers is an assumption of this build (the
+    benchmark configuration names only the pooling)."""
+    import oracle
+    import workloads as wl
+    if not _VGG_CHAIN:
+        first = wl.CFG5[0]
+        x = ((wl.uniform_pm1(wl.stream_key("vgg-chain-pixels"), first.x_shape).astype(np.float64) + 1.0) * 0.5)
+        x = x.astype(np.float32)
+        for i, l in enumerate(wl.CFG5, start=1):
+            _VGG_CHAIN[l.name] = x
+            w = wl.make_inputs(l)["W"]
+            y = np.maximum(np.asarray(oracle.conv2d_fwd(x, w, l.stride, l.pad)), 0.0)
+            if i in wl.VGG_POOL_AFTER:
+                n, h, wd, c = y.shape
+                y = y.reshape(n, h // 2, 2, wd // 2, 2, c).max(axis=(2, 4))
+            x = np.ascontiguousarray(y.astype(np.float32))
+    t = wl.make_inputs(layer)
+    return {"X": _VGG_CHAIN[layer.name], "W": t["W"], "G": t["G"]}
