@@ -114,9 +114,9 @@ int deconv2d(const float *dY, const float *W, float *dX, const conv2d_desc *d,
 
 /* Backward-weight (implied by the paper's training loop, Fig. 2 backward + update):
  *   dW[oc,fh,fw,ic] = sum_{n,oh,ow} dY[n,oh,ow,oc] * X[n, oh*sh-ph+fh, ow*sw-pw+fw, ic]
- * over in-range taps.  The sum over N*OH*OW is always cut into slices whose partial
- * results go through the workspace and are combined in a fixed order, so results are
- * bitwise reproducible. */
+ * over in-range taps.  Unless the output alone fills the chip, the sum over N*OH*OW is cut
+ * into slices whose partial results go through the workspace and are combined in a fixed
+ * order, so results are bitwise reproducible either way. */
 int conv2d_bwd_weight(const float *X, const float *dY, float *dW, const conv2d_desc *d,
                       void *ws, size_t ws_bytes, void *stream);
 
