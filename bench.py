@@ -7,7 +7,8 @@ inputs resident in HBM.  The default workload is the ResNet-style down-sampling 
 (N=128, 32x32x64 -> 16x16x128, 3x3, stride 2, pad 1).  Prints ONE JSON line on stdout.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-cpu-baseline]
-  python bench.py --table [cfg2 cfg3 ...]   per-layer, per-operator table (stderr + JSON line)
+  python bench.py --table [cfg2 cfg3 ...] [--with-oracle]   per-layer, per-operator table (stderr + JSON line)
+  python bench.py --streams                 independent operators on separate streams vs one stream
 """
 from __future__ import annotations
 
@@ -65,14 +66,15 @@ class LayerRunner:
         need = max(p.workspace_bytes for p in self.plans.values())
         self.ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
 
-    def run(self, op):
+    def run(self, op, stream=None, ws=None):
         mc = self.mc
+        ws = self.ws if ws is None else ws
         if op == "fwd":
-            mc.conv2d_fwd(self.X, self.W, self.Y, self.desc, ws=self.ws)
+            mc.conv2d_fwd(self.X, self.W, self.Y, self.desc, ws=ws, stream=stream)
         elif op == "bwd_data":
-            mc.conv2d_bwd_data(self.G, self.W, self.dX, self.desc, ws=self.ws)
+            mc.conv2d_bwd_data(self.G, self.W, self.dX, self.desc, ws=ws, stream=stream)
         else:
-            mc.conv2d_bwd_weight(self.X, self.G, self.dW, self.desc, ws=self.ws)
+            mc.conv2d_bwd_weight(self.X, self.G, self.dW, self.desc, ws=ws, stream=stream)
 
     def step(self):
         for op in OPS:
@@ -106,11 +108,6 @@ class LayerRunner:
             self.torch.cuda.synchronize()
 
 
-def fwd_bytes(l):
-    """Minimum algorithmic HBM bytes of one operator: each of X, W, Y touched once."""
-    return 4 * (l.N * l.IH * l.IW * l.IC + l.OC * l.K + l.M * l.OC)
-
-
 def cpu_baseline(layer, host, min_seconds=12.0):
     """The oracle as it stands, timed on the host cores on the same layer (all three operators),
     repeated until about min_seconds of wall time have passed."""
@@ -132,10 +129,36 @@ def cpu_baseline(layer, host, min_seconds=12.0):
                       % (repeats, layer.name, dt)}
 
 
-def table(mc, torch, cfg_names):
+def op_bytes(l, op):
+    """Minimum algorithmic HBM bytes of one operator: each operand and the result touched once."""
+    x, w, y = l.N * l.IH * l.IW * l.IC, l.OC * l.K, l.M * l.OC
+    if l.FH == 1 and l.FW == 1 and l.stride > 1 and op != "bwd_data":
+        x = l.M * l.IC            # a strided 1x1 filter reads only every stride-th pixel
+    return 4 * (x + w + y)
+
+
+def oracle_ms(layer, host, op):
+    import oracle
+    s, p = layer.stride, layer.pad
+    t0 = time.perf_counter()
+    if op == "fwd":
+        oracle.conv2d_fwd(host["X"], host["W"], s, p)
+    elif op == "bwd_data":
+        oracle.conv2d_bwd_data(host["G"], host["W"], (layer.IH, layer.IW), s, p)
+    else:
+        oracle.conv2d_bwd_weight(host["X"], host["G"], (layer.FH, layer.FW), s, p)
+    return (time.perf_counter() - t0) * 1e3
+
+
+def table(mc, torch, cfg_names, with_oracle=False):
+    """Every layer x operator: warm figure (median of 5 batches of 100 launches on one buffer set)
+    and, for the rows that HBM bandwidth bounds, a cold figure that rotates over enough distinct
+    buffer sets to exceed the 256 MB Infinity Cache."""
     rows = []
     seen = set()
-    log("%-5s %-10s %9s %9s %7s %7s  %s" % ("layer", "op", "ms", "TFLOP/s", "%peak", "GB/s", "plan"))
+    ridge = PEAK_FP32_MFMA_TFLOPS * 1e3 / PEAK_HBM_GBS          # FLOP per byte
+    log("%-5s %-10s %9s %9s %7s %7s %9s %10s  %s" % ("layer", "op", "ms", "TFLOP/s", "%peak", "GB/s",
+                                                     "cold ms", "oracle ms", "plan"))
     for cfg in cfg_names:
         for layer in wl.CONFIGS[cfg]:
             if layer.name in seen:
@@ -144,21 +167,105 @@ def table(mc, torch, cfg_names):
             r = LayerRunner(layer, mc, torch, random_fill=True)
             if not rows:
                 r.spin_up()
+            hbm_bound = layer.flops / op_bytes(layer, "fwd") < 2.0 * ridge
+            sets = [r]
+            if hbm_bound:
+                per_set = 4 * (layer.N * layer.IH * layer.IW * layer.IC + layer.M * layer.OC)
+                sets += [LayerRunner(layer, mc, torch, random_fill=True)
+                         for _ in range(min(16, int(320e6 // per_set)))]
             for op in OPS:
                 ms = r.event_ms(lambda: r.run(op))
+                cold = None
+                if hbm_bound:
+                    state = {"i": 0}
+
+                    def rotate():
+                        state["i"] = (state["i"] + 1) % len(sets)
+                        sets[state["i"]].run(op)
+                    cold = r.event_ms(rotate)
                 tf = layer.flops / ms / 1e9
                 pl = r.plans[op]
                 plan = "v%d %dx%d s%d pm%d g%d" % (pl.variant, pl.tile_m, pl.tile_n, pl.split,
                                                    pl.pos_major, pl.grid)
-                gbs = fwd_bytes(layer) / ms / 1e6
+                gbs = op_bytes(layer, op) / ms / 1e6
+                oms = oracle_ms(layer, r.host, op) if with_oracle else None
                 rows.append({"layer": layer.name, "op": op, "ms": round(ms, 5), "tflops": round(tf, 2),
                              "pct_peak": round(100 * tf / PEAK_FP32_MFMA_TFLOPS, 1),
-                             "gbs": round(gbs, 1), "plan": plan})
-                log("%-5s %-10s %9.4f %9.2f %7.1f %7.0f  %s" % (layer.name, op, ms, tf,
-                                                               100 * tf / PEAK_FP32_MFMA_TFLOPS, gbs, plan))
-            del r
+                             "gbs": round(gbs, 1), "cold_ms": None if cold is None else round(cold, 5),
+                             "cold_gbs": None if cold is None else round(op_bytes(layer, op) / cold / 1e6, 1),
+                             "oracle_ms": None if oms is None else round(oms, 2), "plan": plan})
+                log("%-5s %-10s %9.4f %9.2f %7.1f %7.0f %9s %10s  %s"
+                    % (layer.name, op, ms, tf, 100 * tf / PEAK_FP32_MFMA_TFLOPS, gbs,
+                       "-" if cold is None else "%.4f" % cold, "-" if oms is None else "%.1f" % oms, plan))
+            del r, sets
             torch.cuda.empty_cache()
+    if with_oracle:
+        import oracle
+        log("oracle: plain C loop nests, fp64 accumulation, %d OpenMP threads" % oracle.num_threads())
     return rows
+
+
+def streams_report(mc, torch):
+    """Independent operators on separate streams against the same operators on one stream: the three
+    inception-style branches of configuration 4 on one shared input (forward), and backward-data
+    next to backward-weight for a few layers.  Prints one JSON line."""
+    layers = {l.name: l for l in wl.all_layers()}
+    out = []
+
+    def timed(fn, launches=100, batches=5):
+        for _ in range(20):
+            fn()
+        ts = []
+        for _ in range(batches):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(launches):
+                fn()
+            torch.cuda.synchronize()
+            ts.append((time.perf_counter() - t0) * 1e3 / launches)
+        return sorted(ts)[len(ts) // 2]
+
+    # forward of the 1x1, 3x3, 5x5 branches, one input tensor
+    rs = [LayerRunner(layers[n], mc, torch, random_fill=True) for n in ("C4a", "C4b", "C4c")]
+    rs[0].spin_up()
+    for r in rs[1:]:
+        r.X = rs[0].X
+    sts = [torch.cuda.Stream() for _ in rs]
+    cur = torch.cuda.current_stream()
+
+    def serial():
+        for r in rs:
+            r.run("fwd")
+
+    def parallel():     # no event between the streams inside the timed loop: each stream is its own queue
+        for r, st in zip(rs, sts):
+            r.run("fwd", stream=st)
+    a, b = timed(serial), timed(parallel)
+    out.append({"case": "fwd of C4a | C4b | C4c on one input", "serial_ms": round(a, 5), "streams_ms": round(b, 5),
+                "gain": round(a / b, 3)})
+    log("%-44s serial %.4f ms   3 streams %.4f ms   x%.3f" % (out[-1]["case"], a, b, a / b))
+    del rs
+    for name in ("C2", "C3c", "C4a", "V11", "V5"):
+        r = LayerRunner(layers[name], mc, torch, random_fill=True)
+        # own workspace per operator: they run at the same time
+        need = r.plans["bwd_weight"].workspace_bytes
+        ws2 = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+
+        def serial2():
+            r.run("bwd_data")
+            r.run("bwd_weight")
+
+        def parallel2():
+            r.run("bwd_data", stream=s1)
+            r.run("bwd_weight", stream=s2, ws=ws2)
+        a, b = timed(serial2), timed(parallel2)
+        out.append({"case": "bwd_data | bwd_weight of %s" % name, "serial_ms": round(a, 5),
+                    "streams_ms": round(b, 5), "gain": round(a / b, 3)})
+        log("%-44s serial %.4f ms   2 streams %.4f ms   x%.3f" % (out[-1]["case"], a, b, a / b))
+        del r
+        torch.cuda.empty_cache()
+    return out
 
 
 def main():
@@ -169,6 +276,11 @@ def main():
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--table", nargs="*", default=None, metavar="CFG")
+    ap.add_argument("--streams", action="store_true",
+                    help="independent operators on separate streams vs one stream (inception branches, "
+                         "backward-data next to backward-weight)")
+    ap.add_argument("--with-oracle", action="store_true",
+                    help="with --table: also time the CPU oracle once per layer and operator")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 256 MiB device copy 5 times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -192,9 +304,13 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_each_way": src.numel() * 4, "copies": 5}))
         return
 
+    if args.streams:
+        print(json.dumps({"streams": streams_report(mc, torch)}))
+        return
+
     if args.table is not None:
         names = args.table or list(wl.CONFIGS)
-        rows = table(mc, torch, names)
+        rows = table(mc, torch, names, args.with_oracle)
         print(json.dumps({"table": rows}))
         return
 

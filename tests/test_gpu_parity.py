@@ -178,6 +178,61 @@ def test_side_stream():
         assert rel <= gu.REL_L2_TOL and mx <= gu.MAX_ABS_TOL
 
 
+def test_concurrent_streams_inception_branches():
+    """Independent operators enqueued on different streams at once (the paper's asynchronous APIs
+    run branches of a network in parallel, Sec. III Layer-4 / Sec. IV): the 1x1, 3x3 and 5x5
+    branches of configuration 4 on one shared input, then backward-data and backward-weight of one
+    layer side by side.  Each operator has its own workspace; results must equal those of the
+    same calls made one after the other on one stream bit for bit, and meet the oracle tolerance."""
+    n = 16
+    branches = [mc.make_desc(n, 16, 16, 256, 64, 1, 1, 1, 0), mc.make_desc(n, 16, 16, 256, 128, 3, 3, 1, 1),
+                mc.make_desc(n, 16, 16, 256, 32, 5, 5, 1, 2)]
+    k = wl.stream_key("streams")
+    X = wl.uniform_pm1(k, (n, 16, 16, 256))
+    Ws = [wl.uniform_pm1(k + 1 + i, (d.OC, d.FH, d.FW, d.IC)) for i, d in enumerate(branches)]
+    tX = torch.from_numpy(X).cuda()
+    tWs = [torch.from_numpy(w).cuda() for w in Ws]
+
+    def launch(streams):
+        outs, keep = [], []
+        for d, tw, st in zip(branches, tWs, streams):
+            y = torch.full((d.N, d.OH, d.OW, d.OC), float("nan"), dtype=torch.float32, device="cuda")
+            need = mc.conv2d_workspace_bytes(mc.OP_FWD, d)
+            ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+            keep.append(ws)
+            if st is not None:
+                st.wait_stream(torch.cuda.current_stream())
+            mc.conv2d_fwd(tX, tw, y, d, ws=ws, stream=st)
+            outs.append(y)
+        torch.cuda.synchronize()
+        return [o.cpu().numpy() for o in outs]
+
+    serial = launch([None, None, None])
+    parallel = launch([torch.cuda.Stream() for _ in branches])
+    for d, w, a, b in zip(branches, Ws, serial, parallel):
+        assert np.array_equal(a, b)
+        rel, mx = gu.errors(b, gu.run_oracle("fwd", d, X, w))
+        assert rel <= gu.REL_L2_TOL and mx <= gu.MAX_ABS_TOL
+
+    # backward-data || backward-weight of the 3x3 branch
+    d = branches[1]
+    G = wl.uniform_pm1(k + 9, (d.N, d.OH, d.OW, d.OC))
+    tG = torch.from_numpy(G).cuda()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    dX = torch.full((d.N, d.IH, d.IW, d.IC), float("nan"), dtype=torch.float32, device="cuda")
+    dW = torch.full((d.OC, d.FH, d.FW, d.IC), float("nan"), dtype=torch.float32, device="cuda")
+    ws1 = torch.empty(max(mc.conv2d_workspace_bytes(mc.OP_BWD_DATA, d), 16), dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty(max(mc.conv2d_workspace_bytes(mc.OP_BWD_WEIGHT, d), 16), dtype=torch.uint8, device="cuda")
+    for st in (s1, s2):
+        st.wait_stream(torch.cuda.current_stream())
+    mc.conv2d_bwd_data(tG, tWs[1], dX, d, ws=ws1, stream=s1)
+    mc.conv2d_bwd_weight(tX, tG, dW, d, ws=ws2, stream=s2)
+    torch.cuda.synchronize()
+    for op, got, (a, b) in (("bwd_data", dX, (G, Ws[1])), ("bwd_weight", dW, (X, G))):
+        rel, mx = gu.errors(got.cpu().numpy(), gu.run_oracle(op, d, a, b))
+        assert rel <= gu.REL_L2_TOL and mx <= gu.MAX_ABS_TOL, op
+
+
 FULL_LAYERS = [l for l in wl.all_layers()]
 
 
