@@ -172,7 +172,19 @@ CFG5 = _vgg16()
 # stage ends after these layer indices (1-based) get a 2x2 max-pool in the VGG-16 chain
 VGG_POOL_AFTER = (2, 4, 7, 10)
 
-CONFIGS = {"cfg1": CFG1, "cfg2": CFG2, "cfg3": CFG3, "cfg4": CFG4, "cfg5": CFG5}
+# Beyond the graded configurations: the paper's own batch size (512 images, Table I) and
+# channel counts that are neither powers of two nor multiples of 32 everywhere (inception-style
+# 96 / 160 / 192 / 48, where the paper notes its library loses ground, Sec. V).
+CFG6 = [Layer("B1", 512, 8, 8, 256, 256, 3, 3, 1, 1),
+        Layer("B2", 512, 16, 16, 128, 128, 3, 3, 1, 1),
+        Layer("B3", 512, 4, 4, 512, 512, 3, 3, 1, 1),
+        Layer("G1", 128, 16, 16, 192, 96, 1, 1, 1, 0),
+        Layer("G2", 128, 16, 16, 96, 160, 3, 3, 1, 1),
+        Layer("G3", 128, 8, 8, 160, 192, 3, 3, 1, 1),
+        Layer("G4", 128, 16, 16, 192, 48, 5, 5, 1, 2),
+        Layer("G5", 128, 8, 8, 48, 96, 3, 3, 1, 1)]
+
+CONFIGS = {"cfg1": CFG1, "cfg2": CFG2, "cfg3": CFG3, "cfg4": CFG4, "cfg5": CFG5, "cfg6": CFG6}
 
 
 def all_layers():
