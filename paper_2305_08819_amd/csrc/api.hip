@@ -267,7 +267,8 @@ Plan plan_fwd(const Shape &s)
     const int forced = g_forceVariant.load();
     const bool fits = offsets_fit_32bit((long long)s.N * s.IH * s.IW * s.IC, s, s.IW, s.IC);
     // the 16-byte loader addresses both operands with 32-bit byte offsets
-    const bool chunked = s.IC % kBK == 0 && buffer_addressable(s, (long long)s.N * s.IH * s.IW * s.IC, s.IW, s.IC);
+    // 16-byte loads along the channel axis; a tap's last 32-channel stage may be partly empty
+    const bool chunked = s.IC % 4 == 0 && buffer_addressable(s, (long long)s.N * s.IH * s.IW * s.IC, s.IW, s.IC);
     if (forced == MI355CONV_VARIANT_DIRECT || !fits) return pl;
     pl.variant = MI355CONV_VARIANT_MFMA;
     const long long M = (long long)s.N * s.OH * s.OW;
@@ -279,7 +280,7 @@ Plan plan_fwd(const Shape &s)
         finish_plan(pl, pl.split);
         return pl;
     }
-    const int chunksPerTap = s.IC / kBK;
+    const int chunksPerTap = ceil_div(s.IC, kBK);
     // taps per output position (what a position-major tile walks)
     double avgTapsPos = 0;
     int maxTapsPos = 0;
@@ -391,7 +392,7 @@ Plan plan_bwd_data(const Shape &s)
                       offsets_fit_32bit((long long)s.N * s.OH * s.OW * s.OC, s, s.OW, s.OC) &&
                       pl.outElems < kMaxElems;
     // up to 32 input channels of any count go through the narrow tile with 4-byte filter loads
-    const bool chunked = s.OC % kBK == 0 && (s.IC % 4 == 0 || s.IC <= 32) &&
+    const bool chunked = s.OC % 4 == 0 && (s.IC % 4 == 0 || s.IC <= 32) &&
                          buffer_addressable(s, (long long)s.N * s.OH * s.OW * s.OC, s.OW, s.OC);
     if (forced == MI355CONV_VARIANT_DIRECT || !fits) return pl;
     pl.variant = MI355CONV_VARIANT_MFMA;
@@ -409,7 +410,7 @@ Plan plan_bwd_data(const Shape &s)
         finish_plan(pl, sp);
         return pl;
     }
-    const int chunksPerTap = s.OC / kBK;
+    const int chunksPerTap = ceil_div(s.OC, kBK);
     const bool unitStride = s.sh == 1 && s.sw == 1;
     // stride 1: taps reaching input position (ih, iw) = taps of the flipped filter with pad F-1-p
     double avgTapsPos = 0;
@@ -851,7 +852,7 @@ int run_gather(const float *A, const float *B, float *out, const Shape &s, const
     g.FH = s.FH; g.FW = s.FW;
     g.sh = s.sh; g.sw = s.sw; g.ph = s.ph; g.pw = s.pw;
     g.divN = make_fastdiv((unsigned)s.N);
-    g.divChunksPerTap = make_fastdiv((unsigned)(g.SC / kBK > 0 ? g.SC / kBK : 1));
+    g.divChunksPerTap = make_fastdiv((unsigned)ceil_div(g.SC, kBK));
     g.aBytes = (unsigned)((long long)g.Nimg * g.SH * g.SW * g.SC * 4);
     g.bBytes = (unsigned)((long long)s.OC * s.FH * s.FW * s.IC * 4);
     fill_gather_params(g, pl);

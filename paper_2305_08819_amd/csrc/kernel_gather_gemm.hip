@@ -37,7 +37,10 @@ namespace mi355conv {
 // BELEM (backward-data only): the destination channel count is not a multiple of 4, so a
 // 16-byte load of four filter columns would be misaligned; the B tile is fetched with four
 // 4-byte loads per thread instead (e.g. the first layer's dX with 3 channels).
-template <int BM, int BN, int WAVES_M, bool BWD, bool BELEM = false>
+// RAGGED: the source channel count is a multiple of 4 but not of 32, so the last 32-channel
+// stage of every tap is partly empty; its surplus 16-byte loads get an out-of-range offset
+// (one select per load and stage, which the aligned instantiation does not pay).
+template <int BM, int BN, int WAVES_M, bool BWD, bool BELEM = false, bool RAGGED = false>
 __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGemmParams params)
 {
     STAMP(0);
@@ -63,7 +66,8 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     // taps walked by this tile: the rectangle [uLo,uHi] x [vLo,vHi]
     const int uCnt = tile.uHi >= tile.uLo ? tile.uHi - tile.uLo + 1 : 0;
     const int vCnt = tile.vHi >= tile.vLo ? tile.vHi - tile.vLo + 1 : 0;
-    const int chunksPerTap = p.SC / kBK;
+    const int chunksPerTap = RAGGED ? (p.SC + kBK - 1) / kBK : p.SC / kBK;
+    const int lastValid = p.SC - (chunksPerTap - 1) * kBK;   // source channels in a tap's last stage
     const int nIter = uCnt * vCnt * chunksPerTap;
     const int it0 = (int)fast_div((unsigned)(slice * nIter), p.divSplit);          // nIter * split is far below 2^31
     const int it1 = (int)fast_div((unsigned)((slice + 1) * nIter), p.divSplit);
@@ -109,6 +113,12 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
         }
     }
 
+    // ragged last stage: which of this thread's loads fall inside it
+    const bool aLastOk = aSeg * 4 < lastValid;
+    bool bLastOk[T::PB];
+#pragma unroll
+    for (int i = 0; i < T::PB; ++i) bLastOk[i] = BWD ? bRow + T::B_RPP * i < lastValid : bSeg * 4 < lastValid;
+
     // reduction cursor: current tap (u,v) and chunk within the tap
     int chunk = 0, tapU = tile.uLo, tapV = tile.vLo;
     if (it0 > 0 && it0 < it1) {   // only slices after the first start inside the tap list
@@ -149,17 +159,22 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     constexpr int kItems = T::PA + T::PB;
     auto gload_item = [&](int q, f4 *ga, f4 *gb) __attribute__((always_inline)) {
         const int c0 = chunk * kBK;
+        const bool lastChunk = RAGGED && chunk == chunksPerTap - 1;   // uniform
         if (q < T::PA) {
-            ga[q] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrcA, aOff[q], c0 * 4, 0));
+            const int voff = (lastChunk && !aLastOk) ? kOutOfRange : aOff[q];
+            ga[q] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrcA, voff, c0 * 4, 0));
         } else {
             const int i = q - T::PA;
             const int soff = BWD ? (c0 * wRowStride + tapOffB) * 4 : (tapOffB + c0) * 4;
+            const bool drop = lastChunk && !bLastOk[i];
             if (BELEM) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    gb[i][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrcB, bOffE[i][e], soff, 0));
+                    gb[i][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                                             rsrcB, drop ? kOutOfRange : bOffE[i][e], soff, 0));
             } else {
-                gb[i] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrcB, bOff[i], soff, 0));
+                gb[i] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrcB, drop ? kOutOfRange : bOff[i],
+                                                                                    soff, 0));
             }
         }
     };
@@ -322,12 +337,12 @@ extern "C" int exp_read_stamps(unsigned long long *host, size_t count)
 }
 #endif
 
-template <int BM, int BN, int WAVES_M, bool BWD, bool BELEM = false>
+template <int BM, int BN, int WAVES_M, bool BWD, bool BELEM = false, bool RAGGED = false>
 static hipError_t launch_one(const GatherGemmParams &p, int grid, hipStream_t st)
 {
     using T = GG<BM, BN, WAVES_M, BWD>;
     constexpr size_t kSmemBytes = (2 * (T::A_STAGE + T::B_STAGE) + T::TABLE_INTS) * sizeof(float);
-    auto kern = gather_gemm_kernel<BM, BN, WAVES_M, BWD, BELEM>;
+    auto kern = gather_gemm_kernel<BM, BN, WAVES_M, BWD, BELEM, RAGGED>;
     static bool attrSet[16] = {};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -345,14 +360,20 @@ static hipError_t launch_one(const GatherGemmParams &p, int grid, hipStream_t st
 hipError_t launch_gather_gemm(const GatherGemmParams &p, bool bwdData, int bm, int bn, int grid,
                               hipStream_t st)
 {
-    if (p.DC % 4 != 0) {   // only backward-data into few channels, on the narrow tile
-        if (bwdData && bm == 128 && bn == 32) return launch_one<128, 32, 4, true, true>(p, grid, st);
+    if (p.SC % 4 != 0) return hipErrorInvalidValue;
+    if (bwdData && p.DC % 4 != 0) {   // filter columns by 4-byte loads: on the narrow tile only
+        if (bm == 128 && bn == 32) return launch_one<128, 32, 4, true, true, true>(p, grid, st);
         return hipErrorInvalidValue;
     }
-#define MI355_GG_CASE(BM_, BN_, WM_)                                                    \
-    if (bm == BM_ && bn == BN_)                                                          \
-        return bwdData ? launch_one<BM_, BN_, WM_, true>(p, grid, st)                    \
-                       : launch_one<BM_, BN_, WM_, false>(p, grid, st);
+    const bool ragged = p.SC % kBK != 0;
+#define MI355_GG_CASE(BM_, BN_, WM_)                                                                 \
+    if (bm == BM_ && bn == BN_) {                                                                    \
+        if (ragged)                                                                                  \
+            return bwdData ? launch_one<BM_, BN_, WM_, true, false, true>(p, grid, st)               \
+                           : launch_one<BM_, BN_, WM_, false, false, true>(p, grid, st);             \
+        return bwdData ? launch_one<BM_, BN_, WM_, true>(p, grid, st)                                \
+                       : launch_one<BM_, BN_, WM_, false>(p, grid, st);                              \
+    }
     MI355_GG_CASE(128, 128, 2)
     MI355_GG_CASE(128, 64, 2)
     MI355_GG_CASE(64, 64, 2)

@@ -69,7 +69,9 @@ def test_direct_variant_odd_shapes(shp):
 @pytest.mark.parametrize("split", [0, 2])
 @pytest.mark.parametrize("shp", ODD_SHAPES)
 def test_elementwise_mfma_variant_odd_shapes(shp, split):
-    """Channel counts outside the 16-byte loader's reach go through the element-wise MFMA kernels."""
+    """Channel counts that are not a multiple of 4 go through the element-wise MFMA kernels; those
+    that are a multiple of 4 but not of 32 (24, 48, 16 here) take the 16-byte loaders with a
+    partly empty last stage per tap."""
     say("elem %s split=%d" % (shp, split))
     d = mc.make_desc(*shp)
     mc.conv2d_set_tuning(mc.VARIANT_MFMA, split)
