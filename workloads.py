@@ -184,7 +184,14 @@ CFG6 = [Layer("B1", 512, 8, 8, 256, 256, 3, 3, 1, 1),
         Layer("G4", 128, 16, 16, 192, 48, 5, 5, 1, 2),
         Layer("G5", 128, 8, 8, 48, 96, 3, 3, 1, 1)]
 
-CONFIGS = {"cfg1": CFG1, "cfg2": CFG2, "cfg3": CFG3, "cfg4": CFG4, "cfg5": CFG5, "cfg6": CFG6}
+# Large feature maps (128x128 and up), the regime in which the paper concedes to the vendor
+# library (Sec. IV): many tiles, no slicing of the reduction in forward / backward-data.
+CFG7 = [Layer("L1", 8, 128, 128, 64, 64, 3, 3, 1, 1),
+        Layer("L2", 4, 256, 256, 32, 32, 3, 3, 1, 1),
+        Layer("L3", 8, 128, 128, 64, 128, 3, 3, 2, 1)]
+
+CONFIGS = {"cfg1": CFG1, "cfg2": CFG2, "cfg3": CFG3, "cfg4": CFG4, "cfg5": CFG5, "cfg6": CFG6,
+           "cfg7": CFG7}
 
 
 def all_layers():
