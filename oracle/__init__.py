@@ -9,7 +9,10 @@ accumulation); this module only compiles that file with gcc, loads it with
 ctypes and marshals numpy arrays.  Pin status: every function here is pinned by
 ``tests/test_oracle_pins.py`` (closed forms, delta filters, 1x1 == GEMM,
 scatter/pad-and-slice second forms, adjoint identity, exact finite
-differences, a library cross-check).
+differences, a library cross-check); ``conv2d_fwd_bias_act`` adds the bias add
+and leaky-ReLU of the paper's layer constructors on top of ``conv2d_fwd`` in
+plain numpy fp64 and is pinned by hand-computed values and its special cases
+(slope 1, slope 0, zero bias).
 """
 from __future__ import annotations
 
@@ -131,3 +134,18 @@ def conv2d_bwd_weight(X, G, filter_hw, stride=1, pad=0):
         _load().oracle_conv2d_bwd_weight(_fp(X), _fp(G), _dp(dW), N, IH, IW, IC, OC, FH, FW,
                                          sh, sw, ph, pw)
     return dW
+
+
+def conv2d_fwd_bias_act(X, W, bias=None, negative_slope=1.0, stride=1, pad=0):
+    """act(conv(X, W) + bias[oc]) with act(v) = v if v > 0 else negative_slope * v, in fp64.
+
+    The biased convolution and the leaky-ReLU activation are the paper's layer constructors
+    (Fig. 2: ``conv3D(..., biased)``, ``leakyRelu``); the formula is the usual definition of both.
+    ``bias`` None means no bias; ``negative_slope`` 1 means no activation.
+    """
+    y = np.asarray(conv2d_fwd(X, W, stride, pad), dtype=np.float64)
+    if bias is not None:
+        b = np.asarray(bias, dtype=np.float32).astype(np.float64)
+        assert b.shape == (y.shape[3],)
+        y = y + b[None, None, None, :]
+    return np.where(y > 0.0, y, y * float(negative_slope))

@@ -260,3 +260,38 @@ def test_generators_are_reproducible_and_scaled():
     assert abs(w.std() / np.sqrt(2.0 / 576) - 1) < 0.02
     assert wl.CFG2[0].flops == 2 * 32768 * 128 * 576
     assert sum(l.flops for l in wl.CFG5) == 2 * 128 * 313196544
+
+
+# ---- biased convolution + leaky-ReLU (Fig. 2 constructors) -----------------------------------
+def test_bias_act_hand_values():
+    """1x1 input, 1x1 filter: conv is a product; values worked out by hand."""
+    X = np.array([2.0, -3.0], dtype=np.float32).reshape(2, 1, 1, 1)
+    W = np.array([1.0, -1.0, 0.5], dtype=np.float32).reshape(3, 1, 1, 1)
+    bias = np.array([0.25, -1.0, 2.0], dtype=np.float32)
+    y = oracle.conv2d_fwd_bias_act(X, W, bias, 0.125)
+    # image 0: 2*[1,-1,.5] + b = [2.25, -3, 3] -> leaky: [2.25, -0.375, 3]
+    # image 1: -3*[1,-1,.5] + b = [-2.75, 2, 0.5] -> [-0.34375, 2, 0.5]
+    want = np.array([[2.25, -0.375, 3.0], [-0.34375, 2.0, 0.5]]).reshape(2, 1, 1, 3)
+    assert np.array_equal(y, want)
+
+
+def test_bias_act_special_cases():
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((2, 5, 4, 3)).astype(np.float32)
+    W = rng.standard_normal((4, 3, 2, 3)).astype(np.float32)
+    b = rng.standard_normal(4).astype(np.float32)
+    plain = oracle.conv2d_fwd(X, W, (1, 2), (1, 0))
+    # slope 1: bias only; no bias and slope 1: the convolution itself
+    assert np.array_equal(oracle.conv2d_fwd_bias_act(X, W, None, 1.0, (1, 2), (1, 0)), plain)
+    assert np.allclose(oracle.conv2d_fwd_bias_act(X, W, b, 1.0, (1, 2), (1, 0)), plain + b.astype(np.float64), rtol=0, atol=0)
+    # slope 0: ReLU; the bias shifts channel c only
+    relu = oracle.conv2d_fwd_bias_act(X, W, b, 0.0, (1, 2), (1, 0))
+    assert np.array_equal(relu, np.maximum(plain + b.astype(np.float64), 0.0))
+    # negative slope acts on the negative part only, linearly
+    y = oracle.conv2d_fwd_bias_act(X, W, b, 0.3, (1, 2), (1, 0))
+    z = plain + b.astype(np.float64)
+    assert np.array_equal(y[z > 0], z[z > 0]) and np.allclose(y[z <= 0], 0.3 * z[z <= 0], rtol=1e-15, atol=0)
+    # a wrong channel axis for the bias would fail here: only channel 2 gets a bias
+    b2 = np.zeros(4, dtype=np.float32); b2[2] = 7.0
+    d = oracle.conv2d_fwd_bias_act(X, W, b2, 1.0, (1, 2), (1, 0)) - plain
+    assert np.allclose(d[..., 2], 7.0, rtol=0, atol=1e-12) and not d[..., [0, 1, 3]].any()
