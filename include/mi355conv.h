@@ -101,6 +101,16 @@ int conv2d_set_tile(int tile_m, int tile_n, int pos_major);
 int conv2d_fwd(const float *X, const float *W, float *Y, const conv2d_desc *d,
                void *ws, size_t ws_bytes, void *stream);
 
+/* Forward convolution with the bias add and the leaky-ReLU activation of the paper's layer
+ * constructors (Fig. 2: conv3D(..., biased), leakyRelu) applied in the kernel's epilogue:
+ *   Y[n,oh,ow,oc] = act(conv(X,W)[n,oh,ow,oc] + bias[oc]),  act(v) = v > 0 ? v : negative_slope * v.
+ * bias: device pointer to OC floats, or NULL for no bias; negative_slope = 1 means no
+ * activation, 0 is ReLU.  Everything else (layouts, workspace, errors, enqueue-only) as
+ * conv2d_fwd; when the reduction is sliced the epilogue runs in the combine pass. */
+int conv2d_fwd_bias_act(const float *X, const float *W, const float *bias, float *Y,
+                        const conv2d_desc *d, float negative_slope, void *ws, size_t ws_bytes,
+                        void *stream);
+
 /* Backward-data = deconvolution (Sec. IV: the deconv operator for small feature maps):
  *   dX[n,ih,iw,ic] = sum over (oc,fh,fw) with oh*sh-ph+fh == ih, ow*sw-pw+fw == iw of
  *                    dY[n,oh,ow,oc] * W[oc,fh,fw,ic].

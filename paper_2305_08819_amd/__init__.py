@@ -17,6 +17,7 @@ OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT = 0, 1, 2
 VARIANT_AUTO, VARIANT_DIRECT, VARIANT_MFMA = -1, 0, 1
 
 EXPORTS = ("conv2d_workspace_bytes", "conv2d_query_plan", "conv2d_set_tuning", "conv2d_set_tile", "conv2d_fwd",
+           "conv2d_fwd_bias_act",
            "conv2d_bwd_data", "deconv2d", "conv2d_bwd_weight", "conv2d_status_string",
            "conv2d_last_hip_error")
 
@@ -74,6 +75,8 @@ def load() -> ctypes.CDLL:
             fn = getattr(lib, name)
             fn.argtypes = [vp, vp, vp, dp, vp, ctypes.c_size_t, vp]
             fn.restype = ctypes.c_int
+        lib.conv2d_fwd_bias_act.argtypes = [vp, vp, vp, vp, dp, ctypes.c_float, vp, ctypes.c_size_t, vp]
+        lib.conv2d_fwd_bias_act.restype = ctypes.c_int
         lib.conv2d_status_string.argtypes = [ctypes.c_int]
         lib.conv2d_status_string.restype = ctypes.c_char_p
         lib.conv2d_last_hip_error.argtypes = []
@@ -156,6 +159,26 @@ def conv2d_fwd(X, W, Y, desc: ConvDesc, ws=None, stream=None):
     _check(W, (desc.OC, desc.FH, desc.FW, desc.IC), "W")
     _check(Y, (desc.N, desc.OH, desc.OW, desc.OC), "Y")
     return _call("conv2d_fwd", OP_FWD, X, W, Y, desc, ws, stream)
+
+
+def conv2d_fwd_bias_act(X, W, bias, Y, desc: ConvDesc, negative_slope=1.0, ws=None, stream=None):
+    """Y <- act(conv(X, W) + bias[oc]), act(v) = v if v > 0 else negative_slope * v; bias may be None."""
+    _check(X, (desc.N, desc.IH, desc.IW, desc.IC), "X")
+    _check(W, (desc.OC, desc.FH, desc.FW, desc.IC), "W")
+    _check(Y, (desc.N, desc.OH, desc.OW, desc.OC), "Y")
+    if bias is not None:
+        _check(bias, (desc.OC,), "bias")
+    lib = load()
+    need = conv2d_workspace_bytes(OP_FWD, desc)
+    if ws is None and need:
+        import torch
+        ws = torch.empty(need, dtype=torch.uint8, device=Y.device)
+    nbytes = ws.numel() * ws.element_size() if ws is not None else 0
+    rc = lib.conv2d_fwd_bias_act(_ptr(X), _ptr(W), _ptr(bias), _ptr(Y), ctypes.byref(desc),
+                                 ctypes.c_float(negative_slope), _ptr(ws), nbytes, _stream_handle(stream))
+    if rc != 0:
+        raise Mi355ConvError(rc, "conv2d_fwd_bias_act")
+    return Y
 
 
 def conv2d_bwd_data(dY, W, dX, desc: ConvDesc, ws=None, stream=None):

@@ -833,8 +833,14 @@ int make_plan(int op, const Shape &s, Plan *pl)
     return MI355CONV_OK;
 }
 
+struct Epilogue {
+    bool on = false;
+    const float *bias = nullptr;
+    float slope = 1.f;
+};
+
 int run_gather(const float *A, const float *B, float *out, const Shape &s, const Plan &pl, bool bwd,
-               void *ws, hipStream_t st)
+               void *ws, hipStream_t st, const Epilogue &epi = Epilogue())
 {
     GatherGemmParams g;
     memset(&g, 0, sizeof g);
@@ -856,6 +862,9 @@ int run_gather(const float *A, const float *B, float *out, const Shape &s, const
     g.aBytes = (unsigned)((long long)g.Nimg * g.SH * g.SW * g.SC * 4);
     g.bBytes = (unsigned)((long long)s.OC * s.FH * s.FW * s.IC * 4);
     fill_gather_params(g, pl);
+    g.epilogue = epi.on ? 1 : 0;
+    g.bias = epi.bias;
+    g.slope = epi.slope;
     g.balance = pl.balance;
     g.rowTilesPerPos = 1;
     if (pl.balance) {
@@ -868,7 +877,8 @@ int run_gather(const float *A, const float *B, float *out, const Shape &s, const
                            : launch_gather_gemm(g, bwd, pl.bm, pl.bn, pl.grid, st);
     if (e != hipSuccess) return hip_fail(e);
     if (pl.split > 1) {
-        e = launch_slice_reduce(static_cast<const float *>(ws), out, pl.outElems, pl.split, pl.sliceStride, st);
+        e = launch_slice_reduce(static_cast<const float *>(ws), out, pl.outElems, pl.split, pl.sliceStride, st,
+                                epi.bias, epi.slope, epi.on ? g.DC : 0);
         if (e != hipSuccess) return hip_fail(e);
     }
     return MI355CONV_OK;
@@ -926,8 +936,8 @@ int conv2d_set_tile(int tile_m, int tile_n, int pos_major)
     return MI355CONV_OK;
 }
 
-int conv2d_fwd(const float *X, const float *W, float *Y, const conv2d_desc *d, void *ws, size_t ws_bytes,
-               void *stream)
+static int fwd_impl(const float *X, const float *W, float *Y, const conv2d_desc *d, void *ws, size_t ws_bytes,
+                    void *stream, const Epilogue &epi)
 {
     Shape s;
     Plan pl;
@@ -940,9 +950,29 @@ int conv2d_fwd(const float *X, const float *W, float *Y, const conv2d_desc *d, v
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (pl.variant == MI355CONV_VARIANT_DIRECT) {
         hipError_t e = launch_direct_fwd(X, W, Y, s, st);
+        if (e == hipSuccess && epi.on)
+            e = launch_bias_act(Y, (long long)s.N * s.OH * s.OW * s.OC, epi.bias, epi.slope, s.OC, st);
         return e == hipSuccess ? MI355CONV_OK : hip_fail(e);
     }
-    return run_gather(X, W, Y, s, pl, false, ws, st);
+    return run_gather(X, W, Y, s, pl, false, ws, st, epi);
+}
+
+int conv2d_fwd(const float *X, const float *W, float *Y, const conv2d_desc *d, void *ws, size_t ws_bytes,
+               void *stream)
+{
+    return fwd_impl(X, W, Y, d, ws, ws_bytes, stream, Epilogue());
+}
+
+int conv2d_fwd_bias_act(const float *X, const float *W, const float *bias, float *Y, const conv2d_desc *d,
+                        float negative_slope, void *ws, size_t ws_bytes, void *stream)
+{
+    if (bias && (reinterpret_cast<uintptr_t>(bias) & 3u)) return MI355CONV_ERR_ALIGNMENT;
+    if (!(negative_slope == negative_slope)) return MI355CONV_ERR_UNSUPPORTED;   // NaN
+    Epilogue epi;
+    epi.on = true;
+    epi.bias = bias;
+    epi.slope = negative_slope;
+    return fwd_impl(X, W, Y, d, ws, ws_bytes, stream, epi);
 }
 
 int conv2d_bwd_data(const float *dY, const float *W, float *dX, const conv2d_desc *d, void *ws,

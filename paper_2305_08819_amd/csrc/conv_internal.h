@@ -92,6 +92,10 @@ struct GatherGemmParams {
     // position in posOrder (most taps first).  0 = off.
     int balance;
     int rowTilesPerPos;   // Nimg / BM
+    // epilogue of the unsliced launch: out = act(acc + bias[col]); epilogue == 0: plain store
+    int epilogue;
+    float slope;
+    const float *bias;    // may be null
     FastDiv divN;         // by Nimg
     FastDiv divTilesN, divSplit, divRowTilesPerPos, divChunksPerTap;   // chunks per tap = SC / kBK
     int phaseStart[kMaxPhases];   // first row tile of each phase; INT_MAX past the last phase
@@ -112,7 +116,9 @@ struct GatherView {
     int Nimg, SH, SW, SC, DH, DW, DC, FH, FW, sh, sw, ph, pw;
     int posMajor, split;
     long long sliceStride;
-    int tilesN, xcdUnit, nPhases, balance, rowTilesPerPos;
+    int tilesN, xcdUnit, nPhases, balance, rowTilesPerPos, epilogue;
+    float slope;
+    const float *bias;
     FastDiv divN, divTilesN, divSplit, divRowTilesPerPos, divChunksPerTap;
     const int *phaseStart;
     const GatherPhase *phase;
@@ -125,7 +131,7 @@ __device__ __forceinline__ GatherView gather_view(const GatherGemmParams &p)
 {
     GatherView v{p.A, p.B, p.C, p.aBytes, p.bBytes, p.Nimg, p.SH, p.SW, p.SC, p.DH, p.DW, p.DC, p.FH, p.FW,
                  p.sh, p.sw, p.ph, p.pw, p.posMajor, p.split, p.sliceStride, p.tilesN, p.xcdUnit, p.nPhases,
-                 p.balance, p.rowTilesPerPos, p.divN, p.divTilesN, p.divSplit, p.divRowTilesPerPos,
+                 p.balance, p.rowTilesPerPos, p.epilogue, p.slope, p.bias, p.divN, p.divTilesN, p.divSplit, p.divRowTilesPerPos,
                  p.divChunksPerTap, p.phaseStart, p.phase, p.runs, p.posOrder};
     MI355CONV_PIN(v.A); MI355CONV_PIN(v.B); MI355CONV_PIN(v.C);
     MI355CONV_PIN(v.aBytes); MI355CONV_PIN(v.bBytes);
@@ -259,8 +265,13 @@ hipError_t launch_direct_bwd_data(const float *G, const float *W, float *dX, con
 hipError_t launch_direct_bwd_weight(const float *X, const float *G, float *dW, const Shape &s, hipStream_t st);
 
 // out[i] = sum_{s<split} ws[s*stride + i], combined pairwise in a fixed order.
+// With bias / slope (cols = channel count of the output's last axis, cols > 0):
+// out[i] = act(sum + bias[i % cols]).
 hipError_t launch_slice_reduce(const float *ws, float *out, long long count, int split,
-                               long long stride, hipStream_t st);
+                               long long stride, hipStream_t st, const float *bias = nullptr,
+                               float slope = 1.f, int cols = 0);
+// out[i] = act(out[i] + bias[i % cols]) in place (after the direct forward kernel)
+hipError_t launch_bias_act(float *out, long long count, const float *bias, float slope, int cols, hipStream_t st);
 
 // bm/bn select the compiled tile; returns hipErrorInvalidValue for an unknown pair.
 hipError_t launch_gather_gemm(const GatherGemmParams &p, bool bwdData, int bm, int bn, int grid,

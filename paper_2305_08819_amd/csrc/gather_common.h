@@ -181,10 +181,15 @@ __device__ __forceinline__ void gather_tile_store(const P &p, int slice, int n0,
         for (int j = 0; j < T::NB; ++j) {
             const int col = n0 + wn * T::WTN + j * 32 + l32;
             if (col < p.DC) {
+                const bool epi = p.epilogue && p.split == 1;   // sliced launches leave it to the combine pass
+                const float b = epi && p.bias ? p.bias[col] : 0.f;
+                const float slope = epi ? p.slope : 1.f;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int o = orow[r / 4][r % 4];
-                    if (o >= 0) C[o * p.DC + col] = acc[i][j][r];
+                    float v = acc[i][j][r] + b;
+                    v = v > 0.f ? v : v * slope;
+                    if (o >= 0) C[o * p.DC + col] = v;
                 }
             }
         }

@@ -114,10 +114,22 @@ __global__ __launch_bounds__(256) void direct_bwd_weight_kernel(const float *__r
 // order and rounded once, so the result is reproducible and the combine step adds no error of
 // its own beyond the final rounding.  A workgroup owns 256/G float4 columns; G thread groups
 // each add every G-th slice, then group 0 adds the G group sums in group order through LDS.
+// Optional epilogue (cols > 0): out = act(sum + bias[column]), act(v) = v > 0 ? v : slope * v, the
+// same fp32 arithmetic as the epilogue of an unsliced launch.
+__device__ __forceinline__ float bias_act(float v, long long index, const float *bias, float slope, int cols)
+{
+    if (cols > 0) {
+        if (bias) v += bias[index % cols];
+        v = v > 0.f ? v : v * slope;
+    }
+    return v;
+}
+
 template <int G>
 __global__ __launch_bounds__(256) void slice_reduce_kernel(const float *__restrict__ ws,
                                                            float *__restrict__ out,
-                                                           long long count4, int split, long long stride4)
+                                                           long long count4, int split, long long stride4,
+                                                           const float *__restrict__ bias, float slope, int cols)
 {
     constexpr int COLS = 256 / G;
     __shared__ double red[G > 1 ? (G - 1) * COLS * 4 : 1];
@@ -145,19 +157,29 @@ __global__ __launch_bounds__(256) void slice_reduce_kernel(const float *__restri
         }
     }
     if (g == 0 && i < count4)
-        reinterpret_cast<float4 *>(out)[i] = make_float4((float)a0, (float)a1, (float)a2, (float)a3);
+        reinterpret_cast<float4 *>(out)[i] =
+            make_float4(bias_act((float)a0, 4 * i, bias, slope, cols), bias_act((float)a1, 4 * i + 1, bias, slope, cols),
+                        bias_act((float)a2, 4 * i + 2, bias, slope, cols), bias_act((float)a3, 4 * i + 3, bias, slope, cols));
 }
 
 // scalar tail (count % 4 elements) of the reduce
 __global__ void slice_reduce_tail_kernel(const float *__restrict__ ws, float *__restrict__ out,
-                                         long long first, long long count, int split, long long stride)
+                                         long long first, long long count, int split, long long stride,
+                                         const float *__restrict__ bias, float slope, int cols)
 {
     const long long j = first + threadIdx.x;
     if (j < count) {
         double a = 0;
         for (int s = 0; s < split; ++s) a += ws[s * stride + j];
-        out[j] = (float)a;
+        out[j] = bias_act((float)a, j, bias, slope, cols);
     }
+}
+
+__global__ __launch_bounds__(256) void bias_act_kernel(float *__restrict__ out, long long count,
+                                                       const float *__restrict__ bias, float slope, int cols)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i < count) out[i] = bias_act(out[i], i, bias, slope, cols);
 }
 
 static inline unsigned blocks_for(long long n) { return (unsigned)((n + 255) / 256); }
@@ -183,8 +205,14 @@ hipError_t launch_direct_bwd_weight(const float *X, const float *G, float *dW, c
     return hipGetLastError();
 }
 
+hipError_t launch_bias_act(float *out, long long count, const float *bias, float slope, int cols, hipStream_t st)
+{
+    hipLaunchKernelGGL(bias_act_kernel, dim3(blocks_for(count)), dim3(256), 0, st, out, count, bias, slope, cols);
+    return hipGetLastError();
+}
+
 hipError_t launch_slice_reduce(const float *ws, float *out, long long count, int split,
-                               long long stride, hipStream_t st)
+                               long long stride, hipStream_t st, const float *bias, float slope, int cols)
 {
     // stride is a multiple of 4 (the host pads it), so float4 loads of every slice are aligned
     const long long count4 = count >> 2;
@@ -192,21 +220,22 @@ hipError_t launch_slice_reduce(const float *ws, float *out, long long count, int
         // more thread groups per column when there are few columns and many slices
         int G = 1;
         while (G < 16 && G * 2 <= split && count4 * G < (1 << 17)) G *= 2;
-        const long long cols = 256 / G;
-        const unsigned grid = (unsigned)((count4 + cols - 1) / cols);
+        const long long perWg = 256 / G;   // float4 columns per workgroup
+        const unsigned grid = (unsigned)((count4 + perWg - 1) / perWg);
         const long long stride4 = stride >> 2;
         switch (G) {
-        case 1: hipLaunchKernelGGL(slice_reduce_kernel<1>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4); break;
-        case 2: hipLaunchKernelGGL(slice_reduce_kernel<2>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4); break;
-        case 4: hipLaunchKernelGGL(slice_reduce_kernel<4>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4); break;
-        case 8: hipLaunchKernelGGL(slice_reduce_kernel<8>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4); break;
-        default: hipLaunchKernelGGL(slice_reduce_kernel<16>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4); break;
+        case 1: hipLaunchKernelGGL(slice_reduce_kernel<1>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4, bias, slope, cols); break;
+        case 2: hipLaunchKernelGGL(slice_reduce_kernel<2>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4, bias, slope, cols); break;
+        case 4: hipLaunchKernelGGL(slice_reduce_kernel<4>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4, bias, slope, cols); break;
+        case 8: hipLaunchKernelGGL(slice_reduce_kernel<8>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4, bias, slope, cols); break;
+        default: hipLaunchKernelGGL(slice_reduce_kernel<16>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4, bias, slope, cols); break;
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     if (count4 * 4 < count)
-        hipLaunchKernelGGL(slice_reduce_tail_kernel, dim3(1), dim3(4), 0, st, ws, out, count4 * 4, count, split, stride);
+        hipLaunchKernelGGL(slice_reduce_tail_kernel, dim3(1), dim3(4), 0, st, ws, out, count4 * 4, count, split, stride,
+                           bias, slope, cols);
     return hipGetLastError();
 }
 

@@ -55,6 +55,21 @@ def test_argument_errors_before_any_hip_call(lib, name):
     assert _call(lib, name, 256, 512, 768, mc.make_desc(1 << 20, 64, 64, 64, 64, 3, 3, 1, 1)) == -2  # 2^32 elems
 
 
+def test_bias_act_argument_errors_before_any_hip_call(lib):
+    good = mc.make_desc(4, 8, 8, 3, 16, 3, 3, 1, 1)
+
+    def call(x, w, b, y, desc, slope=0.1):
+        return lib.conv2d_fwd_bias_act(ctypes.c_void_p(x), ctypes.c_void_p(w), ctypes.c_void_p(b), ctypes.c_void_p(y),
+                                       ctypes.byref(desc), ctypes.c_float(slope), ctypes.c_void_p(0), 0, None)
+    assert call(0, 256, 0, 512, good) == -1                      # null tensor (a null bias is allowed)
+    assert call(256, 512, 1026, 768, good) == -4                 # bias not 4-byte aligned
+    assert call(256, 512, 1024, 772, good) == -4                 # misaligned output
+    assert call(256, 512, 1024, 768, good, float("nan")) == -5   # NaN slope
+    bad = mc.make_desc(4, 8, 8, 3, 16, 3, 3, 1, 1)
+    bad.OC = 0
+    assert call(256, 512, 1024, 768, bad) == -2
+
+
 def test_workspace_errors(lib):
     d = mc.make_desc(128, 2, 2, 512, 512, 3, 3, 1, 1)
     need = mc.conv2d_workspace_bytes(mc.OP_FWD, d)

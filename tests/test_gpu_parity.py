@@ -180,6 +180,47 @@ def test_side_stream():
         assert rel <= gu.REL_L2_TOL and mx <= gu.MAX_ABS_TOL
 
 
+BIAS_ACT_SHAPES = [
+    (3, 9, 9, 64, 48, 3, 3, 1, 1),       # 16-byte loaders
+    (2, 7, 6, 5, 7, 3, 2, (2, 1), (1, 0)),   # element-wise loaders, odd output count (scalar tail of the combine pass)
+    (64, 4, 4, 64, 64, 3, 3, 1, 1),      # (y,x,n) row order
+    (2, 8, 8, 32, 10, 1, 1, 1, 0),
+]
+
+
+@pytest.mark.parametrize("variant,split", [(None, 0), (None, 3), ("direct", 0)])
+@pytest.mark.parametrize("shp", BIAS_ACT_SHAPES)
+def test_fwd_bias_act(shp, variant, split):
+    """Biased convolution with leaky-ReLU in the epilogue (unsliced) or in the combine pass (sliced)."""
+    say("bias-act %s %s split=%d" % (shp, variant, split))
+    d = mc.make_desc(*shp)
+    mc.conv2d_set_tuning(mc.VARIANT_DIRECT if variant == "direct" else mc.VARIANT_MFMA, split)
+    X, W, _ = small_inputs(d, hash(shp) & 0xffff)
+    bias = wl.uniform_pm1(wl.stream_key("bias", d.OC), (d.OC,))
+    tX, tW, tb = torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda(), torch.from_numpy(bias).cuda()
+    for b, tbias, slope in ((bias, tb, 0.125), (None, None, 0.0), (bias, tb, 1.0)):
+        buf, out = gu.guarded((d.N, d.OH, d.OW, d.OC))
+        mc.conv2d_fwd_bias_act(tX, tW, tbias, out, d, slope)
+        torch.cuda.synchronize()
+        assert gu.guards_intact(buf)
+        rel, mx = gu.errors(out.cpu().numpy(), gu.oracle.conv2d_fwd_bias_act(X, W, b, slope, (d.sh, d.sw), (d.ph, d.pw)))
+        assert rel <= gu.REL_L2_TOL and mx <= gu.MAX_ABS_TOL, (slope, rel, mx)
+    # no bias, slope 1: exactly the plain forward operator
+    buf, out = gu.guarded((d.N, d.OH, d.OW, d.OC))
+    mc.conv2d_fwd_bias_act(tX, tW, None, out, d, 1.0)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), gu.run_gpu("fwd", d, X, W))
+
+
+def test_fully_connected_as_1x1_convolution():
+    """The paper's fully-connected layer (Fig. 2 `fullconnect`) is the 1x1 operator on a 1x1 map:
+    a CIFAR classifier head, 512 features -> 10 classes, all three operators."""
+    d = mc.make_desc(128, 1, 1, 512, 10, 1, 1, 1, 0)
+    gu.check_all_ops(d, *small_inputs(d, 77), label="fc 512->10")
+    d = mc.make_desc(128, 1, 1, 512, 512, 1, 1, 1, 0)
+    gu.check_all_ops(d, *small_inputs(d, 78), label="fc 512->512")
+
+
 def test_concurrent_streams_inception_branches():
     """Independent operators enqueued on different streams at once (the paper's asynchronous APIs
     run branches of a network in parallel, Sec. III Layer-4 / Sec. IV): the 1x1, 3x3 and 5x5
