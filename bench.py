@@ -150,7 +150,7 @@ def oracle_ms(layer, host, op):
     return (time.perf_counter() - t0) * 1e3
 
 
-def table(mc, torch, cfg_names, with_oracle=False):
+def table(mc, torch, cfg_names, with_oracle=False, with_epilogue=False):
     """Every layer x operator: warm figure (median of 5 batches of 100 launches on one buffer set)
     and, for the rows that HBM bandwidth bounds, a cold figure that rotates over enough distinct
     buffer sets to exceed the 256 MB Infinity Cache."""
@@ -197,6 +197,13 @@ def table(mc, torch, cfg_names, with_oracle=False):
                 log("%-5s %-10s %9.4f %9.2f %7.1f %7.0f %9s %10s  %s"
                     % (layer.name, op, ms, tf, 100 * tf / PEAK_FP32_MFMA_TFLOPS, gbs,
                        "-" if cold is None else "%.4f" % cold, "-" if oms is None else "%.1f" % oms, plan))
+            if with_epilogue:   # forward with bias + leaky-ReLU in the epilogue, against the plain forward
+                bias = torch.zeros(layer.OC, dtype=torch.float32, device="cuda")
+                ms = r.event_ms(lambda: mc.conv2d_fwd_bias_act(r.X, r.W, bias, r.Y, r.desc, 0.01, ws=r.ws))
+                tf = layer.flops / ms / 1e9
+                rows.append({"layer": layer.name, "op": "fwd_bias_act", "ms": round(ms, 5), "tflops": round(tf, 2),
+                             "pct_peak": round(100 * tf / PEAK_FP32_MFMA_TFLOPS, 1)})
+                log("%-5s %-10s %9.4f %9.2f %7.1f" % (layer.name, "fwd+b+act", ms, tf, 100 * tf / PEAK_FP32_MFMA_TFLOPS))
             del r, sets
             torch.cuda.empty_cache()
     if with_oracle:
@@ -279,6 +286,8 @@ def main():
     ap.add_argument("--streams", action="store_true",
                     help="independent operators on separate streams vs one stream (inception branches, "
                          "backward-data next to backward-weight)")
+    ap.add_argument("--with-epilogue", action="store_true",
+                    help="with --table: also time forward with bias + leaky-ReLU in the epilogue")
     ap.add_argument("--with-oracle", action="store_true",
                     help="with --table: also time the CPU oracle once per layer and operator")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -310,7 +319,7 @@ def main():
 
     if args.table is not None:
         names = args.table or list(wl.CONFIGS)
-        rows = table(mc, torch, names, args.with_oracle)
+        rows = table(mc, torch, names, args.with_oracle, args.with_epilogue)
         print(json.dumps({"table": rows}))
         return
 
