@@ -184,7 +184,7 @@ bool tile_compiled(int bm, int bn, bool gather)
     return ((bm == 128 || bm == 64) && (bn == 128 || bn == 64)) || (bm == 32 && bn == 128);
 }
 
-const TileCand kGatherTiles[] = {{128, 128, 0.88, 2}, {128, 64, 0.945, 2}, {64, 64, 0.945, 4}, {128, 32, 0.66, 3}};
+const TileCand kGatherTiles[] = {{128, 128, 0.88, 2}, {128, 64, 0.93, 2}, {64, 64, 0.945, 4}, {128, 32, 0.66, 3}};
 const TileCand kWgradTiles[] = {{128, 128, 0.80, 1}, {64, 128, 0.93, 2}, {128, 64, 0.94, 2}, {64, 64, 0.98, 4},
                                 {32, 128, 0.90, 3}};
 
