@@ -24,7 +24,8 @@
 // is free as long as A and B agree, so a lane reads FOUR consecutive k (one 16-byte LDS
 // read at k = 8*jj + 4*(l/32)) and uses them in four successive MFMAs.
 #include <hip/hip_runtime.h>
-#if defined(EXP_STAMPS)
+// -DMI355CONV_TIMELINE compiles in a per-workgroup timeline (constant-rate clock at eight points).
+#if defined(MI355CONV_TIMELINE)
 namespace mi355conv { __device__ unsigned long long g_stamps[8192 * 8]; }
 #define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) mi355conv::g_stamps[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
 #else
@@ -330,7 +331,7 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     STAMP(5);
 }
 
-#if defined(EXP_STAMPS)
+#if defined(MI355CONV_TIMELINE)
 extern "C" int exp_read_stamps(unsigned long long *host, size_t count)
 {
     return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_stamps), count * sizeof(unsigned long long));

@@ -24,7 +24,9 @@
 // Accuracy: the accumulator is folded into a second one every `flushChunks` stages (512
 // products), so no fp32 chain is longer than that however long the slice is.
 #include <hip/hip_runtime.h>
-#if defined(EXP_STAMPS)
+// -DMI355CONV_TIMELINE compiles in a per-workgroup timeline (constant-rate clock at five points,
+// the CU the workgroup ran on, shader cycles): the measurements behind the pipeline's design.
+#if defined(MI355CONV_TIMELINE)
 namespace mi355conv { __device__ unsigned long long g_wstamps[16384 * 8]; }
 #define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 16384) mi355conv::g_wstamps[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
 #endif
@@ -46,13 +48,10 @@ struct WF {
 };
 }  // namespace
 
-#ifndef WF_OCC64
-#define WF_OCC64 4
-#endif
 // PM: rows in (oh, ow, n) order with N a multiple of 32 and OH*OW <= 64, so that a stage sits on
 // one output position and positions fit 64-bit masks.
 template <int BM, int BN, bool PM>
-__global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 64 * 64) ? WF_OCC64 : 2) void wgrad_fast_kernel(const WgradParams params)
+__global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 64 * 64) ? 4 : 2) void wgrad_fast_kernel(const WgradParams params)
 {
     using T = WF<BM, BN>;
     extern __shared__ f4 smem_raw[];
@@ -61,7 +60,7 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
 
     STAMP(0);
     const WgradView p = wgrad_view(params);
-#if defined(EXP_STAMPS)
+#if defined(MI355CONV_TIMELINE)
     if (threadIdx.x == 0 && blockIdx.x < 16384) {
         g_wstamps[blockIdx.x * 8 + 5] = __builtin_amdgcn_s_getreg((31 << 11) | 4);    // HW_ID
         g_wstamps[blockIdx.x * 8 + 6] = __builtin_amdgcn_s_getreg((31 << 11) | 20);   // XCC_ID
@@ -305,27 +304,17 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
     auto stage = [&](int buf, bool doLoad, int ld, bool doStore, int st, bool adv) __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < kSteps; ++s) {
-#if !defined(EXP_NOBAR)
             if (s == kSlots) __syncthreads();
-#endif
             const int sp = s + kAhead;
-#if !defined(EXP_NOFRAG)
             if (sp < kSteps) read_step(buf, sp, fa[sp % kRing], fb[sp % kRing]);
             else read_step(buf ^ 1, sp - kSteps, fa[sp % kRing], fb[sp % kRing]);
-#endif
 #pragma unroll
             for (int q = 0; q < kItems; ++q)
                 if (q * kSlots / kItems == s) {
-#if !defined(EXP_NOGLOAD)
                     if (doLoad) gload_item(q, ggS[ld], gxS[ld]);
-#endif
-#if !defined(EXP_NOLSTORE)
                     if (doStore) lds_store_item(q, buf ^ 1, ggS[st], gxS[st]);
-#endif
                 }
-#if !defined(EXP_NOSET)
             if (adv && s >= kAdvStep) set_piece(s - kAdvStep, advCh);
-#endif
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < T::MB; ++i)
@@ -403,12 +392,12 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
             }
         }
     STAMP(4);
-#if defined(EXP_STAMPS)
+#if defined(MI355CONV_TIMELINE)
     if (threadIdx.x == 0 && blockIdx.x < 16384) g_wstamps[blockIdx.x * 8 + 7] = clock64() - expClk0;
 #endif
 }
 
-#if defined(EXP_STAMPS)
+#if defined(MI355CONV_TIMELINE)
 extern "C" int exp_read_wstamps(unsigned long long *host, size_t count)
 {
     return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_wstamps), count * sizeof(unsigned long long));
