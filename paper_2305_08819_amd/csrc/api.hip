@@ -30,7 +30,8 @@ struct Plan {
     int split = 1;
     int posMajor = 0;
     int elem = 0;          // element-wise loader (channel counts the 16-byte loader cannot take)
-    int fast = 0;          // backward-weight: aligned-map kernel without accumulator folding
+    int fast = 0;          // backward-weight: aligned-map kernel
+    int smallIc = 0;       // backward-data: patch-gradient GEMM + col2im kernel for very few input channels
     int grid = 0;
     int tilesM = 0, tilesN = 0;
     int flushChunks = 16;
@@ -396,6 +397,19 @@ Plan plan_bwd_data(const Shape &s)
                          buffer_addressable(s, (long long)s.N * s.OH * s.OW * s.OC, s.OW, s.OC);
     if (forced == MI355CONV_VARIANT_DIRECT || !fits) return pl;
     pl.variant = MI355CONV_VARIANT_MFMA;
+    // very few input channels (first layer): P = dY x W as a dense GEMM, then a col2im gather
+    int ftm = 0, ftn = 0;
+    if (s.sh == 1 && s.sw == 1 && s.IC <= 4 && s.FH * s.FW * s.IC <= 32 && s.OC % kBK == 0 &&
+        (4 + s.FH - 1) * (32 + s.FW - 1) <= 224 && g_forceSplit.load() == 0 && !forced_tile(&ftm, &ftn, true) &&
+        (long long)s.N * s.OH * s.OW * s.OC * 4 < (1LL << 31) && pl.outElems * 4 < (1LL << 31)) {
+        pl.smallIc = 1;
+        pl.bm = 128;     // 4 x 32 pixels of dX per workgroup
+        pl.bn = 32;
+        pl.tilesM = s.N * ceil_div(s.IH, 4) * ceil_div(s.IW, 32);
+        pl.tilesN = 1;
+        finish_plan(pl, 1);
+        return pl;
+    }
     if (!chunked) {
         pl.elem = 1;
         // every phase walks the whole flat (tap, oc) range; taps of other phases multiply zeros
@@ -989,6 +1003,17 @@ int conv2d_bwd_data(const float *dY, const float *W, float *dX, const conv2d_des
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (pl.variant == MI355CONV_VARIANT_DIRECT) {
         hipError_t e = launch_direct_bwd_data(dY, W, dX, s, st);
+        return e == hipSuccess ? MI355CONV_OK : hip_fail(e);
+    }
+    if (pl.smallIc) {
+        SmallIcParams q;
+        memset(&q, 0, sizeof q);
+        q.G = dY; q.W = W; q.dX = dX;
+        q.gBytes = (unsigned)((long long)s.N * s.OH * s.OW * s.OC * 4);
+        q.wBytes = (unsigned)((long long)s.OC * s.FH * s.FW * s.IC * 4);
+        q.N = s.N; q.IH = s.IH; q.IW = s.IW; q.IC = s.IC; q.OC = s.OC; q.OH = s.OH; q.OW = s.OW;
+        q.FH = s.FH; q.FW = s.FW; q.ph = s.ph; q.pw = s.pw;
+        hipError_t e = launch_bwd_data_small_ic(q, st);
         return e == hipSuccess ? MI355CONV_OK : hip_fail(e);
     }
     return run_gather(dY, W, dX, s, pl, true, ws, st);

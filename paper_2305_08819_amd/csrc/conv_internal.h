@@ -221,6 +221,15 @@ __device__ __forceinline__ WgradView wgrad_view(const WgradParams &p)
 }
 #endif
 
+// ---- backward-data for very few input channels (kernel_small_ic.hip) ----------------------------
+struct SmallIcParams {
+    const float *G;       // dY [N, OH, OW, OC]
+    const float *W;       // [OC, FH, FW, IC]
+    float *dX;            // [N, IH, IW, IC]
+    unsigned gBytes, wBytes;
+    int N, IH, IW, IC, OC, OH, OW, FH, FW, ph, pw;
+};
+
 // MI355X spreads consecutive workgroup ids round-robin over its 8 XCDs, each with its own
 // L2.  Map the hardware id to a logical id so that `unit` consecutive logical ids (workgroups
 // that share operand tiles) run on one XCD, while units are still dealt round-robin so every
@@ -282,5 +291,7 @@ hipError_t launch_wgrad(const WgradParams &p, int bm, int bn, bool xElem, int gr
 // Aligned maps (OW divides 32; OH*OW divides or is a multiple of 32), IC % 4 == 0, OC % 4 == 0,
 // tensors below 2^31 bytes.
 hipError_t launch_wgrad_fast(const WgradParams &p, int bm, int bn, int grid, hipStream_t st);
+// unit stride, FH*FW*IC <= 32, IC <= 4, OC % 32 == 0, (4+FH-1)*(32+FW-1) <= 224, tensors below 2^31 bytes
+hipError_t launch_bwd_data_small_ic(const SmallIcParams &p, hipStream_t st);
 
 }  // namespace mi355conv

@@ -101,6 +101,27 @@ def test_bwd_data_few_channels(shp, split):
     gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), label=str(shp))
 
 
+# backward-data with very few input channels, unit stride: patch-gradient GEMM + col2im kernel
+SMALL_IC_SHAPES = [
+    (3, 7, 9, 3, 64, 3, 3, 1, 1),
+    (2, 33, 35, 3, 32, 3, 3, 1, 1),       # several tiles along both axes, ragged edges
+    (2, 9, 40, 4, 96, 3, 2, 1, (2, 0)),   # pad larger than the usual, non-square filter
+    (5, 6, 5, 1, 32, 3, 3, 1, 0),         # no padding, one channel
+    (2, 8, 8, 2, 64, 1, 1, 1, 0),
+    (1, 5, 70, 3, 64, 2, 3, 1, (0, 2)),
+]
+
+
+@pytest.mark.parametrize("shp", SMALL_IC_SHAPES)
+def test_bwd_data_small_ic(shp):
+    say("small-ic %s" % (shp,))
+    d = mc.make_desc(*shp)
+    mc.conv2d_set_tuning(mc.VARIANT_MFMA, 0)
+    pl = mc.conv2d_query_plan(mc.OP_BWD_DATA, d)
+    assert pl.variant == mc.VARIANT_MFMA and pl.grid == d.N * ((d.IH + 3) // 4) * ((d.IW + 31) // 32)
+    gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), ops=("bwd_data",), label=str(shp))
+
+
 # backward-weight with at most 32 output channels on aligned maps: the 32x128 tile (one block row)
 NARROW_OC_SHAPES = [
     (4, 8, 8, 16, 32, 3, 3, 1, 1),
