@@ -494,6 +494,27 @@ Plan plan_bwd_weight(const Shape &s)
     const bool eligible = s.OC % 4 == 0 && M < kMaxElems - kBK && (long long)s.N * s.IH * s.IW < kMaxElems;
     if (forced == MI355CONV_VARIANT_DIRECT || !eligible) return pl;
     pl.variant = MI355CONV_VARIANT_MFMA;
+    int ftm = 0, ftn = 0;
+    if (s.FH * s.FW * s.IC <= 32 && !forced_tile(&ftm, &ftn, false) &&
+        (long long)s.N * s.IH * s.IW * s.IC * 4 < (1LL << 31) && M * s.OC * 4 < (1LL << 31)) {
+        // very few input channels (first layer): one 64 x 32 tile per 64 output channels, rows sliced
+        pl.smallIc = 1;
+        pl.bm = 64;
+        pl.bn = 32;
+        pl.tilesM = ceil_div(s.OC, 64);
+        pl.tilesN = 1;
+        const int chunks = ceil_div(M, kBK);
+        int sp = g_forceSplit.load();
+        if (sp <= 0) {   // about two workgroups per CU, at least 4 stages each
+            sp = 512 / pl.tilesM;
+            if (sp > chunks / 4) sp = chunks / 4;
+        }
+        if (sp > chunks) sp = chunks;
+        if (sp > kMaxSplit) sp = kMaxSplit;
+        if (sp < 1) sp = 1;
+        finish_plan(pl, sp);
+        return pl;
+    }
     pl.elem = s.IC % 4 != 0;
     const int chunksAll = ceil_div(M, kBK);
     const int ohow = s.OH * s.OW;
@@ -1040,6 +1061,30 @@ int conv2d_bwd_weight(const float *X, const float *dY, float *dW, const conv2d_d
     if (pl.variant == MI355CONV_VARIANT_DIRECT) {
         hipError_t e = launch_direct_bwd_weight(X, dY, dW, s, st);
         return e == hipSuccess ? MI355CONV_OK : hip_fail(e);
+    }
+    if (pl.smallIc) {
+        SmallIcParams q;
+        memset(&q, 0, sizeof q);
+        q.G = dY; q.X = X;
+        q.C = pl.split > 1 ? static_cast<float *>(ws) : dW;
+        q.gBytes = (unsigned)((long long)s.N * s.OH * s.OW * s.OC * 4);
+        q.xBytes = (unsigned)((long long)s.N * s.IH * s.IW * s.IC * 4);
+        q.N = s.N; q.IH = s.IH; q.IW = s.IW; q.IC = s.IC; q.OC = s.OC; q.OH = s.OH; q.OW = s.OW;
+        q.FH = s.FH; q.FW = s.FW; q.ph = s.ph; q.pw = s.pw; q.sh = s.sh; q.sw = s.sw;
+        q.split = pl.split;
+        q.M = s.N * s.OH * s.OW;
+        q.sliceStride = pl.sliceStride;
+        q.divOHOW = make_fastdiv((unsigned)(s.OH * s.OW));
+        q.divOW = make_fastdiv((unsigned)s.OW);
+        q.divIC = make_fastdiv((unsigned)s.IC);
+        q.divFW = make_fastdiv((unsigned)s.FW);
+        hipError_t e = launch_wgrad_small_ic(q, st);
+        if (e != hipSuccess) return hip_fail(e);
+        if (pl.split > 1) {
+            e = launch_slice_reduce(static_cast<const float *>(ws), dW, pl.outElems, pl.split, pl.sliceStride, st);
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        return MI355CONV_OK;
     }
     WgradParams w;
     memset(&w, 0, sizeof w);

@@ -228,6 +228,13 @@ struct SmallIcParams {
     float *dX;            // [N, IH, IW, IC]
     unsigned gBytes, wBytes;
     int N, IH, IW, IC, OC, OH, OW, FH, FW, ph, pw;
+    // backward-weight only
+    const float *X;       // [N, IH, IW, IC]
+    float *C;             // dW, or workspace base when split > 1
+    unsigned xBytes;
+    int sh, sw, split, M;
+    long long sliceStride;
+    FastDiv divOHOW, divOW, divIC, divFW;
 };
 
 // MI355X spreads consecutive workgroup ids round-robin over its 8 XCDs, each with its own
@@ -293,5 +300,7 @@ hipError_t launch_wgrad(const WgradParams &p, int bm, int bn, bool xElem, int gr
 hipError_t launch_wgrad_fast(const WgradParams &p, int bm, int bn, int grid, hipStream_t st);
 // unit stride, FH*FW*IC <= 32, IC <= 4, OC % 32 == 0, (4+FH-1)*(32+FW-1) <= 224, tensors below 2^31 bytes
 hipError_t launch_bwd_data_small_ic(const SmallIcParams &p, hipStream_t st);
+// FH*FW*IC <= 32, any stride; grid = ceil(OC / 64) * split
+hipError_t launch_wgrad_small_ic(const SmallIcParams &p, hipStream_t st);
 
 }  // namespace mi355conv

@@ -172,4 +172,143 @@ hipError_t launch_bwd_data_small_ic(const SmallIcParams &p, hipStream_t st)
     return hipGetLastError();
 }
 
+// ---- backward-weight for very few input channels ----------------------------------------------
+// dW[oc, (fh,fw,ic)] = sum_m dY[m, oc] * patch[m, (fh,fw,ic)] with at most 32 columns: one 64 x 32
+// output tile per 64 output channels, the rows m = (n, oh, ow) cut into `split` slices.  The
+// kernel is bound by reading dY once, so it moves in macro-stages of 4 x 32 rows: all loads of a
+// macro-stage are in flight together (dY with 16-byte loads, the patch matrix element by element
+// - each thread owns one column, so its filter tap is fixed), and the next macro-stage is
+// requested before the current one is multiplied.  The four waves are 2 (oc halves) x 2 (halves
+// of a 32-row stage's 16 MFMA steps); the two step halves are added through LDS at the end.
+namespace {
+constexpr int kSub = 4;                                   // 32-row stages per macro-stage
+constexpr int kWsLDG = 64 + 8, kWsLDX = 32 + 8;
+constexpr int kWsGStage = kBK * kWsLDG, kWsXStage = kBK * kWsLDX;
+}  // namespace
+
+__global__ __launch_bounds__(kThreads, 2) void wgrad_small_ic_kernel(const SmallIcParams p)
+{
+    constexpr int LDG = kWsLDG, LDX = kWsLDX, G_STAGE = kWsGStage, X_STAGE = kWsXStage;
+    extern __shared__ f4 smem_raw[];
+    float *Gs = reinterpret_cast<float *>(smem_raw);       // [kSub][32 rows][LDG]
+    float *Xs = Gs + kSub * G_STAGE;                       // [kSub][32 rows][LDX]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int slice = blockIdx.x % p.split, tmo = blockIdx.x / p.split;
+    const int oc0 = tmo * 64;
+    const int Kp = p.FH * p.FW * p.IC, ohow = p.OH * p.OW;
+    const int chunksTotal = (p.M + kBK - 1) / kBK;
+    const int ch0 = (int)((long long)slice * chunksTotal / p.split), ch1 = (int)((long long)(slice + 1) * chunksTotal / p.split);
+
+    constexpr int kOutOfRange = (int)0x80000000;
+    const __amdgpu_buffer_rsrc_t rsrcG =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.G), 0, (int)p.gBytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcX =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.X), 0, (int)p.xBytes, 0x00020000);
+
+    // dY loader: 32 rows x 16 segments per stage, 2 per thread; rows past M are past the tensor and read zeros
+    const int gSeg = tid & 15, gRow = tid >> 4;
+    int gOff[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+        gOff[i] = oc0 + gSeg * 4 < p.OC ? ((gRow + 16 * i) * p.OC + oc0 + gSeg * 4) * 4 : kOutOfRange;
+    // patch loader: thread owns column xCol (its tap is fixed) and rows xRow + 8*i of every stage
+    const int xCol = tid & 31, xRow = tid >> 5;
+    const bool colOk = xCol < Kp;
+    const int tap = colOk ? (int)fast_div((unsigned)xCol, p.divIC) : 0;
+    const int ic = xCol - tap * p.IC;
+    const int fh = (int)fast_div((unsigned)tap, p.divFW), fw = tap - fh * p.FW;
+
+    f4 gg[kSub][2];
+    float gx[kSub][4];
+    auto gload = [&](int chBase) __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < kSub; ++s) {
+            const int ch = chBase + s;
+            const bool live = ch < ch1;      // uniform; stages past the slice load zeros
+            const int m0 = ch * kBK;
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                gg[s][i] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                      rsrcG, live ? gOff[i] : kOutOfRange, live ? m0 * p.OC * 4 : 0, 0));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int m = m0 + xRow + 8 * i;
+                const int n = (int)fast_div((unsigned)m, p.divOHOW);
+                const int r = m - n * ohow;
+                const int oh = (int)fast_div((unsigned)r, p.divOW), ow = r - oh * p.OW;
+                const int ih = oh * p.sh - p.ph + fh, iw = ow * p.sw - p.pw + fw;
+                const bool ok = live && colOk && m < p.M && (unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW;
+                const int off = ok ? (((n * p.IH + ih) * p.IW + iw) * p.IC + ic) * 4 : kOutOfRange;
+                gx[s][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrcX, off, 0, 0));
+            }
+        }
+    };
+    auto lds_store = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < kSub; ++s) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                *reinterpret_cast<f4 *>(Gs + s * G_STAGE + (gRow + 16 * i) * LDG + gSeg * 4) = gg[s][i];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) Xs[s * X_STAGE + (xRow + 8 * i) * LDX + xCol] = gx[s][i];
+        }
+    };
+
+    float16v acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    const int wo = wave >> 1, wk = wave & 1;   // oc half, half of a stage's MFMA steps
+
+    if (ch0 < ch1) {
+        gload(ch0);
+        for (int ch = ch0; ch < ch1; ch += kSub) {
+            lds_store();
+            __syncthreads();
+            if (ch + kSub < ch1) gload(ch + kSub);
+            // lane (l32, lh) supplies row k = 2*step + lh of a stage: G^T as A, patch as B
+#pragma unroll
+            for (int s = 0; s < kSub; ++s) {
+                const float *g = Gs + s * G_STAGE + lh * LDG + wo * 32 + l32;
+                const float *x = Xs + s * X_STAGE + lh * LDX + l32;
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    const int step = wk * 8 + t;
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(g[2 * step * LDG], x[2 * step * LDX], acc, 0, 0, 0);
+                }
+            }
+            __syncthreads();   // all waves are done with this macro-stage's tiles
+        }
+    }
+
+    // add the two step halves: waves with wk = 1 hand their block to the wave with the same oc half
+    float *red = Gs;   // 64 x 33 floats, the stage buffers are free now
+    if (wk == 1) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) red[(wo * 32 + 8 * (r / 4) + 4 * lh + (r % 4)) * 33 + l32] = acc[r];
+    }
+    __syncthreads();
+    if (wk == 0) {
+        float *C = p.C + (long long)slice * p.sliceStride;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = 8 * (r / 4) + 4 * lh + (r % 4);
+            const int oc = oc0 + wo * 32 + row;
+            if (oc < p.OC && l32 < Kp) C[oc * Kp + l32] = acc[r] + red[(wo * 32 + row) * 33 + l32];
+        }
+    }
+}
+
+hipError_t launch_wgrad_small_ic(const SmallIcParams &p, hipStream_t st)
+{
+    if (p.FH * p.FW * p.IC > 32 || p.split < 1) return hipErrorInvalidValue;
+    constexpr size_t smem = (size_t)kSub * (kWsGStage + kWsXStage) * sizeof(float);
+    static_assert(64 * 33 <= kSub * kWsGStage, "the reduction buffer fits over the dY stages");
+    static_assert(smem <= 64 * 1024, "within the default dynamic LDS limit");
+    const int grid = ((p.OC + 63) / 64) * p.split;
+    hipLaunchKernelGGL(wgrad_small_ic_kernel, dim3((unsigned)grid), dim3(kThreads), smem, st, p);
+    return hipGetLastError();
+}
+
 }  // namespace mi355conv

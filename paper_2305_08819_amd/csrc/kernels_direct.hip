@@ -113,7 +113,8 @@ __global__ __launch_bounds__(256) void direct_bwd_weight_kernel(const float *__r
 // out[i] = sum_s ws[s*stride + i].  The partials are fp32; they are added in fp64 in a fixed
 // order and rounded once, so the result is reproducible and the combine step adds no error of
 // its own beyond the final rounding.  A workgroup owns 256/G float4 columns; G thread groups
-// each add every G-th slice, then group 0 adds the G group sums in group order through LDS.
+// each add every G-th slice, then the G group sums are combined by halving (group g takes
+// group g + w for w = G/2, G/4, ... 1) through LDS - a fixed tree, whatever the timing.
 // Optional epilogue (cols > 0): out = act(sum + bias[column]), act(v) = v > 0 ? v : slope * v, the
 // same fp32 arithmetic as the epilogue of an unsliced launch.
 __device__ __forceinline__ float bias_act(float v, long long index, const float *bias, float slope, int cols)
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(256) void slice_reduce_kernel(const float *__restri
                                                            const float *__restrict__ bias, float slope, int cols)
 {
     constexpr int COLS = 256 / G;
-    __shared__ double red[G > 1 ? (G - 1) * COLS * 4 : 1];
+    __shared__ double red[G > 1 ? 256 * 4 : 1];
     const int c = threadIdx.x % COLS, g = threadIdx.x / COLS;
     const long long i = (long long)blockIdx.x * COLS + c;
     double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
@@ -144,17 +145,18 @@ __global__ __launch_bounds__(256) void slice_reduce_kernel(const float *__restri
         }
     }
     if (G > 1) {
-        if (g > 0) {
-            double *r = red + ((g - 1) * COLS + c) * 4;
-            r[0] = a0; r[1] = a1; r[2] = a2; r[3] = a3;
-        }
+        double *mine = red + (g * COLS + c) * 4;
+        mine[0] = a0; mine[1] = a1; mine[2] = a2; mine[3] = a3;
         __syncthreads();
-        if (g == 0) {
-            for (int k = 1; k < G; ++k) {
-                const double *r = red + ((k - 1) * COLS + c) * 4;
-                a0 += r[0]; a1 += r[1]; a2 += r[2]; a3 += r[3];
+#pragma unroll
+        for (int w = G / 2; w >= 1; w /= 2) {
+            if (g < w) {
+                const double *other = red + ((g + w) * COLS + c) * 4;
+                mine[0] += other[0]; mine[1] += other[1]; mine[2] += other[2]; mine[3] += other[3];
             }
+            __syncthreads();
         }
+        a0 = mine[0]; a1 = mine[1]; a2 = mine[2]; a3 = mine[3];
     }
     if (g == 0 && i < count4)
         reinterpret_cast<float4 *>(out)[i] =
@@ -219,17 +221,24 @@ hipError_t launch_slice_reduce(const float *ws, float *out, long long count, int
     if (count4 > 0) {
         // more thread groups per column when there are few columns and many slices
         int G = 1;
-        while (G < 16 && G * 2 <= split && count4 * G < (1 << 17)) G *= 2;
+        while (G < 256 && G * 2 <= split && count4 * G < (1 << 17)) G *= 2;
         const long long perWg = 256 / G;   // float4 columns per workgroup
         const unsigned grid = (unsigned)((count4 + perWg - 1) / perWg);
         const long long stride4 = stride >> 2;
+#define MI355CONV_SR(G_)                                                                                  \
+    case G_:                                                                                              \
+        hipLaunchKernelGGL(slice_reduce_kernel<G_>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, \
+                           stride4, bias, slope, cols);                                                   \
+        break;
         switch (G) {
-        case 1: hipLaunchKernelGGL(slice_reduce_kernel<1>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4, bias, slope, cols); break;
-        case 2: hipLaunchKernelGGL(slice_reduce_kernel<2>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4, bias, slope, cols); break;
-        case 4: hipLaunchKernelGGL(slice_reduce_kernel<4>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4, bias, slope, cols); break;
-        case 8: hipLaunchKernelGGL(slice_reduce_kernel<8>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4, bias, slope, cols); break;
-        default: hipLaunchKernelGGL(slice_reduce_kernel<16>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4, bias, slope, cols); break;
+            MI355CONV_SR(1) MI355CONV_SR(2) MI355CONV_SR(4) MI355CONV_SR(8) MI355CONV_SR(16) MI355CONV_SR(32)
+            MI355CONV_SR(64) MI355CONV_SR(128)
+        default:
+            hipLaunchKernelGGL(slice_reduce_kernel<256>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4,
+                               bias, slope, cols);
+            break;
         }
+#undef MI355CONV_SR
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -119,7 +119,20 @@ def test_bwd_data_small_ic(shp):
     mc.conv2d_set_tuning(mc.VARIANT_MFMA, 0)
     pl = mc.conv2d_query_plan(mc.OP_BWD_DATA, d)
     assert pl.variant == mc.VARIANT_MFMA and pl.grid == d.N * ((d.IH + 3) // 4) * ((d.IW + 31) // 32)
-    gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), ops=("bwd_data",), label=str(shp))
+    gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), label=str(shp))
+
+
+@pytest.mark.parametrize("split", [0, 1, 7])
+@pytest.mark.parametrize("shp", SMALL_IC_SHAPES + [(3, 9, 9, 3, 32, 3, 3, 2, 1), (2, 11, 8, 1, 100, 5, 5, (1, 2), 2),
+                                                   (70, 4, 4, 2, 64, 3, 3, 1, 1)])
+def test_bwd_weight_small_ic(shp, split):
+    """Backward-weight with at most 32 patch columns (FH*FW*IC): 64 x 32 tile, rows sliced."""
+    say("small-ic wgrad %s split=%d" % (shp, split))
+    d = mc.make_desc(*shp)
+    mc.conv2d_set_tuning(mc.VARIANT_MFMA, split)
+    pl = mc.conv2d_query_plan(mc.OP_BWD_WEIGHT, d)
+    assert pl.variant == mc.VARIANT_MFMA and (pl.tile_m, pl.tile_n) == (64, 32)
+    gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), ops=("bwd_weight",), label=str(shp))
 
 
 # backward-weight with at most 32 output channels on aligned maps: the 32x128 tile (one block row)
