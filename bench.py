@@ -8,6 +8,7 @@ inputs resident in HBM.  The default workload is the ResNet-style down-sampling 
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-cpu-baseline]
   python bench.py --table [cfg2 cfg3 ...] [--with-oracle]   per-layer, per-operator table (stderr + JSON line)
+  python bench.py --workload cfg5           a whole configuration back to back (VGG-16: 39 operators per step)
   python bench.py --streams                 independent operators on separate streams vs one stream
 """
 from __future__ import annotations
@@ -321,6 +322,33 @@ def main():
         names = args.table or list(wl.CONFIGS)
         rows = table(mc, torch, names, args.with_oracle, args.with_epilogue)
         print(json.dumps({"table": rows}))
+        return
+
+    if args.workload in wl.CONFIGS:
+        # a whole configuration back to back on one stream (e.g. cfg5: the 39 operators of VGG-16)
+        layers = wl.CONFIGS[args.workload]
+        rs = [LayerRunner(l, mc, torch, random_fill=True) for l in layers]
+        rs[0].spin_up()
+
+        def stack():
+            for r in rs:
+                r.step()
+        for _ in range(max(args.warmup // 10, 5)):
+            stack()
+        steps = max(args.steps // 10, 10)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            stack()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        flop = 3 * sum(l.flops for l in layers)
+        print(json.dumps({"metric": "TFLOP/s and % FP32 MFMA peak per conv op (fwd/dgrad/wgrad), CIFAR shapes",
+                          "value": round(flop / ms / 1e9, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": steps,
+                          "ms_per_step": round(ms, 5), "higher_is_better": True, "dtype": "f32", "data": "synthetic",
+                          "config": {"workload": "%s: %d layers x (fwd+bwd_data+bwd_weight) back to back on one stream"
+                                                 % (args.workload, len(layers)), "flop_per_step": flop,
+                                     "pct_fp32_mfma_peak": round(100 * flop / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 2)}}))
         return
 
     layer = {l.name: l for l in wl.all_layers()}[args.workload]

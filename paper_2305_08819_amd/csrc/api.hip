@@ -10,6 +10,7 @@
 #include <cstdio>
 #include <cstring>
 #include <mutex>
+#include <unordered_map>
 
 using namespace mi355conv;
 
@@ -809,21 +810,24 @@ void plan_balance_wgrad(const Shape &s, Plan &pl)
     pl.balance = 1;
 }
 
-// Plans depend on the descriptor and the tuning overrides only; the last ones are kept in a small
-// direct-mapped table so that the enqueue path does not repeat the search (and the
-// longest-first dealing) on every call.
+// Plans depend on the descriptor and the tuning overrides only; they are kept in a hash map so
+// that the enqueue path does not repeat the search (and the longest-first dealing, which takes
+// a good fraction of a millisecond) on every call.
 struct PlanKey {
     int v[17];
     bool operator==(const PlanKey &o) const { return memcmp(v, o.v, sizeof v) == 0; }
 };
-struct PlanSlot {
-    bool used = false;
-    PlanKey key;
-    Plan plan;
+struct PlanKeyHash {
+    size_t operator()(const PlanKey &k) const
+    {
+        unsigned h = 2166136261u;
+        for (int i = 0; i < 17; ++i) h = (h ^ (unsigned)k.v[i]) * 16777619u;
+        return h;
+    }
 };
-constexpr int kPlanSlots = 256;
+constexpr size_t kMaxCachedPlans = 4096;   // the map is emptied when it grows past this
 std::mutex g_planMutex;
-PlanSlot *g_planTable = nullptr;   // allocated on first use, never freed
+std::unordered_map<PlanKey, Plan, PlanKeyHash> *g_planMap = nullptr;   // allocated on first use, never freed
 
 int make_plan(int op, const Shape &s, Plan *pl)
 {
@@ -834,14 +838,14 @@ int make_plan(int op, const Shape &s, Plan *pl)
                           g_forceVariant.load(), g_forceSplit.load(), g_forceBM.load(), g_forceBN.load(),
                           g_forcePosMajor.load()};
     memcpy(k.v, vals, sizeof vals);
-    unsigned h = 2166136261u;
-    for (int i = 0; i < 17; ++i) h = (h ^ (unsigned)k.v[i]) * 16777619u;
-    const int slot = (int)(h % kPlanSlots);
     {
         std::lock_guard<std::mutex> lock(g_planMutex);
-        if (g_planTable && g_planTable[slot].used && g_planTable[slot].key == k) {
-            *pl = g_planTable[slot].plan;
-            return MI355CONV_OK;
+        if (g_planMap) {
+            auto it = g_planMap->find(k);
+            if (it != g_planMap->end()) {
+                *pl = it->second;
+                return MI355CONV_OK;
+            }
         }
     }
     switch (op) {
@@ -860,10 +864,9 @@ int make_plan(int op, const Shape &s, Plan *pl)
     }
     {
         std::lock_guard<std::mutex> lock(g_planMutex);
-        if (!g_planTable) g_planTable = new PlanSlot[kPlanSlots];
-        g_planTable[slot].key = k;
-        g_planTable[slot].plan = *pl;
-        g_planTable[slot].used = true;
+        if (!g_planMap) g_planMap = new std::unordered_map<PlanKey, Plan, PlanKeyHash>();
+        if (g_planMap->size() >= kMaxCachedPlans) g_planMap->clear();
+        (*g_planMap)[k] = *pl;
     }
     return MI355CONV_OK;
 }
