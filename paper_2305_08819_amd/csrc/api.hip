@@ -520,7 +520,7 @@ Plan plan_bwd_weight(const Shape &s)
     const int chunksAll = ceil_div(M, kBK);
     const int ohow = s.OH * s.OW;
     // fast kernel: rows of a 32-row stage always sit at the same place relative to its first pixel
-    const bool aligned = kBK % s.OW == 0 && (ohow % kBK == 0 || kBK % ohow == 0);
+    const bool aligned = (kBK % s.OW == 0 && (ohow % kBK == 0 || kBK % ohow == 0)) || s.OW % kBK == 0;
     pl.fast = !pl.elem && aligned && chunksAll >= 1 &&
               (long long)s.N * s.IH * s.IW * s.IC * 4 < (1LL << 31) && M * s.OC * 4 < (1LL << 31);
     // the fast kernel keeps a 64-bit mask of output positions in (oh,ow,n) order

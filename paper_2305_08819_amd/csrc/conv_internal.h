@@ -295,7 +295,8 @@ hipError_t launch_gather_gemm(const GatherGemmParams &p, bool bwdData, int bm, i
 // same tiles (except 128x128), element-wise loader: any channel counts
 hipError_t launch_gather_elem(const GatherGemmParams &p, bool bwdData, int bm, int bn, int grid, hipStream_t st);
 hipError_t launch_wgrad(const WgradParams &p, int bm, int bn, bool xElem, int grid, hipStream_t st);
-// Aligned maps (OW divides 32; OH*OW divides or is a multiple of 32), IC % 4 == 0, OC % 4 == 0,
+// Aligned maps (OW divides 32 and OH*OW divides or is a multiple of 32; or OW a multiple of 32, row-major
+// order only), IC % 4 == 0, OC % 4 == 0,
 // tensors below 2^31 bytes.
 hipError_t launch_wgrad_fast(const WgradParams &p, int bm, int bn, int grid, hipStream_t st);
 // unit stride, FH*FW*IC <= 32, IC <= 4, OC % 32 == 0, (4+FH-1)*(32+FW-1) <= 224, tensors below 2^31 bytes

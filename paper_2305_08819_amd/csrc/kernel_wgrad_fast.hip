@@ -50,7 +50,10 @@ struct WF {
 
 // PM: rows in (oh, ow, n) order with N a multiple of 32 and OH*OW <= 64, so that a stage sits on
 // one output position and positions fit 64-bit masks.
-template <int BM, int BN, bool PM>
+// WIDE (with PM false): OW is a multiple of 32 instead of a divisor, so a stage is 32 neighbouring
+// pixels of one output row that starts at column ow0 = 0, 32, 64, ...: the column validity of a
+// thread's tap then depends on ow0 and is tested per stage (two more VALU per load).
+template <int BM, int BN, bool PM, bool WIDE = false>
 __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 64 * 64) ? 4 : 2) void wgrad_fast_kernel(const WgradParams params)
 {
     using T = WF<BM, BN>;
@@ -118,6 +121,7 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
     // X: element offset of the thread's part of the address; validity inputs.
     // Rows past the last image need no test: their addresses lie past the end of X and of G.
     int xPart[T::PX];
+    int xWBase[WIDE ? T::PX : 1];           // WIDE: input column of the thread's tap when the stage starts at ow0 = 0
     int xHBase[T::PX];                      // !PM: input row relative to the stage's first one; far out of range
                                             //      where the thread's column is never inside the image
     unsigned long long liveMask = 0ull;     // PM: positions at which this thread's tap is inside the image
@@ -155,7 +159,12 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
             const int iw = ow * p.sw - p.pw + xFw;
             xHBase[i] = doh * p.sh - p.ph + xFh;
             xPart[i] = ((dn * p.IH + xHBase[i]) * p.IW + iw) * p.IC + xIc;   // may be negative
-            if (!(xOk && (unsigned)iw < (unsigned)p.IW)) xHBase[i] = kInvalidCoord;
+            if (WIDE) {
+                xWBase[i] = iw;
+                if (!xOk) xHBase[i] = kInvalidCoord;
+            } else if (!(xOk && (unsigned)iw < (unsigned)p.IW)) {
+                xHBase[i] = kInvalidCoord;
+            }
         }
     }
 
@@ -179,7 +188,7 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
     // instead of leaving one long run of ALU work between two MFMAs.
     int gSoff = 0;                 // bytes
     int xVoff[T::PX];              // bytes, recomputed per stage
-    int curA = 0, curB = 0, curUni = 0;   // uniform intermediates handed from piece to piece
+    int curA = 0, curB = 0, curUni = 0, curW = 0;   // uniform intermediates handed from piece to piece
     auto set_piece = [&](int piece, int ch) __attribute__((always_inline)) {
         if constexpr (PM) {
             if (piece == 0) {
@@ -207,14 +216,17 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
                 curB = m0 - curA * ohow;                              // first output pixel inside it
             } else if (piece == 1) {
                 const int oh0 = (int)fast_div((unsigned)curB, p.divOW);
+                if (WIDE) curW = (curB - oh0 * p.OW) * p.sw;          // ow0 * sw: the stage's column shift
                 curB = oh0 * p.sh;
-                curUni = (curA * p.IH + curB) * p.IW * p.IC;
+                curUni = ((curA * p.IH + curB) * p.IW + (WIDE ? curW : 0)) * p.IC;
             } else {
 #pragma unroll
                 for (int i = 0; i < T::PX; ++i)
                     if ((i < T::PX / 2) == (piece == 2)) {
                         const int off = (xPart[i] + curUni) * 4;
-                        xVoff[i] = (unsigned)(curB + xHBase[i]) < (unsigned)p.IH ? off : kOutOfRange;
+                        bool ok = (unsigned)(curB + xHBase[i]) < (unsigned)p.IH;
+                        if (WIDE) ok = ok && (unsigned)(curW + xWBase[i]) < (unsigned)p.IW;
+                        xVoff[i] = ok ? off : kOutOfRange;
                     }
             }
         }
@@ -404,11 +416,11 @@ extern "C" int exp_read_wstamps(unsigned long long *host, size_t count)
 }
 #endif
 
-template <int BM, int BN, bool PM>
+template <int BM, int BN, bool PM, bool WIDE = false>
 static hipError_t launch_fast_one(const WgradParams &p, int grid, hipStream_t st)
 {
     using T = WF<BM, BN>;
-    auto kern = wgrad_fast_kernel<BM, BN, PM>;
+    auto kern = wgrad_fast_kernel<BM, BN, PM, WIDE>;
     static bool attrSet[16] = {};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -426,10 +438,14 @@ static hipError_t launch_fast_one(const WgradParams &p, int grid, hipStream_t st
 hipError_t launch_wgrad_fast(const WgradParams &p, int bm, int bn, int grid, hipStream_t st)
 {
     if (p.posMajor && (p.N % kBK != 0 || p.OH * p.OW > 64)) return hipErrorInvalidValue;
+    const bool wide = p.OW > kBK;   // a multiple of 32 (host guarantees), row-major order only
+    if (wide && (p.posMajor || p.OW % kBK != 0)) return hipErrorInvalidValue;
 #define MI355CONV_WF(BM_, BN_)                                                        \
-    if (bm == BM_ && bn == BN_)                                                       \
+    if (bm == BM_ && bn == BN_) {                                                     \
+        if (wide) return launch_fast_one<BM_, BN_, false, true>(p, grid, st);         \
         return p.posMajor ? launch_fast_one<BM_, BN_, true>(p, grid, st)              \
-                          : launch_fast_one<BM_, BN_, false>(p, grid, st);
+                          : launch_fast_one<BM_, BN_, false>(p, grid, st);            \
+    }
     MI355CONV_WF(128, 128)
     MI355CONV_WF(64, 128)
     MI355CONV_WF(64, 64)

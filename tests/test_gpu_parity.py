@@ -135,6 +135,25 @@ def test_bwd_weight_small_ic(shp, split):
     gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), ops=("bwd_weight",), label=str(shp))
 
 
+# output rows of 64, 96, 128 pixels: the fast backward-weight kernel's wide-row variant
+WIDE_ROW_SHAPES = [
+    (1, 4, 64, 8, 32, 3, 3, 1, 1),
+    (2, 6, 96, 4, 16, 3, 3, 1, 1),
+    (1, 8, 128, 8, 8, 3, 3, 2, 1),
+    (1, 3, 64, 12, 64, 5, 5, 1, 2),
+    (2, 2, 64, 16, 32, 1, 1, 1, 0),
+]
+
+
+@pytest.mark.parametrize("split", [0, 1, 3])
+@pytest.mark.parametrize("shp", WIDE_ROW_SHAPES)
+def test_bwd_weight_wide_rows(shp, split):
+    say("wide rows %s split=%d" % (shp, split))
+    d = mc.make_desc(*shp)
+    mc.conv2d_set_tuning(mc.VARIANT_MFMA, split)
+    gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), ops=("bwd_weight",), label=str(shp))
+
+
 # backward-weight with at most 32 output channels on aligned maps: the 32x128 tile (one block row)
 NARROW_OC_SHAPES = [
     (4, 8, 8, 16, 32, 3, 3, 1, 1),
