@@ -83,6 +83,13 @@ size_t conv2d_workspace_bytes(int op, const conv2d_desc *d);
 /* Fill *info with the plan the entry point would run.  Host only; no HIP call. */
 int conv2d_query_plan(int op, const conv2d_desc *d, conv2d_plan_info *info);
 
+/* Where the plan would send hardware workgroup id `workgroup` (0 <= workgroup < grid): its
+ * rank in the order "longest work first" and the relative length of that work item (taps or
+ * live positions; 1 for plans whose workgroups are all alike).  While a launch is resident,
+ * workgroup ids 256 apart share a CU; the library deals unequal work items to the CUs through
+ * this mapping (paper Sec. IV: the small-feature-map operators).  Host only; for tests. */
+int conv2d_query_workgroup(int op, const conv2d_desc *d, int workgroup, int *rank, int *work);
+
 /* Process-wide override for tests and sweeps: variant = MI355CONV_VARIANT_AUTO or a
  * variant code, split = 0 (auto) or a forced slice count >= 1 (clamped to what the shape
  * allows).  Not thread-safe against concurrent operator calls. */

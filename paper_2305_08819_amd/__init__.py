@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_PKG, "libmi355conv.so")
 OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT = 0, 1, 2
 VARIANT_AUTO, VARIANT_DIRECT, VARIANT_MFMA = -1, 0, 1
 
-EXPORTS = ("conv2d_workspace_bytes", "conv2d_query_plan", "conv2d_set_tuning", "conv2d_set_tile", "conv2d_fwd",
+EXPORTS = ("conv2d_workspace_bytes", "conv2d_query_plan", "conv2d_query_workgroup", "conv2d_set_tuning", "conv2d_set_tile", "conv2d_fwd",
            "conv2d_fwd_bias_act",
            "conv2d_bwd_data", "deconv2d", "conv2d_bwd_weight", "conv2d_status_string",
            "conv2d_last_hip_error")
@@ -67,6 +67,9 @@ def load() -> ctypes.CDLL:
         lib.conv2d_workspace_bytes.restype = ctypes.c_size_t
         lib.conv2d_query_plan.argtypes = [ctypes.c_int, dp, ctypes.POINTER(PlanInfo)]
         lib.conv2d_query_plan.restype = ctypes.c_int
+        lib.conv2d_query_workgroup.argtypes = [ctypes.c_int, dp, ctypes.c_int, ctypes.POINTER(ctypes.c_int),
+                                               ctypes.POINTER(ctypes.c_int)]
+        lib.conv2d_query_workgroup.restype = ctypes.c_int
         lib.conv2d_set_tuning.argtypes = [ctypes.c_int, ctypes.c_int]
         lib.conv2d_set_tuning.restype = ctypes.c_int
         lib.conv2d_set_tile.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
@@ -107,6 +110,15 @@ def conv2d_query_plan(op: int, desc: ConvDesc) -> PlanInfo:
     if rc != 0:
         raise Mi355ConvError(rc, "conv2d_query_plan")
     return info
+
+
+def conv2d_query_workgroup(op: int, desc: ConvDesc, workgroup: int):
+    """(rank, work) of hardware workgroup id `workgroup` under the plan's longest-first dealing."""
+    rank, work = ctypes.c_int(0), ctypes.c_int(0)
+    rc = load().conv2d_query_workgroup(op, ctypes.byref(desc), workgroup, ctypes.byref(rank), ctypes.byref(work))
+    if rc != 0:
+        raise Mi355ConvError(rc, "conv2d_query_workgroup")
+    return rank.value, work.value
 
 
 def conv2d_set_tuning(variant: int = VARIANT_AUTO, split: int = 0) -> None:

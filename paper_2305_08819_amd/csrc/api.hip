@@ -47,6 +47,7 @@ struct Plan {
     int itemsPerClassUnit = 0;   // workgroups per position (gather) / per tap (backward-weight)
     BalanceRuns runs = {};
     unsigned char order[256] = {};   // rank -> position (gather) or tap (backward-weight)
+    unsigned char unitWork[256] = {}; // length of unit u (taps / live positions), by rank
 };
 
 int out_extent(int in, int pad, int f, int stride)
@@ -769,6 +770,7 @@ void plan_balance_gather(const Shape &s, Plan &pl, bool bwd)
     for (int i = 0; i < nPos; ++i) {
         pl.order[i] = (unsigned char)order[i];
         work[i] = taps[order[i]];
+        pl.unitWork[i] = (unsigned char)(work[i] < 255 ? work[i] : 255);
     }
     pl.itemsPerClassUnit = (s.N / pl.bm) * pl.tilesN * pl.split;
     const int resident = pl.bm * pl.bn <= 64 * 64 ? 4 : 2;
@@ -803,6 +805,7 @@ void plan_balance_wgrad(const Shape &s, Plan &pl)
     for (int i = 0; i < nTaps; ++i) {
         pl.order[i] = (unsigned char)order[i];
         work[i] = live[order[i]];
+        pl.unitWork[i] = (unsigned char)(work[i] < 255 ? work[i] : 255);
     }
     pl.itemsPerClassUnit = (s.IC / pl.bn) * pl.tilesM * pl.split;
     const int resident = pl.bm * pl.bn <= 64 * 64 ? 4 : pl.bm * pl.bn >= 128 * 128 ? 1 : 2;
@@ -950,6 +953,30 @@ int conv2d_query_plan(int op, const conv2d_desc *d, conv2d_plan_info *info)
     info->pos_major = pl.posMajor;
     info->grid = pl.grid;
     info->workspace_bytes = pl.wsBytes;
+    return MI355CONV_OK;
+}
+
+int conv2d_query_workgroup(int op, const conv2d_desc *d, int workgroup, int *rank, int *work)
+{
+    if (!rank || !work) return MI355CONV_ERR_NULL_PTR;
+    Shape s;
+    Plan pl;
+    int rc = check_desc(d, &s);
+    if (rc != MI355CONV_OK) return rc;
+    rc = make_plan(op, s, &pl);
+    if (rc != MI355CONV_OK) return rc;
+    if (workgroup < 0 || workgroup >= pl.grid) return MI355CONV_ERR_BAD_DIM;
+    *rank = workgroup;
+    *work = 1;
+    if (!pl.balance) return MI355CONV_OK;
+    if (pl.runs.n) {   // the same lookup as the kernels' balanced_rank()
+        const int slot = balance_slot(workgroup, pl.grid);
+        int r = 0;
+        for (int i = 1; i < pl.runs.n; ++i)
+            if (slot >= pl.runs.idStart[i]) r = i;
+        *rank = pl.runs.rankStart[r] + (slot - pl.runs.idStart[r]);
+    }
+    *work = pl.unitWork[*rank / pl.itemsPerClassUnit];
     return MI355CONV_OK;
 }
 

@@ -103,3 +103,30 @@ def test_plans(lib):
         mc.conv2d_set_tuning(mc.VARIANT_AUTO, 0)
     with pytest.raises(mc.Mi355ConvError):
         mc.conv2d_set_tuning(5, 0)
+
+
+def test_longest_first_dealing_is_a_permutation_and_balances(lib):
+    """Small maps in (y,x,n) order have workgroups of unequal length; the host deals them to the 256 CUs
+    (hardware ids 256 apart share a CU while the grid is resident).  Every id must map to a distinct
+    rank, and the busiest CU must stay close to the mean - for grids that are and are not multiples of 256."""
+    cases = [(mc.OP_FWD, mc.make_desc(128, 4, 4, 512, 512, 3, 3, 1, 1)),         # 1024 workgroups, taps 9/6/4
+             (mc.OP_BWD_DATA, mc.make_desc(128, 4, 4, 256, 512, 3, 3, 1, 1)),
+             (mc.OP_BWD_WEIGHT, mc.make_desc(128, 4, 4, 512, 512, 3, 3, 1, 1)),  # 576: 64 CUs hold three
+             (mc.OP_BWD_WEIGHT, mc.make_desc(128, 4, 4, 256, 512, 3, 3, 1, 1)),  # 288
+             (mc.OP_FWD, mc.make_desc(128, 8, 8, 256, 256, 3, 3, 1, 1))]
+    for op, d in cases:
+        pl = mc.conv2d_query_plan(op, d)
+        assert pl.pos_major == 1 and pl.grid > 256
+        seen, load = set(), [0] * 256
+        for wg in range(pl.grid):
+            rank, work = mc.conv2d_query_workgroup(op, d, wg)
+            assert 0 <= rank < pl.grid and rank not in seen
+            seen.add(rank)
+            load[wg % 256] += work
+        mean = sum(load) / 256.0
+        assert max(load) <= 1.5 * mean if pl.grid < 512 else max(load) <= 1.1 * mean, (op, pl.grid, max(load), mean)
+    # all workgroups alike: identity
+    d = mc.make_desc(128, 16, 16, 256, 64, 1, 1, 1, 0)
+    assert mc.conv2d_query_workgroup(mc.OP_FWD, d, 5) == (5, 1)
+    with pytest.raises(mc.Mi355ConvError):
+        mc.conv2d_query_workgroup(mc.OP_FWD, d, 1 << 20)
