@@ -275,6 +275,19 @@ Plan plan_fwd(const Shape &s)
     if (forced == MI355CONV_VARIANT_DIRECT || !fits) return pl;
     pl.variant = MI355CONV_VARIANT_MFMA;
     const long long M = (long long)s.N * s.OH * s.OW;
+    int ftm = 0, ftn = 0;
+    if (s.FH * s.FW * s.IC <= 32 && (s.IC % 4 != 0 || s.IC <= 4) && g_forceSplit.load() == 0 &&
+        !forced_tile(&ftm, &ftn, true) && (long long)s.N * s.IH * s.IW * s.IC * 4 < (1LL << 31) &&
+        pl.outElems * 4 < (1LL << 31)) {
+        // very few input channels (first layer): the whole reduction is one MFMA stage
+        pl.smallIc = 1;
+        pl.bm = 128;
+        pl.bn = 64;
+        pl.tilesM = ceil_div(M, 128);
+        pl.tilesN = ceil_div(s.OC, 64);
+        finish_plan(pl, 1);
+        return pl;
+    }
     if (!chunked) {   // element-wise loader: flat reduction range, no tap skipping
         pl.elem = 1;
         const double stages = (double)ceil_div((long long)s.FH * s.FW * s.IC, kBK);
@@ -1015,6 +1028,24 @@ static int fwd_impl(const float *X, const float *W, float *Y, const conv2d_desc 
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (pl.variant == MI355CONV_VARIANT_DIRECT) {
         hipError_t e = launch_direct_fwd(X, W, Y, s, st);
+        if (e == hipSuccess && epi.on)
+            e = launch_bias_act(Y, (long long)s.N * s.OH * s.OW * s.OC, epi.bias, epi.slope, s.OC, st);
+        return e == hipSuccess ? MI355CONV_OK : hip_fail(e);
+    }
+    if (pl.smallIc) {
+        SmallIcParams q;
+        memset(&q, 0, sizeof q);
+        q.X = X; q.W = W; q.dX = Y;
+        q.xBytes = (unsigned)((long long)s.N * s.IH * s.IW * s.IC * 4);
+        q.wBytes = (unsigned)((long long)s.OC * s.FH * s.FW * s.IC * 4);
+        q.N = s.N; q.IH = s.IH; q.IW = s.IW; q.IC = s.IC; q.OC = s.OC; q.OH = s.OH; q.OW = s.OW;
+        q.FH = s.FH; q.FW = s.FW; q.ph = s.ph; q.pw = s.pw; q.sh = s.sh; q.sw = s.sw;
+        q.M = s.N * s.OH * s.OW;
+        q.divOHOW = make_fastdiv((unsigned)(s.OH * s.OW));
+        q.divOW = make_fastdiv((unsigned)s.OW);
+        q.divIC = make_fastdiv((unsigned)s.IC);
+        q.divFW = make_fastdiv((unsigned)s.FW);
+        hipError_t e = launch_fwd_small_ic(q, st);
         if (e == hipSuccess && epi.on)
             e = launch_bias_act(Y, (long long)s.N * s.OH * s.OW * s.OC, epi.bias, epi.slope, s.OC, st);
         return e == hipSuccess ? MI355CONV_OK : hip_fail(e);

@@ -225,7 +225,7 @@ __device__ __forceinline__ WgradView wgrad_view(const WgradParams &p)
 struct SmallIcParams {
     const float *G;       // dY [N, OH, OW, OC]
     const float *W;       // [OC, FH, FW, IC]
-    float *dX;            // [N, IH, IW, IC]
+    float *dX;            // [N, IH, IW, IC]; the forward kernel writes Y [N, OH, OW, OC] through it
     unsigned gBytes, wBytes;
     int N, IH, IW, IC, OC, OH, OW, FH, FW, ph, pw;
     // backward-weight only
@@ -303,5 +303,7 @@ hipError_t launch_wgrad_fast(const WgradParams &p, int bm, int bn, int grid, hip
 hipError_t launch_bwd_data_small_ic(const SmallIcParams &p, hipStream_t st);
 // FH*FW*IC <= 32, any stride; grid = ceil(OC / 64) * split
 hipError_t launch_wgrad_small_ic(const SmallIcParams &p, hipStream_t st);
+// FH*FW*IC <= 32, any stride, any OC; X, W, dX (= Y), M, strides, divisors set
+hipError_t launch_fwd_small_ic(const SmallIcParams &p, hipStream_t st);
 
 }  // namespace mi355conv

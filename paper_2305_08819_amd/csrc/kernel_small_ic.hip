@@ -172,6 +172,105 @@ hipError_t launch_bwd_data_small_ic(const SmallIcParams &p, hipStream_t st)
     return hipGetLastError();
 }
 
+// ---- forward for very few input channels -------------------------------------------------------
+// Y[m, oc] = sum_k patch[m, k] * W[oc, k] with k = (fh,fw,ic) and at most 32 patch columns: the
+// whole reduction is one MFMA stage.  A workgroup gathers the patch rows of 128 output pixels
+// element by element (a thread owns one row; the tap of column k is uniform, so its address
+// part is a scalar), 64 filter rows, multiplies once and stores.  Bound by writing Y.
+__global__ __launch_bounds__(kThreads, 2) void fwd_small_ic_kernel(const SmallIcParams p)
+{
+    constexpr int BMf = 128, BNf = 64, LDf = 33;      // odd pitch: both the stores (lane = row) and the
+                                                      // fragment reads (lane = row, 4 bytes) spread over banks
+    __shared__ float As[BMf * LDf];
+    __shared__ float Bs[BNf * LDf];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int tilesN = (p.OC + BNf - 1) / BNf;
+    const int tn = blockIdx.x % tilesN, tm = blockIdx.x / tilesN;
+    const int m0 = tm * BMf, oc0 = tn * BNf;
+    const int Kp = p.FH * p.FW * p.IC, ohow = p.OH * p.OW;
+
+    constexpr int kOutOfRange = (int)0x80000000;
+    const __amdgpu_buffer_rsrc_t rsrcX =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.X), 0, (int)p.xBytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcW =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.W), 0, (int)p.wBytes, 0x00020000);
+
+    // filter tile: Bs[oc][k], 64 x 32 elements, 8 per thread (k fastest: coalesced rows of W)
+    float wv[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int idx = tid + kThreads * i;
+        const int oc = idx >> 5, k = idx & 31;
+        const int off = (k < Kp && oc0 + oc < p.OC) ? ((oc0 + oc) * Kp + k) * 4 : kOutOfRange;
+        wv[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrcW, off, 0, 0));
+    }
+    // patch tile: thread owns row (tid & 127) and the columns of one half (16 each)
+    const int row = tid & (BMf - 1), khalf = tid >> 7;
+    const int m = m0 + row;
+    const int n = (int)fast_div((unsigned)m, p.divOHOW);
+    const int r = m - n * ohow;
+    const int oh = (int)fast_div((unsigned)r, p.divOW), ow = r - oh * p.OW;
+    const int ihBase = oh * p.sh - p.ph, iwBase = ow * p.sw - p.pw;
+    const int pixBase = ((n * p.IH + ihBase) * p.IW + iwBase) * p.IC * 4;   // bytes; may be negative
+    float xv[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int k = khalf * 16 + i;                                     // uniform per instruction
+        const int tap = (int)fast_div((unsigned)k, p.divIC), ic = k - tap * p.IC;
+        const int fh = (int)fast_div((unsigned)tap, p.divFW), fw = tap - fh * p.FW;
+        const bool ok = k < Kp && m < p.M && (unsigned)(ihBase + fh) < (unsigned)p.IH &&
+                        (unsigned)(iwBase + fw) < (unsigned)p.IW;
+        const int off = ok ? pixBase + ((fh * p.IW + fw) * p.IC + ic) * 4 : kOutOfRange;
+        xv[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrcX, off, 0, 0));
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int idx = tid + kThreads * i;
+        Bs[(idx >> 5) * LDf + (idx & 31)] = wv[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) As[row * LDf + khalf * 16 + i] = xv[i];
+    __syncthreads();
+
+    // wave w: rows 32w .. 32w+31, all 64 columns
+    float16v acc[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[j][q] = 0.f;
+    const float *a = As + (wave * 32 + l32) * LDf + lh;
+    const float *b = Bs + l32 * LDf + lh;
+#pragma unroll
+    for (int step = 0; step < 16; ++step) {
+        const float fa = a[2 * step];
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa, b[j * 32 * LDf + 2 * step], acc[j], 0, 0, 0);
+    }
+    // accumulator register q of lane l is row 8*(q/4)+4*(l/32)+q%4, column l%32
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int col = oc0 + j * 32 + l32;
+        if (col < p.OC) {
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int mm = m0 + wave * 32 + 8 * (q / 4) + 4 * lh + (q % 4);
+                if (mm < p.M) p.dX[(long long)mm * p.OC + col] = acc[j][q];
+            }
+        }
+    }
+}
+
+hipError_t launch_fwd_small_ic(const SmallIcParams &p, hipStream_t st)
+{
+    if (p.FH * p.FW * p.IC > 32) return hipErrorInvalidValue;
+    const int grid = ((p.M + 127) / 128) * ((p.OC + 63) / 64);
+    hipLaunchKernelGGL(fwd_small_ic_kernel, dim3((unsigned)grid), dim3(kThreads), 0, st, p);
+    return hipGetLastError();
+}
+
 // ---- backward-weight for very few input channels ----------------------------------------------
 // dW[oc, (fh,fw,ic)] = sum_m dY[m, oc] * patch[m, (fh,fw,ic)] with at most 32 columns: one 64 x 32
 // output tile per 64 output channels, the rows m = (n, oh, ow) cut into `split` slices.  The

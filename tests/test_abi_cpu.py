@@ -81,8 +81,16 @@ def test_workspace_errors(lib):
 
 def test_plans(lib):
     q = mc.conv2d_query_plan
-    # 3 input channels: element-wise MFMA variant; odd output channels: backward-weight goes direct
+    # 3 input channels: first-layer kernels (one MFMA stage, 128 x 64 tile forward; 4 x 32 pixels per
+    # workgroup backward-data; 64 x 32 backward-weight); odd output channels: backward-weight goes direct
     p = q(mc.OP_FWD, mc.make_desc(4, 8, 8, 3, 16, 3, 3, 1, 1))
+    assert p.variant == mc.VARIANT_MFMA and (p.tile_m, p.tile_n, p.split) == (128, 64, 1) and p.grid == 2
+    p = q(mc.OP_BWD_DATA, mc.make_desc(128, 32, 32, 3, 64, 3, 3, 1, 1))
+    assert p.variant == mc.VARIANT_MFMA and p.grid == 128 * 8 and p.workspace_bytes == 0
+    p = q(mc.OP_BWD_WEIGHT, mc.make_desc(128, 32, 32, 3, 64, 3, 3, 1, 1))
+    assert (p.tile_m, p.tile_n) == (64, 32) and p.split > 1
+    # 5 input channels with a 3x3 filter (45 patch columns): element-wise loaders
+    p = q(mc.OP_FWD, mc.make_desc(4, 8, 8, 5, 16, 3, 3, 1, 1))
     assert p.variant == mc.VARIANT_MFMA and p.tile_n == 32
     p = q(mc.OP_BWD_WEIGHT, mc.make_desc(4, 8, 8, 3, 15, 3, 3, 1, 1))
     assert p.variant == mc.VARIANT_DIRECT and p.workspace_bytes == 0
