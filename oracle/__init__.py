@@ -12,7 +12,9 @@ scatter/pad-and-slice second forms, adjoint identity, exact finite
 differences, a library cross-check); ``conv2d_fwd_bias_act`` adds the bias add
 and leaky-ReLU of the paper's layer constructors on top of ``conv2d_fwd`` in
 plain numpy fp64 and is pinned by hand-computed values and its special cases
-(slope 1, slope 0, zero bias).
+(slope 1, slope 0, zero bias); ``conv2d_fwd_u8`` converts 8-bit pixels to
+fp32 (byte * scale, rounded once to fp32) before ``conv2d_fwd`` and is pinned
+by hand values, the scale-1 case and its linearity in the scale.
 """
 from __future__ import annotations
 
@@ -149,3 +151,14 @@ def conv2d_fwd_bias_act(X, W, bias=None, negative_slope=1.0, stride=1, pad=0):
         assert b.shape == (y.shape[3],)
         y = y + b[None, None, None, :]
     return np.where(y > 0.0, y, y * float(negative_slope))
+
+
+def conv2d_fwd_u8(X8, scale, W, stride=1, pad=0):
+    """Forward convolution of 8-bit pixels: x = fp32(byte) * fp32(scale), rounded once to fp32 (the
+    paper converts pixel bytes to floats on the device, Sec. III; Table I: pixels / 255), then
+    ``conv2d_fwd``.  The conversion is part of the operator, so it is done in the precision the
+    operator is defined in (fp32); the sums are fp64 as everywhere in this oracle."""
+    x8 = np.ascontiguousarray(X8)
+    assert x8.dtype == np.uint8 and x8.ndim == 4
+    x = x8.astype(np.float32) * np.float32(scale)
+    return conv2d_fwd(x, W, stride, pad)

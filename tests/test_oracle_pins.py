@@ -295,3 +295,23 @@ def test_bias_act_special_cases():
     b2 = np.zeros(4, dtype=np.float32); b2[2] = 7.0
     d = oracle.conv2d_fwd_bias_act(X, W, b2, 1.0, (1, 2), (1, 0)) - plain
     assert np.allclose(d[..., 2], 7.0, rtol=0, atol=1e-12) and not d[..., [0, 1, 3]].any()
+
+
+# ---- forward from 8-bit pixels -------------------------------------------------------------------
+def test_fwd_u8_hand_values_and_scale():
+    X8 = np.array([[0, 255], [128, 3]], dtype=np.uint8).reshape(1, 2, 2, 1)
+    W = np.array([2.0], dtype=np.float32).reshape(1, 1, 1, 1)
+    y = oracle.conv2d_fwd_u8(X8, 0.5, W)                      # exact: bytes * 0.5 * 2
+    assert np.array_equal(y.reshape(2, 2), np.array([[0.0, 255.0], [128.0, 3.0]]))
+    rng = np.random.default_rng(11)
+    X8 = rng.integers(0, 256, size=(2, 6, 5, 3), dtype=np.uint8)
+    W = rng.standard_normal((4, 3, 3, 3)).astype(np.float32)
+    # scale 1: the plain operator on the bytes as floats
+    assert np.array_equal(oracle.conv2d_fwd_u8(X8, 1.0, W, 1, 1), oracle.conv2d_fwd(X8.astype(np.float32), W, 1, 1))
+    # a power-of-two scale commutes with every rounding: exact linearity
+    assert np.array_equal(oracle.conv2d_fwd_u8(X8, 0.25, W, 2, 1), 0.25 * oracle.conv2d_fwd_u8(X8, 1.0, W, 2, 1))
+    # 1/255: each pixel is the fp32 product byte * fp32(1/255), not a double-precision quotient
+    y = oracle.conv2d_fwd_u8(X8, 1.0 / 255.0, W, 1, 1)
+    x32 = (X8.astype(np.float32) * np.float32(1.0 / 255.0))
+    assert x32.dtype == np.float32 and np.array_equal(y, oracle.conv2d_fwd(x32, W, 1, 1))
+    assert np.abs(y - oracle.conv2d_fwd(X8.astype(np.float64).astype(np.float32), W, 1, 1) / 255.0).max() < 1e-5
