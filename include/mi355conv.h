@@ -118,6 +118,14 @@ int conv2d_fwd_bias_act(const float *X, const float *W, const float *bias, float
                         const conv2d_desc *d, float negative_slope, void *ws, size_t ws_bytes,
                         void *stream);
 
+/* First-layer forward from 8-bit pixels: X8 holds unsigned bytes [N,IH,IW,IC] (device); every
+ * pixel is converted on load, x = (float)byte * scale (the paper converts pixel bytes to floats
+ * on the device, Sec. III; Table I scales by 1/255), then as conv2d_fwd.  X8 needs no alignment.
+ * Only shapes the first-layer kernel takes (FH*FW*IC <= 32, and IC <= 4 or not a multiple of 4),
+ * under automatic tuning; MI355CONV_ERR_UNSUPPORTED otherwise.  No workspace. */
+int conv2d_fwd_u8(const unsigned char *X8, float scale, const float *W, float *Y,
+                  const conv2d_desc *d, void *stream);
+
 /* Backward-data = deconvolution (Sec. IV: the deconv operator for small feature maps):
  *   dX[n,ih,iw,ic] = sum over (oc,fh,fw) with oh*sh-ph+fh == ih, ow*sw-pw+fw == iw of
  *                    dY[n,oh,ow,oc] * W[oc,fh,fw,ic].

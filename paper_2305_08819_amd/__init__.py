@@ -17,7 +17,7 @@ OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT = 0, 1, 2
 VARIANT_AUTO, VARIANT_DIRECT, VARIANT_MFMA = -1, 0, 1
 
 EXPORTS = ("conv2d_workspace_bytes", "conv2d_query_plan", "conv2d_query_workgroup", "conv2d_set_tuning", "conv2d_set_tile", "conv2d_fwd",
-           "conv2d_fwd_bias_act",
+           "conv2d_fwd_bias_act", "conv2d_fwd_u8",
            "conv2d_bwd_data", "deconv2d", "conv2d_bwd_weight", "conv2d_status_string",
            "conv2d_last_hip_error")
 
@@ -80,6 +80,8 @@ def load() -> ctypes.CDLL:
             fn.restype = ctypes.c_int
         lib.conv2d_fwd_bias_act.argtypes = [vp, vp, vp, vp, dp, ctypes.c_float, vp, ctypes.c_size_t, vp]
         lib.conv2d_fwd_bias_act.restype = ctypes.c_int
+        lib.conv2d_fwd_u8.argtypes = [vp, ctypes.c_float, vp, vp, dp, vp]
+        lib.conv2d_fwd_u8.restype = ctypes.c_int
         lib.conv2d_status_string.argtypes = [ctypes.c_int]
         lib.conv2d_status_string.restype = ctypes.c_char_p
         lib.conv2d_last_hip_error.argtypes = []
@@ -190,6 +192,22 @@ def conv2d_fwd_bias_act(X, W, bias, Y, desc: ConvDesc, negative_slope=1.0, ws=No
                                  ctypes.c_float(negative_slope), _ptr(ws), nbytes, _stream_handle(stream))
     if rc != 0:
         raise Mi355ConvError(rc, "conv2d_fwd_bias_act")
+    return Y
+
+
+def conv2d_fwd_u8(X8, scale, W, Y, desc: ConvDesc, stream=None):
+    """Y <- conv(float(X8) * scale, W) for uint8 pixels X8[N,IH,IW,IC]; first-layer shapes only."""
+    import torch
+    if not (X8.is_cuda and X8.dtype == torch.uint8 and X8.is_contiguous()):
+        raise ValueError("X8 must be a contiguous uint8 CUDA tensor")
+    if tuple(X8.shape) != (desc.N, desc.IH, desc.IW, desc.IC):
+        raise ValueError("X8 has shape %s" % (tuple(X8.shape),))
+    _check(W, (desc.OC, desc.FH, desc.FW, desc.IC), "W")
+    _check(Y, (desc.N, desc.OH, desc.OW, desc.OC), "Y")
+    rc = load().conv2d_fwd_u8(_ptr(X8), ctypes.c_float(scale), _ptr(W), _ptr(Y), ctypes.byref(desc),
+                              _stream_handle(stream))
+    if rc != 0:
+        raise Mi355ConvError(rc, "conv2d_fwd_u8")
     return Y
 
 

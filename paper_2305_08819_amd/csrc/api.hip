@@ -1015,7 +1015,7 @@ int conv2d_set_tile(int tile_m, int tile_n, int pos_major)
 }
 
 static int fwd_impl(const float *X, const float *W, float *Y, const conv2d_desc *d, void *ws, size_t ws_bytes,
-                    void *stream, const Epilogue &epi)
+                    void *stream, const Epilogue &epi, const unsigned char *X8 = nullptr, float scale = 1.f)
 {
     Shape s;
     Plan pl;
@@ -1023,8 +1023,14 @@ static int fwd_impl(const float *X, const float *W, float *Y, const conv2d_desc 
     if (rc != MI355CONV_OK) return rc;
     rc = make_plan(MI355CONV_OP_FWD, s, &pl);
     if (rc != MI355CONV_OK) return rc;
-    rc = check_buffers(X, W, Y, pl, ws, ws_bytes);
-    if (rc != MI355CONV_OK) return rc;
+    if (X8) {   // bytes: only the first-layer kernel converts on load
+        if (!W || !Y) return MI355CONV_ERR_NULL_PTR;
+        if ((reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(Y)) & 15u) return MI355CONV_ERR_ALIGNMENT;
+        if (!pl.smallIc) return MI355CONV_ERR_UNSUPPORTED;
+    } else {
+        rc = check_buffers(X, W, Y, pl, ws, ws_bytes);
+        if (rc != MI355CONV_OK) return rc;
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (pl.variant == MI355CONV_VARIANT_DIRECT) {
         hipError_t e = launch_direct_fwd(X, W, Y, s, st);
@@ -1035,8 +1041,11 @@ static int fwd_impl(const float *X, const float *W, float *Y, const conv2d_desc 
     if (pl.smallIc) {
         SmallIcParams q;
         memset(&q, 0, sizeof q);
-        q.X = X; q.W = W; q.dX = Y;
-        q.xBytes = (unsigned)((long long)s.N * s.IH * s.IW * s.IC * 4);
+        q.X = X8 ? reinterpret_cast<const float *>(X8) : X;
+        q.W = W; q.dX = Y;
+        q.u8 = X8 ? 1 : 0;
+        q.scale = scale;
+        q.xBytes = (unsigned)((long long)s.N * s.IH * s.IW * s.IC * (X8 ? 1 : 4));
         q.wBytes = (unsigned)((long long)s.OC * s.FH * s.FW * s.IC * 4);
         q.N = s.N; q.IH = s.IH; q.IW = s.IW; q.IC = s.IC; q.OC = s.OC; q.OH = s.OH; q.OW = s.OW;
         q.FH = s.FH; q.FW = s.FW; q.ph = s.ph; q.pw = s.pw; q.sh = s.sh; q.sw = s.sw;
@@ -1057,6 +1066,13 @@ int conv2d_fwd(const float *X, const float *W, float *Y, const conv2d_desc *d, v
                void *stream)
 {
     return fwd_impl(X, W, Y, d, ws, ws_bytes, stream, Epilogue());
+}
+
+int conv2d_fwd_u8(const unsigned char *X8, float scale, const float *W, float *Y, const conv2d_desc *d, void *stream)
+{
+    if (!X8) return MI355CONV_ERR_NULL_PTR;
+    if (!(scale == scale)) return MI355CONV_ERR_UNSUPPORTED;   // NaN
+    return fwd_impl(nullptr, W, Y, d, nullptr, 0, stream, Epilogue(), X8, scale);
 }
 
 int conv2d_fwd_bias_act(const float *X, const float *W, const float *bias, float *Y, const conv2d_desc *d,

@@ -235,6 +235,9 @@ struct SmallIcParams {
     int sh, sw, split, M;
     long long sliceStride;
     FastDiv divOHOW, divOW, divIC, divFW;
+    // forward only: X holds unsigned bytes, converted on load as (float)byte * scale
+    int u8;
+    float scale;
 };
 
 // MI355X spreads consecutive workgroup ids round-robin over its 8 XCDs, each with its own

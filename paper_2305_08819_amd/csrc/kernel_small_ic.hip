@@ -177,6 +177,8 @@ hipError_t launch_bwd_data_small_ic(const SmallIcParams &p, hipStream_t st)
 // whole reduction is one MFMA stage.  A workgroup gathers the patch rows of 128 output pixels
 // element by element (a thread owns one row; the tap of column k is uniform, so its address
 // part is a scalar), 64 filter rows, multiplies once and stores.  Bound by writing Y.
+// U8: X holds unsigned bytes (pixels); each is converted on load, x = (float)byte * p.scale.
+template <bool U8>
 __global__ __launch_bounds__(kThreads, 2) void fwd_small_ic_kernel(const SmallIcParams p)
 {
     constexpr int BMf = 128, BNf = 64, LDf = 33;      // odd pitch: both the stores (lane = row) and the
@@ -213,7 +215,8 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_small_ic_kernel(const SmallIc
     const int r = m - n * ohow;
     const int oh = (int)fast_div((unsigned)r, p.divOW), ow = r - oh * p.OW;
     const int ihBase = oh * p.sh - p.ph, iwBase = ow * p.sw - p.pw;
-    const int pixBase = ((n * p.IH + ihBase) * p.IW + iwBase) * p.IC * 4;   // bytes; may be negative
+    constexpr int kElem = U8 ? 1 : 4;                                       // bytes per element of X
+    const int pixBase = ((n * p.IH + ihBase) * p.IW + iwBase) * p.IC * kElem;   // bytes; may be negative
     float xv[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -222,8 +225,9 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_small_ic_kernel(const SmallIc
         const int fh = (int)fast_div((unsigned)tap, p.divFW), fw = tap - fh * p.FW;
         const bool ok = k < Kp && m < p.M && (unsigned)(ihBase + fh) < (unsigned)p.IH &&
                         (unsigned)(iwBase + fw) < (unsigned)p.IW;
-        const int off = ok ? pixBase + ((fh * p.IW + fw) * p.IC + ic) * 4 : kOutOfRange;
-        xv[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrcX, off, 0, 0));
+        const int off = ok ? pixBase + ((fh * p.IW + fw) * p.IC + ic) * kElem : kOutOfRange;
+        if (U8) xv[i] = (float)__builtin_amdgcn_raw_buffer_load_b8(rsrcX, off, 0, 0) * p.scale;
+        else xv[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrcX, off, 0, 0));
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -267,7 +271,8 @@ hipError_t launch_fwd_small_ic(const SmallIcParams &p, hipStream_t st)
 {
     if (p.FH * p.FW * p.IC > 32) return hipErrorInvalidValue;
     const int grid = ((p.M + 127) / 128) * ((p.OC + 63) / 64);
-    hipLaunchKernelGGL(fwd_small_ic_kernel, dim3((unsigned)grid), dim3(kThreads), 0, st, p);
+    if (p.u8) hipLaunchKernelGGL(fwd_small_ic_kernel<true>, dim3((unsigned)grid), dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL(fwd_small_ic_kernel<false>, dim3((unsigned)grid), dim3(kThreads), 0, st, p);
     return hipGetLastError();
 }
 

@@ -70,6 +70,18 @@ def test_bias_act_argument_errors_before_any_hip_call(lib):
     assert call(256, 512, 1024, 768, bad) == -2
 
 
+def test_fwd_u8_argument_errors_before_any_hip_call(lib):
+    def call(x8, w, y, desc, scale=0.5):
+        return lib.conv2d_fwd_u8(ctypes.c_void_p(x8), ctypes.c_float(scale), ctypes.c_void_p(w), ctypes.c_void_p(y),
+                                 ctypes.byref(desc), None)
+    first = mc.make_desc(4, 8, 8, 3, 16, 3, 3, 1, 1)
+    assert call(0, 512, 768, first) == -1                       # null pixels
+    assert call(257, 512, 0, first) == -1                       # null output (odd pixel address is fine)
+    assert call(257, 516, 768, first) == -4                     # misaligned filter
+    assert call(257, 512, 768, first, float("nan")) == -5
+    assert call(256, 512, 768, mc.make_desc(4, 8, 8, 64, 16, 3, 3, 1, 1)) == -5   # not a first-layer shape
+
+
 def test_workspace_errors(lib):
     d = mc.make_desc(128, 2, 2, 512, 512, 3, 3, 1, 1)
     need = mc.conv2d_workspace_bytes(mc.OP_FWD, d)

@@ -265,6 +265,34 @@ def test_fwd_bias_act(shp, variant, split):
     assert np.array_equal(out.cpu().numpy(), gu.run_gpu("fwd", d, X, W))
 
 
+@pytest.mark.parametrize("shp", [(8, 32, 32, 3, 64, 3, 3, 1, 1), (3, 9, 11, 1, 20, 5, 5, 2, 2), (2, 7, 7, 3, 16, 3, 3, (2, 1), 1),
+                                 (5, 6, 6, 6, 8, 2, 2, 1, 0)])
+def test_fwd_u8_pixels(shp):
+    """First-layer forward from 8-bit pixels, converted on load with scale 1/255."""
+    say("u8 %s" % (shp,))
+    d = mc.make_desc(*shp)
+    k = wl.stream_key("u8", *shp[:5])
+    X8 = ((wl.uniform_pm1(k, (d.N, d.IH, d.IW, d.IC)).astype(np.float64) + 1.0) * 127.99).astype(np.uint8)
+    W = wl.uniform_pm1(k + 1, (d.OC, d.FH, d.FW, d.IC))
+    scale = 1.0 / 255.0
+    buf, out = gu.guarded((d.N, d.OH, d.OW, d.OC))
+    mc.conv2d_fwd_u8(torch.from_numpy(X8).cuda(), scale, torch.from_numpy(W).cuda(), out, d)
+    torch.cuda.synchronize()
+    assert gu.guards_intact(buf)
+    rel, mx = gu.errors(out.cpu().numpy(), gu.oracle.conv2d_fwd_u8(X8, scale, W, (d.sh, d.sw), (d.ph, d.pw)))
+    assert rel <= gu.REL_L2_TOL and mx <= gu.MAX_ABS_TOL, (rel, mx)
+    assert int(X8.max()) > 200 and int(X8.min()) < 50
+
+
+def test_fwd_u8_rejects_other_shapes():
+    d = mc.make_desc(2, 8, 8, 64, 64, 3, 3, 1, 1)
+    x8 = torch.zeros((2, 8, 8, 64), dtype=torch.uint8, device="cuda")
+    w = torch.zeros((64, 3, 3, 64), device="cuda")
+    y = torch.zeros((2, 8, 8, 64), device="cuda")
+    with pytest.raises(mc.Mi355ConvError):
+        mc.conv2d_fwd_u8(x8, 1.0, w, y, d)
+
+
 def test_fully_connected_as_1x1_convolution():
     """The paper's fully-connected layer (Fig. 2 `fullconnect`) is the 1x1 operator on a 1x1 map:
     a CIFAR classifier head, 512 features -> 10 classes, all three operators."""
