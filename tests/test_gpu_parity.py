@@ -302,6 +302,26 @@ def test_fully_connected_as_1x1_convolution():
     gu.check_all_ops(d, *small_inputs(d, 78), label="fc 512->512")
 
 
+@pytest.mark.parametrize("shp,split", [((128, 5, 3, 64, 256, 3, 3, 1, 1), 8), ((128, 3, 3, 64, 192, 3, 3, 1, 1), 5),
+                                       ((64, 6, 6, 32, 128, 5, 5, 1, 2), 4)])
+def test_balanced_dealing_odd_grids(shp, split):
+    """(y,x,n) row order with grids that are not multiples of 256 and maps that are not square: the
+    longest-first dealing (a permutation of the workgroups) must leave every result intact."""
+    say("balanced %s split=%d" % (shp, split))
+    d = mc.make_desc(*shp)
+    mc.conv2d_set_tuning(mc.VARIANT_MFMA, split)
+    mc.conv2d_set_tile(64, 64, 1)
+    grids = []
+    for op in (mc.OP_FWD, mc.OP_BWD_DATA, mc.OP_BWD_WEIGHT):
+        pl = mc.conv2d_query_plan(op, d)
+        assert pl.pos_major == 1
+        grids.append(pl.grid)
+        ranks = {mc.conv2d_query_workgroup(op, d, wg)[0] for wg in range(pl.grid)}
+        assert ranks == set(range(pl.grid))
+    assert max(grids) > 256
+    gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), label=str(shp))
+
+
 def test_concurrent_streams_inception_branches():
     """Independent operators enqueued on different streams at once (the paper's asynchronous APIs
     run branches of a network in parallel, Sec. III Layer-4 / Sec. IV): the 1x1, 3x3 and 5x5
