@@ -31,7 +31,7 @@ PEAK_HBM_GBS = 8000.0
 OPS = ("fwd", "bwd_data", "bwd_weight")
 # HBM bytes per operator launch of the default workload (C2), from FETCH_SIZE + WRITE_SIZE scaled by a
 # 256 MiB copy (profiles/bench_C2_kernel_trace.md); bwd_weight = main kernel + slice reduce.
-MEASURED_TRAFFIC_BYTES = {"C2": {"fwd": 56.3e6 + 16.8e6, "bwd_data": 40.8e6 + 33.6e6,
+MEASURED_TRAFFIC_BYTES = {"C2": {"fwd": 56.3e6 + 16.8e6, "bwd_data": 43.0e6 + 33.6e6,
                                  "bwd_weight": 84.4e6 + 8.3e6 + 8.3e6 + 0.3e6}}
 KERNEL_OF_OP = {"fwd": "gather_gemm_kernel<fwd>", "bwd_data": "gather_gemm_kernel<bwd_data>",
                 "bwd_weight": "wgrad_fast_kernel + slice_reduce_kernel"}
