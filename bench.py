@@ -296,7 +296,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (--gpus 1); the hot path has no "
-                 "multi-GPU part, see DESIGN.md for how it would shard")
+                 "multi-GPU part (it would shard by batch, with one all-reduce of dW per layer)")
 
     import torch
     import paper_2305_08819_amd as mc
