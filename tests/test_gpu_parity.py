@@ -377,6 +377,55 @@ def test_concurrent_streams_inception_branches():
         assert rel <= gu.REL_L2_TOL and mx <= gu.MAX_ABS_TOL, op
 
 
+def test_hip_graph_replay_matches_eager():
+    """The entry points only enqueue kernels (no allocation, no memset, no synchronisation), so a
+    sequence of operators can be captured into a HIP graph.  Every replay - with eager launches and
+    synchronisations in between - must reproduce the eager results bit for bit."""
+    descs = [mc.make_desc(64, 4, 4, 64, 128, 3, 3, 1, 1),      # sliced reductions + combine pass, (y,x,n) order
+             mc.make_desc(8, 16, 16, 32, 64, 3, 3, 2, 1),      # stride phases
+             mc.make_desc(16, 12, 12, 3, 32, 3, 3, 1, 1)]      # first-layer kernels
+    k = wl.stream_key("graph")
+    items = []
+    for i, d in enumerate(descs):
+        X = torch.from_numpy(wl.uniform_pm1(k + 3 * i, (d.N, d.IH, d.IW, d.IC))).cuda()
+        W = torch.from_numpy(wl.uniform_pm1(k + 3 * i + 1, (d.OC, d.FH, d.FW, d.IC))).cuda()
+        G = torch.from_numpy(wl.uniform_pm1(k + 3 * i + 2, (d.N, d.OH, d.OW, d.OC))).cuda()
+        outs = [torch.empty((d.N, d.OH, d.OW, d.OC), device="cuda"), torch.empty_like(X), torch.empty_like(W)]
+        wss = [torch.empty(max(mc.conv2d_workspace_bytes(op, d), 16), dtype=torch.uint8, device="cuda")
+               for op in (mc.OP_FWD, mc.OP_BWD_DATA, mc.OP_BWD_WEIGHT)]
+        items.append((d, X, W, G, outs, wss))
+
+    def enqueue():
+        for d, X, W, G, outs, wss in items:
+            mc.conv2d_fwd(X, W, outs[0], d, ws=wss[0])
+            mc.conv2d_bwd_data(G, W, outs[1], d, ws=wss[1])
+            mc.conv2d_bwd_weight(X, G, outs[2], d, ws=wss[2])
+
+    enqueue()
+    torch.cuda.synchronize()
+    eager = [[o.clone() for o in it[4]] for it in items]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        enqueue()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            enqueue()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for it in items:                       # poison, then eager work of the program in between
+            for o in it[4]:
+                o.fill_(float("nan"))
+        scratch = torch.randn(1 << 16, device="cuda").sum().item()
+        assert scratch == scratch
+        graph.replay()
+        torch.cuda.synchronize()
+        for it, ref in zip(items, eager):
+            for o, r in zip(it[4], ref):
+                assert torch.equal(o, r), rep
+
+
 FULL_LAYERS = [l for l in wl.all_layers()]
 
 
