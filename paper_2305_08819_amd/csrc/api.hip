@@ -578,7 +578,7 @@ Plan plan_bwd_weight(const Shape &s)
     pl.posMajor = posMajor;
     pl.tilesM = ceil_div(s.OC, pl.bm);
     pl.tilesN = ceil_div(Ktot, pl.bn);
-    pl.flushChunks = 16;   // 512-product chains
+    pl.flushChunks = M > 150000 ? 8 : 16;   // fp32 chains of at most 512 products (256 for very long reductions)
     finish_plan(pl, pl.split);
     return pl;
 }
