@@ -455,7 +455,19 @@ def test_hip_graph_replay_matches_eager():
                 assert torch.equal(o, r), rep
 
 
-FULL_LAYERS = [l for l in wl.all_layers()]
+def _distinct_shapes(layers):
+    seen, out = set(), []
+    for l in layers:
+        key = (l.N, l.IH, l.IW, l.IC, l.OC, l.FH, l.FW, l.stride, l.pad)
+        # the VGG-16 stack is kept whole: its inputs come from the chain through the oracle
+        if key in seen and l not in wl.CFG5:
+            continue
+        seen.add(key)
+        out.append(l)
+    return out
+
+
+FULL_LAYERS = _distinct_shapes(wl.all_layers())
 
 
 @pytest.mark.parametrize("layer", FULL_LAYERS, ids=[l.name for l in FULL_LAYERS])

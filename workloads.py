@@ -190,8 +190,23 @@ CFG7 = [Layer("L1", 8, 128, 128, 64, 64, 3, 3, 1, 1),
         Layer("L2", 4, 256, 256, 32, 32, 3, 3, 1, 1),
         Layer("L3", 8, 128, 128, 64, 128, 3, 3, 2, 1)]
 
+# The distinct convolutions of a CIFAR-style ResNet-18 (3x3 stem, four stages of basic blocks,
+# stride-2 3x3 and 1x1 shortcut convolutions between stages), batch 128: the other network family
+# the paper trains (Sec. IV, Table III).  Repeated layers appear once.
+CFG8 = [Layer("R1", 128, 32, 32, 3, 64, 3, 3, 1, 1),
+        Layer("R2", 128, 32, 32, 64, 64, 3, 3, 1, 1),
+        Layer("R3", 128, 32, 32, 64, 128, 3, 3, 2, 1),
+        Layer("R3s", 128, 32, 32, 64, 128, 1, 1, 2, 0),
+        Layer("R4", 128, 16, 16, 128, 128, 3, 3, 1, 1),
+        Layer("R5", 128, 16, 16, 128, 256, 3, 3, 2, 1),
+        Layer("R5s", 128, 16, 16, 128, 256, 1, 1, 2, 0),
+        Layer("R6", 128, 8, 8, 256, 256, 3, 3, 1, 1),
+        Layer("R7", 128, 8, 8, 256, 512, 3, 3, 2, 1),
+        Layer("R7s", 128, 8, 8, 256, 512, 1, 1, 2, 0),
+        Layer("R8", 128, 4, 4, 512, 512, 3, 3, 1, 1)]
+
 CONFIGS = {"cfg1": CFG1, "cfg2": CFG2, "cfg3": CFG3, "cfg4": CFG4, "cfg5": CFG5, "cfg6": CFG6,
-           "cfg7": CFG7}
+           "cfg7": CFG7, "cfg8": CFG8}
 
 
 def all_layers():
