@@ -112,7 +112,7 @@ struct CostParams {
     double reduceUs;       // launch + ramp of the slice-reduce kernel
     double reduceBytesPerUs;
 };
-constexpr CostParams kGatherCost = {0.85, 0.95, 1.0, 1.0, 0.10, 5.0, 0.5, 8.0e6};
+constexpr CostParams kGatherCost = {0.85, 0.95, 1.0, 1.0, 0.25, 4.0, 0.5, 8.0e6};
 constexpr CostParams kWgradCost = {0.80, 0.95, 1.05, 0.56, 0.20, 4.0, 10.0, 6.2e6};
 
 constexpr double kCuFlopPerUs = 157.3e6 / 256.0;   // fp32 MFMA FLOP per microsecond per CU
