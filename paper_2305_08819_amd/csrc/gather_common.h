@@ -162,34 +162,60 @@ __device__ __forceinline__ GatherTile gather_tile_setup(const P &p, int *rowBase
 }
 
 // Epilogue: rows of a 32x32 block are spread over accumulator registers, columns over lanes.
-// The 16 destination-pixel indices of a block are fetched with four 16-byte LDS reads; output
-// offsets fit 32 bits because every tensor holds fewer than 2^31 elements.
+// With `scratch` (32 x kLDT floats of LDS owned by the calling wave) and a destination whose
+// channel count is a multiple of 4, each block is turned in LDS so that a lane holds four
+// neighbouring columns of one row: four 16-byte stores per block, each covering eight 128-byte
+// row segments, instead of sixteen 4-byte stores covering two.  Otherwise the 16
+// destination-pixel indices of a block are fetched with four 16-byte LDS reads and every
+// accumulator register is stored on its own.  Output offsets fit 32 bits because every tensor
+// holds fewer than 2^31 elements.
+constexpr int kLDT = 36;   // pitch of the turning buffer: 16-byte aligned rows, bank-skewed
 template <class T, class P>
 __device__ __forceinline__ void gather_tile_store(const P &p, int slice, int n0, const int *outRow,
                                                   const float16v (&acc)[T::MB][T::NB], int wm, int wn, int l32,
-                                                  int lh)
+                                                  int lh, float *scratch = nullptr)
 {
     typedef int i4 __attribute__((ext_vector_type(4)));
     float *C = p.C + (long long)slice * p.sliceStride;
+    const bool epi = p.epilogue && p.split == 1;   // sliced launches leave it to the combine pass
+    const float slope = epi ? p.slope : 1.f;
+    const int lane = lh * 32 + l32;
 #pragma unroll
     for (int i = 0; i < T::MB; ++i) {
-        i4 orow[4];
-#pragma unroll
-        for (int g = 0; g < 4; ++g)
-            orow[g] = *reinterpret_cast<const i4 *>(outRow + wm * T::WTM + i * 32 + 8 * g + 4 * lh);
 #pragma unroll
         for (int j = 0; j < T::NB; ++j) {
-            const int col = n0 + wn * T::WTN + j * 32 + l32;
-            if (col < p.DC) {
-                const bool epi = p.epilogue && p.split == 1;   // sliced launches leave it to the combine pass
-                const float b = epi && p.bias ? p.bias[col] : 0.f;
-                const float slope = epi ? p.slope : 1.f;
+            const int colBase = n0 + wn * T::WTN + j * 32;
+            if (scratch && (p.DC & 3) == 0 && colBase + 32 <= p.DC) {   // uniform
+                const float b = epi && p.bias ? p.bias[colBase + l32] : 0.f;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int o = orow[r / 4][r % 4];
                     float v = acc[i][j][r] + b;
                     v = v > 0.f ? v : v * slope;
-                    if (o >= 0) C[o * p.DC + col] = v;
+                    scratch[(8 * (r / 4) + 4 * lh + (r % 4)) * kLDT + l32] = v;
+                }
+                // the LDS pipeline keeps a wave's accesses in order; no other wave touches this buffer
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int row = q * 8 + (lane >> 3), seg = lane & 7;
+                    const f4 v = *reinterpret_cast<const f4 *>(scratch + row * kLDT + seg * 4);
+                    const int o = outRow[wm * T::WTM + i * 32 + row];
+                    if (o >= 0) *reinterpret_cast<f4 *>(C + o * p.DC + colBase + seg * 4) = v;
+                }
+            } else {
+                i4 orow[4];
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    orow[g] = *reinterpret_cast<const i4 *>(outRow + wm * T::WTM + i * 32 + 8 * g + 4 * lh);
+                const int col = colBase + l32;
+                if (col < p.DC) {
+                    const float b = epi && p.bias ? p.bias[col] : 0.f;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int o = orow[r / 4][r % 4];
+                        float v = acc[i][j][r] + b;
+                        v = v > 0.f ? v : v * slope;
+                        if (o >= 0) C[o * p.DC + col] = v;
+                    }
                 }
             }
         }

@@ -327,7 +327,10 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     }
 
     STAMP(4);
-    gather_tile_store<T>(p, slice, n0, outRow, acc, wm, wn, l32, lh);
+    // the stage buffers are free now (every wave read its last fragments before the last barrier;
+    // what is still read from them is never used): each wave turns its blocks in its own part
+    static_assert(4 * 32 * kLDT <= 2 * T::A_STAGE, "four turning buffers fit over the A stages");
+    gather_tile_store<T>(p, slice, n0, outRow, acc, wm, wn, l32, lh, As + wave * 32 * kLDT);
     STAMP(5);
 }
 
