@@ -139,7 +139,17 @@ __global__ __launch_bounds__(256) void slice_reduce_kernel(const float *__restri
     double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
     if (i < count4) {
         const float4 *p = reinterpret_cast<const float4 *>(ws) + i;
-        for (int s = g; s < split; s += G) {
+        int s = g;
+        // four loads in flight, added in slice order
+        for (; s + 3 * G < split; s += 4 * G) {
+            const float4 v0 = p[s * stride4], v1 = p[(s + G) * stride4], v2 = p[(s + 2 * G) * stride4],
+                         v3 = p[(s + 3 * G) * stride4];
+            a0 += v0.x; a1 += v0.y; a2 += v0.z; a3 += v0.w;
+            a0 += v1.x; a1 += v1.y; a2 += v1.z; a3 += v1.w;
+            a0 += v2.x; a1 += v2.y; a2 += v2.z; a3 += v2.w;
+            a0 += v3.x; a1 += v3.y; a2 += v3.z; a3 += v3.w;
+        }
+        for (; s < split; s += G) {
             const float4 v = p[s * stride4];
             a0 += v.x; a1 += v.y; a2 += v.z; a3 += v.w;
         }
