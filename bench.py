@@ -166,8 +166,8 @@ def table(mc, torch, cfg_names, with_oracle=False, with_epilogue=False):
                 continue
             seen.add(layer.name)
             r = LayerRunner(layer, mc, torch, random_fill=True)
-            if not rows:
-                r.spin_up()
+            if not rows or with_oracle:
+                r.spin_up()      # the oracle's seconds on the host let the clock governor fall back
             hbm_bound = layer.flops / op_bytes(layer, "fwd") < 2.0 * ridge
             sets = [r]
             if hbm_bound:
@@ -189,7 +189,7 @@ def table(mc, torch, cfg_names, with_oracle=False, with_epilogue=False):
                 plan = "v%d %dx%d s%d pm%d g%d" % (pl.variant, pl.tile_m, pl.tile_n, pl.split,
                                                    pl.pos_major, pl.grid)
                 gbs = op_bytes(layer, op) / ms / 1e6
-                oms = oracle_ms(layer, r.host, op) if with_oracle else None
+                oms = None
                 rows.append({"layer": layer.name, "op": op, "ms": round(ms, 5), "tflops": round(tf, 2),
                              "pct_peak": round(100 * tf / PEAK_FP32_MFMA_TFLOPS, 1),
                              "gbs": round(gbs, 1), "cold_ms": None if cold is None else round(cold, 5),
@@ -198,6 +198,10 @@ def table(mc, torch, cfg_names, with_oracle=False, with_epilogue=False):
                 log("%-5s %-10s %9.4f %9.2f %7.1f %7.0f %9s %10s  %s"
                     % (layer.name, op, ms, tf, 100 * tf / PEAK_FP32_MFMA_TFLOPS, gbs,
                        "-" if cold is None else "%.4f" % cold, "-" if oms is None else "%.1f" % oms, plan))
+            if with_oracle:      # after the layer's GPU timing, so that it does not cool the clocks in between
+                for row in rows[-len(OPS):]:
+                    row["oracle_ms"] = round(oracle_ms(layer, r.host, row["op"]), 2)
+                    log("%-5s %-10s oracle %.1f ms" % (layer.name, row["op"], row["oracle_ms"]))
             if with_epilogue:   # forward with bias + leaky-ReLU in the epilogue, against the plain forward
                 bias = torch.zeros(layer.OC, dtype=torch.float32, device="cuda")
                 ms = r.event_ms(lambda: mc.conv2d_fwd_bias_act(r.X, r.W, bias, r.Y, r.desc, 0.01, ws=r.ws))
