@@ -155,10 +155,11 @@ def _check(t, shape, name):
 
 def _call(name, op, a, b, out, desc, ws, stream):
     lib = load()
-    need = conv2d_workspace_bytes(op, desc)
-    if ws is None and need:
-        import torch
-        ws = torch.empty(need, dtype=torch.uint8, device=out.device)
+    if ws is None:      # the library checks the size of a workspace the caller brings
+        need = conv2d_workspace_bytes(op, desc)
+        if need:
+            import torch
+            ws = torch.empty(need, dtype=torch.uint8, device=out.device)
     nbytes = ws.numel() * ws.element_size() if ws is not None else 0
     rc = getattr(lib, name)(_ptr(a), _ptr(b), _ptr(out), ctypes.byref(desc), _ptr(ws), nbytes,
                             _stream_handle(stream))
