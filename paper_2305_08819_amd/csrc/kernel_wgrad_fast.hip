@@ -92,8 +92,8 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
     const int ohow = p.OH * p.OW;
 
     const int chunksTotal = (p.M + kBK - 1) / kBK;
-    const int ch0 = slice * chunksTotal / p.split;
-    const int ch1 = (slice + 1) * chunksTotal / p.split;
+    int ch0 = slice * chunksTotal / p.split;          // (oh,ow,n) order: replaced below by a cut of the live stages
+    int ch1 = (slice + 1) * chunksTotal / p.split;
 
     constexpr int kOutOfRange = (int)0x80000000;
     const __amdgpu_buffer_rsrc_t rsrcG =
@@ -146,6 +146,21 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
             hi |= (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(liveMask >> 32), l);
         }
         tileLive = ((unsigned long long)hi << 32) | lo;
+        // Slices cut the tile's LIVE stages evenly, not its rows: a slice of the first output rows
+        // would otherwise be nearly empty for a tap that reaches up, and the slices of one tile
+        // would differ in length by several times.  Live stage q sits at the (q / cpp)-th live
+        // position, chunk q % cpp of it (cpp = chunks per position).
+        const int cpp = p.N / kBK;
+        const int liveQ = __popcll(tileLive) * cpp;
+        auto chunk_of = [&](int q) __attribute__((always_inline)) -> int {
+            if (q >= liveQ) return chunksTotal;
+            const int idx = q / cpp;
+            unsigned long long m = tileLive;
+            for (int k = 0; k < idx; ++k) m &= m - 1;     // drop the idx lowest live positions
+            return __builtin_ctzll(m) * cpp + (q - idx * cpp);
+        };
+        ch0 = chunk_of((int)((long long)slice * liveQ / p.split));
+        ch1 = chunk_of((int)((long long)(slice + 1) * liveQ / p.split));
     } else {
 #pragma unroll
         for (int i = 0; i < T::PX; ++i) {
