@@ -578,6 +578,13 @@ Plan plan_bwd_weight(const Shape &s)
     pl.posMajor = posMajor;
     pl.tilesM = ceil_div(s.OC, pl.bm);
     pl.tilesN = ceil_div(Ktot, pl.bn);
+    // A grid barely above one lap of 256 leaves most CUs with one workgroup and a few with two whole
+    // ones; two slices per tile halve the items, and the dealing then fills the CUs to 3 halves at most
+    // (measured on 288 tiles: 43 -> 38 us).  The model's whole-number quantisation does not see this.
+    if (posMajor && pl.fast && pl.split == 1 && g_forceSplit.load() == 0 && s.IC % pl.bn == 0) {
+        const long long tiles = (long long)pl.tilesM * pl.tilesN;
+        if (tiles > 256 && tiles < 384 && chunks * live >= 8) pl.split = 2;
+    }
     pl.flushChunks = M > 150000 ? 8 : 16;   // fp32 chains of at most 512 products (256 for very long reductions)
     finish_plan(pl, pl.split);
     return pl;
