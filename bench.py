@@ -9,6 +9,7 @@ inputs resident in HBM.  The default workload is the ResNet-style down-sampling 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-cpu-baseline]
   python bench.py --table [cfg2 cfg3 ...] [--with-oracle]   per-layer, per-operator table (stderr + JSON line)
   python bench.py --workload cfg5           a whole configuration back to back (VGG-16: 39 operators per step)
+  python bench.py --regret C2,V8            planner pick against an exhaustive tile / order / slice sweep
   python bench.py --streams                 independent operators on separate streams vs one stream
 """
 from __future__ import annotations
@@ -280,6 +281,58 @@ def streams_report(mc, torch):
     return out
 
 
+def regret_report(mc, torch, names):
+    """Planner pick against an exhaustive sweep of compiled tiles x row orders x slice counts, per
+    layer and operator (the overrides conv2d_set_tile / conv2d_set_tuning drive the sweep)."""
+    import itertools
+    layers = {l.name: l for l in wl.all_layers()}
+    gather_tiles = [(128, 128), (128, 64), (64, 64), (128, 32)]
+    wgrad_tiles = [(128, 128), (64, 128), (128, 64), (64, 64), (32, 128)]
+    splits = (1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256)
+    opcodes = {"fwd": mc.OP_FWD, "bwd_data": mc.OP_BWD_DATA, "bwd_weight": mc.OP_BWD_WEIGHT}
+    rows = []
+    try:
+        for name in names:
+            r = LayerRunner(layers[name], mc, torch, random_fill=True)
+            r.spin_up()
+            for op in OPS:
+                mc.conv2d_set_tile(0, 0, -1)
+                mc.conv2d_set_tuning(mc.VARIANT_AUTO, 0)
+                pl0 = mc.conv2d_query_plan(opcodes[op], r.desc)
+                if pl0.workspace_bytes > r.ws.numel():
+                    r.ws = torch.empty(pl0.workspace_bytes, dtype=torch.uint8, device="cuda")
+                base = r.event_ms(lambda: r.run(op), 50, 10, 3)
+                best, best_plan, seen = base, "planner", set()
+                for (bm, bn), pm in itertools.product(wgrad_tiles if op == "bwd_weight" else gather_tiles, (0, 1)):
+                    for sp in splits:
+                        mc.conv2d_set_tile(bm, bn, pm)
+                        mc.conv2d_set_tuning(mc.VARIANT_AUTO, sp)
+                        pl = mc.conv2d_query_plan(opcodes[op], r.desc)
+                        key = (pl.tile_m, pl.tile_n, pl.pos_major, pl.split)
+                        if key in seen or pl.variant != mc.VARIANT_MFMA or not 128 <= pl.grid <= 8192:
+                            continue
+                        seen.add(key)
+                        if pl.workspace_bytes > (1 << 29):
+                            continue
+                        if pl.workspace_bytes > r.ws.numel():
+                            r.ws = torch.empty(pl.workspace_bytes, dtype=torch.uint8, device="cuda")
+                        ms = r.event_ms(lambda: r.run(op), 30, 5, 3)
+                        if ms < best:
+                            best, best_plan = ms, "%dx%d pm%d s%d g%d" % (key + (pl.grid,))
+                rows.append({"layer": name, "op": op, "planner_ms": round(base, 5), "best_ms": round(best, 5),
+                             "best_plan": best_plan, "regret_pct": round(100 * (base / best - 1), 1),
+                             "planner_plan": "%dx%d pm%d s%d g%d" % (pl0.tile_m, pl0.tile_n, pl0.pos_major,
+                                                                    pl0.split, pl0.grid)})
+                log("%-4s %-10s planner %-24s %.4f ms | best %.4f ms %-24s | regret %.1f%%"
+                    % (name, op, rows[-1]["planner_plan"], base, best, best_plan, rows[-1]["regret_pct"]))
+            del r
+            torch.cuda.empty_cache()
+    finally:
+        mc.conv2d_set_tile(0, 0, -1)
+        mc.conv2d_set_tuning(mc.VARIANT_AUTO, 0)
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -288,6 +341,8 @@ def main():
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--table", nargs="*", default=None, metavar="CFG")
+    ap.add_argument("--regret", default=None, metavar="LAYER,LAYER",
+                    help="planner pick against an exhaustive sweep of tiles, row orders and slice counts")
     ap.add_argument("--graph", action="store_true",
                     help="with --workload cfgN: capture one step into a HIP graph and time its replay")
     ap.add_argument("--streams", action="store_true",
@@ -322,6 +377,10 @@ def main():
 
     if args.streams:
         print(json.dumps({"streams": streams_report(mc, torch)}))
+        return
+
+    if args.regret:
+        print(json.dumps({"regret": regret_report(mc, torch, args.regret.split(","))}))
         return
 
     if args.table is not None:

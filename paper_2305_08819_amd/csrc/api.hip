@@ -187,7 +187,7 @@ bool tile_compiled(int bm, int bn, bool gather)
     return ((bm == 128 || bm == 64) && (bn == 128 || bn == 64)) || (bm == 32 && bn == 128);
 }
 
-const TileCand kGatherTiles[] = {{128, 128, 0.88, 2}, {128, 64, 0.93, 2}, {64, 64, 0.945, 4}, {128, 32, 0.66, 3}};
+const TileCand kGatherTiles[] = {{128, 128, 0.88, 2}, {128, 64, 0.93, 2}, {64, 64, 0.945, 4}, {128, 32, 0.80, 3}};
 const TileCand kWgradTiles[] = {{128, 128, 0.80, 1}, {64, 128, 0.93, 2}, {128, 64, 0.94, 2}, {64, 64, 0.98, 4},
                                 {32, 128, 0.90, 3}};
 
@@ -320,7 +320,8 @@ Plan plan_fwd(const Shape &s)
         } else {
             // no column tile wider than needed, and the narrow tile only for narrow outputs
             if (c.bn > 32 && c.bn / 2 >= s.OC) continue;
-            if (c.bn == 32 && s.OC > 32) continue;
+            // the narrow tile: narrow outputs, or a channel count whose last 64-wide tile would be at most half used
+            if (c.bn == 32 && s.OC > 32 && !(s.OC % 64 != 0 && s.OC % 64 <= 32)) continue;
         }
         const long long tiles = (long long)ceil_div(M, c.bm) * ceil_div(s.OC, c.bn);
         for (int order = 0; order < 2; ++order) {
@@ -468,7 +469,7 @@ Plan plan_bwd_data(const Shape &s)
             if (c.bm != fbm || c.bn != fbn) continue;
         } else {
             if (c.bn > 32 && c.bn / 2 >= s.IC) continue;
-            if (c.bn == 32 && s.IC > 32) continue;
+            if (c.bn == 32 && s.IC > 32 && !(s.IC % 64 != 0 && s.IC % 64 <= 32)) continue;
         }
         Plan trial = pl;
         double avgTaps = 0;
