@@ -558,7 +558,9 @@ Plan plan_bwd_weight(const Shape &s)
     for (int pass = 0; pass < 2 && pl.bm == 0; ++pass) {   // second pass: the forced tile does not apply here
         for (const TileCand &c : kWgradTiles) {
             if (pl.elem && c.bn != 64) continue;   // element-wise X loader is compiled for 64-wide tiles
-            if (c.bm == 32 && (!pl.fast || s.OC > 32)) continue;   // one block row: narrow outputs, fast kernel only
+            // one block row (fast kernel only): narrow outputs, or a channel count whose last 64-row tile
+            // would be at most half used
+            if (c.bm == 32 && (!pl.fast || (s.OC > 32 && !(s.OC % 64 != 0 && s.OC % 64 <= 32)))) continue;
             if (pass == 0 && haveForced && !(pl.elem && fbn != 64)) {
                 if (c.bm != fbm || c.bn != fbn) continue;
             } else {
