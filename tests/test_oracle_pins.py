@@ -315,3 +315,61 @@ def test_fwd_u8_hand_values_and_scale():
     x32 = (X8.astype(np.float32) * np.float32(1.0 / 255.0))
     assert x32.dtype == np.float32 and np.array_equal(y, oracle.conv2d_fwd(x32, W, 1, 1))
     assert np.abs(y - oracle.conv2d_fwd(X8.astype(np.float64).astype(np.float32), W, 1, 1) / 255.0).max() < 1e-5
+
+
+# ---- do the pins bite?  mistakes planted in a copy of the definition, on the CPU -----------------
+def _fwd_with_mistake(X, W, s, p, mistake):
+    """The forward definition as plain loops, with one plausible mistake switched on."""
+    (sh, sw), (ph, pw) = s, p
+    N, IH, IW, IC = X.shape
+    OC, FH, FW, _ = W.shape
+    if mistake == "swapped stride":
+        sh, sw = sw, sh
+    if mistake == "swapped padding":
+        ph, pw = pw, ph
+    OH, OW = (IH + 2 * ph - FH) // sh + 1, (IW + 2 * pw - FW) // sw + 1
+    Y = np.zeros((N, OH, OW, OC))
+    for oh in range(OH):
+        for ow in range(OW):
+            for fh in range(FH):
+                for fw in range(FW):
+                    ih, iw = oh * sh - ph + fh, ow * sw - pw + fw
+                    if mistake == "padding on the far side":
+                        ih, iw = oh * sh + ph - (FH - 1) + fh, ow * sw + pw - (FW - 1) + fw
+                    if not (0 <= ih < IH and 0 <= iw < IW):
+                        continue
+                    if mistake == "dropped last tap" and fh == FH - 1 and fw == FW - 1 and FH * FW > 1:
+                        continue
+                    wf = W[:, FH - 1 - fh, FW - 1 - fw, :] if mistake == "flipped filter" else \
+                        W[:, fw, fh, :] if mistake == "transposed filter" and FH == FW else W[:, fh, fw, :]
+                    Y[:, oh, ow, :] += X[:, ih, iw, :].astype(np.float64) @ wf.astype(np.float64).T
+    return Y
+
+
+def _pins_hold(fwd):
+    """The forward pins with the implementation passed in: shifted delta, all-ones closed form,
+    pad-and-slice second form on an asymmetric shape."""
+    C = 2
+    X = rnd(1, 6, 7, C)
+    W = np.zeros((C, 3, 3, C), np.float32)
+    for c in range(C):
+        W[c, 0, 2, c] = 1
+    expect = np.zeros((1, 6, 7, C))
+    expect[:, 1:, :-1] = X[:, :-1, 1:]
+    ok = np.array_equal(fwd(X, W, (1, 1), (1, 1)), expect)
+    # all ones, 4x5 map, 3x2 filter, stride (1,2), pad (1,0): count of taps inside the image
+    Y = fwd(np.ones((1, 4, 5, 3), np.float32), np.ones((2, 3, 2, 3), np.float32), (1, 2), (1, 0))
+    rows = np.array([2, 3, 3, 2])
+    ok = ok and Y.shape == (1, 4, 2, 2) and np.array_equal(Y[0, :, :, 0], 3.0 * np.outer(rows, [2, 2]))
+    Xr, Wr = rnd(2, 7, 5, 3), rnd(4, 3, 2, 3)
+    Yr = fwd(Xr, Wr, (2, 1), (0, 1))
+    ref = fwd_pad_slice(Xr, Wr, (2, 1), (0, 1))
+    return bool(ok and Yr.shape == ref.shape and rel(Yr, ref) < 1e-12)
+
+
+def test_planted_mistakes_fail_the_pins():
+    assert _pins_hold(lambda X, W, s, p: np.asarray(oracle.conv2d_fwd(X, W, s, p)))
+    assert _pins_hold(lambda X, W, s, p: _fwd_with_mistake(X, W, s, p, None))
+    for mistake in ("flipped filter", "transposed filter", "swapped stride", "swapped padding",
+                    "padding on the far side", "dropped last tap"):
+        assert not _pins_hold(lambda X, W, s, p: _fwd_with_mistake(X, W, s, p, mistake)), mistake
