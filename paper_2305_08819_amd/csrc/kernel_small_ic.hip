@@ -183,8 +183,8 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_small_ic_kernel(const SmallIc
 {
     constexpr int BMf = 128, BNf = 64, LDf = 33;      // odd pitch: both the stores (lane = row) and the
                                                       // fragment reads (lane = row, 4 bytes) spread over banks
-    __shared__ float As[BMf * LDf];
-    __shared__ float Bs[BNf * LDf];
+    __shared__ __attribute__((aligned(16))) float sm[BMf * LDf + BNf * LDf];
+    float *As = sm, *Bs = sm + BMf * LDf;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lh = lane >> 5;
@@ -254,6 +254,30 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_small_ic_kernel(const SmallIc
             acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa, b[j * 32 * LDf + 2 * step], acc[j], 0, 0, 0);
     }
     // accumulator register q of lane l is row 8*(q/4)+4*(l/32)+q%4, column l%32
+    if ((p.OC & 3) == 0) {
+        // the kernel is bound by writing Y: turn each 32x32 block through LDS (the tiles are done
+        // with) so that a lane stores 16 bytes and a store instruction covers eight 128-byte runs
+        static_assert(4 * 32 * kLDT <= BMf * LDf + BNf * LDf, "four turning buffers fit over the tiles");
+        __syncthreads();                       // every wave has read its last fragments
+        float *scratch = sm + wave * 32 * kLDT;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int colBase = oc0 + j * 32;
+            if (colBase < p.OC) {              // uniform; OC % 4 == 0, so 16-byte groups are in or out as a whole
+#pragma unroll
+                for (int q = 0; q < 16; ++q) scratch[(8 * (q / 4) + 4 * lh + (q % 4)) * kLDT + l32] = acc[j][q];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int rowT = t * 8 + (lane >> 3), seg = lane & 7;
+                    const f4 v = *reinterpret_cast<const f4 *>(scratch + rowT * kLDT + seg * 4);
+                    const int mm = m0 + wave * 32 + rowT;
+                    if (mm < p.M && colBase + seg * 4 < p.OC)
+                        *reinterpret_cast<f4 *>(p.dX + (long long)mm * p.OC + colBase + seg * 4) = v;
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int col = oc0 + j * 32 + l32;
