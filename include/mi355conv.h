@@ -26,6 +26,16 @@
  *   - All argument checks happen before the first HIP call, so they can be exercised
  *     on a machine without a GPU.
  *   - Return value: MI355CONV_OK (0) or a negative mi355conv_status.
+ *   - Stream capture: the operator entry points only enqueue kernels (no allocation, no
+ *     memset, no synchronisation), so they may be recorded into a HIP graph.  The first
+ *     operator call on a device also does one-time device set-up (kernel attributes), which must not happen inside a capture: call conv2d_init() - or any operator
+ *     once - on that device before capturing.
+ *   - Process-global tuning: conv2d_set_tuning / conv2d_set_tile change what
+ *     conv2d_workspace_bytes, conv2d_query_plan, conv2d_query_workgroup and every operator
+ *     entry point choose from then on, in all threads.  They exist for tests and sweeps; a
+ *     program that calls operators from several threads or streams leaves them alone (or sets
+ *     them once before it starts), because a workspace sized under one tuning may be too small
+ *     under another (the entry point then returns MI355CONV_ERR_WORKSPACE, it never overruns).
  */
 #ifndef MI355CONV_H
 #define MI355CONV_H
@@ -42,7 +52,7 @@ typedef enum mi355conv_status {
     MI355CONV_ERR_BAD_DIM = -2,     /* dim <= 0, stride <= 0, pad < 0, OH/OW <= 0, >= 2^31 */
     MI355CONV_ERR_WORKSPACE = -3,   /* ws_bytes below conv2d_workspace_bytes(), or ws NULL */
     MI355CONV_ERR_ALIGNMENT = -4,   /* a tensor or the workspace is not 16-byte aligned    */
-    MI355CONV_ERR_UNSUPPORTED = -5, /* bad op code / tuning value                          */
+    MI355CONV_ERR_UNSUPPORTED = -5, /* bad op code / tuning value / shape an entry point does not take */
     MI355CONV_ERR_HIP = -6          /* a HIP runtime call or kernel launch failed          */
 } mi355conv_status;
 
@@ -73,7 +83,24 @@ typedef struct conv2d_plan_info {
     int pos_major;      /* 1: GEMM rows ordered (oh,ow,n) so tiles skip padded taps         */
     int grid;           /* workgroups of the main kernel                                    */
     size_t workspace_bytes;
+    int kernel;         /* MI355CONV_KERNEL_*: which kernel family runs the plan            */
 } conv2d_plan_info;
+
+/* Kernel families (conv2d_plan_info.kernel); for tests, which force every compiled variant. */
+enum {
+    MI355CONV_KERNEL_DIRECT = 0,
+    MI355CONV_KERNEL_GATHER = 1,       /* gather-GEMM, 16-byte loads along the channel axis     */
+    MI355CONV_KERNEL_GATHER_ELEM = 2,  /* gather-GEMM, element-wise loads (any channel count)   */
+    MI355CONV_KERNEL_FIRST_LAYER = 3,  /* the kernels for at most 32 patch columns / 4 channels */
+    MI355CONV_KERNEL_WGRAD = 4,        /* backward-weight, any map shape                        */
+    MI355CONV_KERNEL_WGRAD_FAST = 5    /* backward-weight, aligned maps                         */
+};
+
+/* One-time set-up of the CURRENT device (idempotent, thread-safe): raises the LDS limit of the
+ * large-tile kernels.  Optional - the first operator
+ * call on a device does the same - except before stream capture, where it (or one operator call)
+ * is required.  Must not be called while a capture is under way. */
+int conv2d_init(void);
 
 /* Bytes of device workspace the given operator needs for this shape under the current
  * tuning (0 is possible).  Returns 0 on invalid arguments too; the entry points report
@@ -144,6 +171,14 @@ int deconv2d(const float *dY, const float *W, float *dX, const conv2d_desc *d,
  * order, so results are bitwise reproducible either way. */
 int conv2d_bwd_weight(const float *X, const float *dY, float *dW, const conv2d_desc *d,
                       void *ws, size_t ws_bytes, void *stream);
+
+/* Measurement aid (not an operator): launches a register-only v_mfma_f32_32x32x2_f32 loop with
+ * valu_per_8_mfma in {0, 16, 48, 96} ordinary vector instructions per 8 matrix instructions, on
+ * `workgroups` workgroups of 256 threads, `iters` x 8 matrix instructions per wave, i.e.
+ * workgroups * 4 * iters * 8 * 4096 FLOP.  out: device, workgroups * 256 floats (written so the
+ * loop is not optimised away).  The caller times the launch; bench.py --mfma-peak reports the
+ * sustained fp32 matrix rate that the "% of measured peak" figures refer to. */
+int conv2d_probe_mfma_rate(int valu_per_8_mfma, int workgroups, int iters, float *out, void *stream);
 
 /* Static text for a status code. */
 const char *conv2d_status_string(int status);

@@ -15,11 +15,13 @@ LIB_PATH = os.path.join(_PKG, "libmi355conv.so")
 
 OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT = 0, 1, 2
 VARIANT_AUTO, VARIANT_DIRECT, VARIANT_MFMA = -1, 0, 1
+KERNEL_DIRECT, KERNEL_GATHER, KERNEL_GATHER_ELEM, KERNEL_FIRST_LAYER, KERNEL_WGRAD, KERNEL_WGRAD_FAST = range(6)
 
 EXPORTS = ("conv2d_workspace_bytes", "conv2d_query_plan", "conv2d_query_workgroup", "conv2d_set_tuning", "conv2d_set_tile", "conv2d_fwd",
            "conv2d_fwd_bias_act", "conv2d_fwd_u8",
            "conv2d_bwd_data", "deconv2d", "conv2d_bwd_weight", "conv2d_status_string",
-           "conv2d_last_hip_error")
+           "conv2d_last_hip_error", "conv2d_init",
+           "conv2d_probe_mfma_rate")
 
 
 class ConvDesc(ctypes.Structure):
@@ -40,7 +42,7 @@ class PlanInfo(ctypes.Structure):
     """Mirror of ``conv2d_plan_info``."""
     _fields_ = [("variant", ctypes.c_int), ("tile_m", ctypes.c_int), ("tile_n", ctypes.c_int),
                 ("split", ctypes.c_int), ("pos_major", ctypes.c_int), ("grid", ctypes.c_int),
-                ("workspace_bytes", ctypes.c_size_t)]
+                ("workspace_bytes", ctypes.c_size_t), ("kernel", ctypes.c_int)]
 
 
 class Mi355ConvError(RuntimeError):
@@ -82,6 +84,10 @@ def load() -> ctypes.CDLL:
         lib.conv2d_fwd_bias_act.restype = ctypes.c_int
         lib.conv2d_fwd_u8.argtypes = [vp, ctypes.c_float, vp, vp, dp, vp]
         lib.conv2d_fwd_u8.restype = ctypes.c_int
+        lib.conv2d_init.argtypes = []
+        lib.conv2d_init.restype = ctypes.c_int
+        lib.conv2d_probe_mfma_rate.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
+        lib.conv2d_probe_mfma_rate.restype = ctypes.c_int
         lib.conv2d_status_string.argtypes = [ctypes.c_int]
         lib.conv2d_status_string.restype = ctypes.c_char_p
         lib.conv2d_last_hip_error.argtypes = []
@@ -135,6 +141,13 @@ def conv2d_set_tile(tile_m: int = 0, tile_n: int = 0, pos_major: int = -1) -> No
         raise Mi355ConvError(rc, "conv2d_set_tile")
 
 
+def conv2d_init() -> None:
+    """One-time set-up of the current device (needed before stream capture; otherwise optional)."""
+    rc = load().conv2d_init()
+    if rc != 0:
+        raise Mi355ConvError(rc, "conv2d_init")
+
+
 def _ptr(t):
     return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
 
@@ -153,13 +166,23 @@ def _check(t, shape, name):
         raise ValueError("%s has shape %s, expected %s" % (name, tuple(t.shape), tuple(shape)))
 
 
+def _own_workspace(need, like, stream):
+    """Workspace for a call that brought none.  The tensor is dropped when the call returns, while
+    the kernels may still be running: it is tied to the stream they run on, so torch's caching
+    allocator does not hand the block to another stream's allocation before they finish."""
+    if not need:
+        return None
+    import torch
+    ws = torch.empty(need, dtype=torch.uint8, device=like.device)
+    if stream is not None:
+        ws.record_stream(stream)
+    return ws
+
+
 def _call(name, op, a, b, out, desc, ws, stream):
     lib = load()
     if ws is None:      # the library checks the size of a workspace the caller brings
-        need = conv2d_workspace_bytes(op, desc)
-        if need:
-            import torch
-            ws = torch.empty(need, dtype=torch.uint8, device=out.device)
+        ws = _own_workspace(conv2d_workspace_bytes(op, desc), out, stream)
     nbytes = ws.numel() * ws.element_size() if ws is not None else 0
     rc = getattr(lib, name)(_ptr(a), _ptr(b), _ptr(out), ctypes.byref(desc), _ptr(ws), nbytes,
                             _stream_handle(stream))
@@ -184,10 +207,8 @@ def conv2d_fwd_bias_act(X, W, bias, Y, desc: ConvDesc, negative_slope=1.0, ws=No
     if bias is not None:
         _check(bias, (desc.OC,), "bias")
     lib = load()
-    need = conv2d_workspace_bytes(OP_FWD, desc)
-    if ws is None and need:
-        import torch
-        ws = torch.empty(need, dtype=torch.uint8, device=Y.device)
+    if ws is None:
+        ws = _own_workspace(conv2d_workspace_bytes(OP_FWD, desc), Y, stream)
     nbytes = ws.numel() * ws.element_size() if ws is not None else 0
     rc = lib.conv2d_fwd_bias_act(_ptr(X), _ptr(W), _ptr(bias), _ptr(Y), ctypes.byref(desc),
                                  ctypes.c_float(negative_slope), _ptr(ws), nbytes, _stream_handle(stream))
@@ -234,3 +255,11 @@ def conv2d_bwd_weight(X, dY, dW, desc: ConvDesc, ws=None, stream=None):
     _check(dY, (desc.N, desc.OH, desc.OW, desc.OC), "dY")
     _check(dW, (desc.OC, desc.FH, desc.FW, desc.IC), "dW")
     return _call("conv2d_bwd_weight", OP_BWD_WEIGHT, X, dY, dW, desc, ws, stream)
+
+
+def conv2d_probe_mfma_rate(valu_per_8_mfma, workgroups, iters, out, stream=None):
+    """Launch the register-only fp32 MFMA loop (measurement aid); returns the FLOP it executes."""
+    rc = load().conv2d_probe_mfma_rate(valu_per_8_mfma, workgroups, iters, _ptr(out), _stream_handle(stream))
+    if rc != 0:
+        raise Mi355ConvError(rc, "conv2d_probe_mfma_rate")
+    return workgroups * 4 * iters * 8 * 4096

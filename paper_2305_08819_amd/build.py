@@ -14,7 +14,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libmi355conv.so")
 SOURCES = ["api.hip", "kernels_direct.hip", "kernel_gather_gemm.hip", "kernel_gather_elem.hip",
-           "kernel_wgrad.hip", "kernel_wgrad_fast.hip", "kernel_small_ic.hip"]
+           "kernel_wgrad.hip", "kernel_wgrad_fast.hip", "kernel_small_ic.hip", "probe_mfma.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-fp32 VALU forms are kept out of the generated code on purpose

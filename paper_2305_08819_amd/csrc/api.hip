@@ -540,7 +540,8 @@ Plan plan_bwd_weight(const Shape &s)
               (long long)s.N * s.IH * s.IW * s.IC * 4 < (1LL << 31) && M * s.OC * 4 < (1LL << 31);
     // the fast kernel keeps a 64-bit mask of output positions in (oh,ow,n) order
     const bool smallMap = (s.ph > 0 || s.pw > 0) && s.OH * s.OW <= kSmallMapPixels;
-    const int posMajor = resolve_order(smallMap, s.N % kBK == 0 && !pl.elem && (!pl.fast || ohow <= 64));
+    // ... and takes (oh,ow,n) order only where an output row is at most one stage long
+    const int posMajor = resolve_order(smallMap, s.N % kBK == 0 && !pl.elem && (!pl.fast || (ohow <= 64 && s.OW <= kBK)));
     const long long Ktot = (long long)s.FH * s.FW * s.IC;
     const int chunks = ceil_div(M, kBK);
     // fraction of (position, tap) pairs inside the image = share of stages a tile keeps
@@ -597,6 +598,31 @@ int hip_fail(hipError_t e)
 {
     snprintf(t_hipError, sizeof t_hipError, "%s", hipGetErrorString(e));
     return MI355CONV_ERR_HIP;
+}
+
+// ---- per-device set-up -------------------------------------------------------------------
+constexpr int kMaxDevices = 64;
+std::mutex g_deviceMutex;
+std::atomic<int> g_deviceReady[kMaxDevices];
+
+// Once per device, with that device current and no stream capture under way: raises the LDS limit
+// of the large-tile kernels.
+int prepare_device(int *devOut)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return hip_fail(hipErrorInvalidDevice);
+    if (devOut) *devOut = dev;
+    if (g_deviceReady[dev].load(std::memory_order_acquire)) return MI355CONV_OK;
+    std::lock_guard<std::mutex> lock(g_deviceMutex);
+    if (g_deviceReady[dev].load(std::memory_order_relaxed)) return MI355CONV_OK;
+    e = prepare_gather_gemm();
+    if (e == hipSuccess) e = prepare_wgrad();
+    if (e == hipSuccess) e = prepare_wgrad_fast();
+    if (e != hipSuccess) return hip_fail(e);
+    g_deviceReady[dev].store(1, std::memory_order_release);
+    return MI355CONV_OK;
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -836,6 +862,26 @@ void plan_balance_wgrad(const Shape &s, Plan &pl)
     pl.balance = 1;
 }
 
+// The plan against the preconditions of the launcher it names (the same predicates the launchers
+// apply).  A plan that fails here is a defect of the planner; the entry points then report
+// MI355CONV_ERR_UNSUPPORTED before any HIP call instead of a launch error.
+bool plan_launchable(int op, const Shape &s, const Plan &pl)
+{
+    if (pl.variant != MI355CONV_VARIANT_MFMA) return true;
+    if (pl.bm <= 0 || pl.bn <= 0 || pl.split < 1 || pl.grid < 1) return false;
+    if (op == MI355CONV_OP_BWD_WEIGHT) {
+        if (pl.smallIc) return patch_small_ic_accepts(s.IC, s.FH, s.FW) && pl.bm == 64 && pl.bn == 32;
+        if (pl.fast) return wgrad_fast_accepts(s.N, s.OH, s.OW, s.IC, s.OC, pl.posMajor, pl.bm, pl.bn);
+        return wgrad_accepts(s.N, s.IC, s.OC, pl.posMajor, pl.elem != 0, pl.bm, pl.bn);
+    }
+    const bool bwd = op == MI355CONV_OP_BWD_DATA;
+    if (pl.smallIc)
+        return bwd ? bwd_data_small_ic_accepts(s.IC, s.OC, s.FH, s.FW, s.sh, s.sw) : patch_small_ic_accepts(s.IC, s.FH, s.FW);
+    if (pl.posMajor && s.N % pl.bm != 0) return false;   // a row tile sits on one pixel position
+    if (pl.elem) return gather_elem_accepts(pl.bm, pl.bn);
+    return gather_gemm_accepts(bwd ? s.OC : s.IC, bwd ? s.IC : s.OC, bwd, pl.bm, pl.bn);
+}
+
 // Plans depend on the descriptor and the tuning overrides only; they are kept in a hash map so
 // that the enqueue path does not repeat the search (and the longest-first dealing, which takes
 // a good fraction of a millisecond) on every call.
@@ -888,6 +934,7 @@ int make_plan(int op, const Shape &s, Plan *pl)
         if (pl->variant == MI355CONV_VARIANT_MFMA) plan_balance_wgrad(s, *pl);
         break;
     }
+    if (!plan_launchable(op, s, *pl)) return MI355CONV_ERR_UNSUPPORTED;
     {
         std::lock_guard<std::mutex> lock(g_planMutex);
         if (!g_planMap) g_planMap = new std::unordered_map<PlanKey, Plan, PlanKeyHash>();
@@ -976,6 +1023,10 @@ int conv2d_query_plan(int op, const conv2d_desc *d, conv2d_plan_info *info)
     info->pos_major = pl.posMajor;
     info->grid = pl.grid;
     info->workspace_bytes = pl.wsBytes;
+    if (pl.variant == MI355CONV_VARIANT_DIRECT) info->kernel = MI355CONV_KERNEL_DIRECT;
+    else if (pl.smallIc) info->kernel = MI355CONV_KERNEL_FIRST_LAYER;
+    else if (op == MI355CONV_OP_BWD_WEIGHT) info->kernel = pl.fast ? MI355CONV_KERNEL_WGRAD_FAST : MI355CONV_KERNEL_WGRAD;
+    else info->kernel = pl.elem ? MI355CONV_KERNEL_GATHER_ELEM : MI355CONV_KERNEL_GATHER;
     return MI355CONV_OK;
 }
 
@@ -1041,6 +1092,8 @@ static int fwd_impl(const float *X, const float *W, float *Y, const conv2d_desc 
         rc = check_buffers(X, W, Y, pl, ws, ws_bytes);
         if (rc != MI355CONV_OK) return rc;
     }
+    rc = prepare_device(nullptr);
+    if (rc != MI355CONV_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (pl.variant == MI355CONV_VARIANT_DIRECT) {
         hipError_t e = launch_direct_fwd(X, W, Y, s, st);
@@ -1108,6 +1161,8 @@ int conv2d_bwd_data(const float *dY, const float *W, float *dX, const conv2d_des
     if (rc != MI355CONV_OK) return rc;
     rc = check_buffers(dY, W, dX, pl, ws, ws_bytes);
     if (rc != MI355CONV_OK) return rc;
+    rc = prepare_device(nullptr);
+    if (rc != MI355CONV_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (pl.variant == MI355CONV_VARIANT_DIRECT) {
         hipError_t e = launch_direct_bwd_data(dY, W, dX, s, st);
@@ -1143,6 +1198,8 @@ int conv2d_bwd_weight(const float *X, const float *dY, float *dW, const conv2d_d
     rc = make_plan(MI355CONV_OP_BWD_WEIGHT, s, &pl);
     if (rc != MI355CONV_OK) return rc;
     rc = check_buffers(X, dY, dW, pl, ws, ws_bytes);
+    if (rc != MI355CONV_OK) return rc;
+    rc = prepare_device(nullptr);
     if (rc != MI355CONV_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (pl.variant == MI355CONV_VARIANT_DIRECT) {
@@ -1214,6 +1271,8 @@ int conv2d_bwd_weight(const float *X, const float *dY, float *dW, const conv2d_d
     }
     return MI355CONV_OK;
 }
+
+int conv2d_init(void) { return prepare_device(nullptr); }
 
 const char *conv2d_status_string(int status)
 {

@@ -279,6 +279,54 @@ __device__ __forceinline__ int xcd_remap(int bid, int grid, int unit)
     return ((q / unit) * kXcds + x) * unit + q % unit;
 }
 
+// ---- what each launcher takes, as host-side predicates ---------------------------------------
+// The planner checks every plan against the same predicate that the launcher applies, so a plan
+// that a launcher would refuse is caught on the host before any HIP call (and by a CPU test
+// that sweeps shapes through conv2d_query_plan).
+inline bool gather_gemm_accepts(int srcC, int dstC, bool bwdData, int bm, int bn)
+{
+    if (srcC % 4 != 0) return false;
+    if (bwdData && dstC % 4 != 0) return bm == 128 && bn == 32;   // filter columns by 4-byte loads
+    return (bm == 128 && (bn == 128 || bn == 64 || bn == 32)) || (bm == 64 && bn == 64);
+}
+inline bool gather_elem_accepts(int bm, int bn)
+{
+    return (bm == 128 && (bn == 64 || bn == 32)) || (bm == 64 && bn == 64);
+}
+// Generic backward-weight kernel: (oh,ow,n) order needs stages that sit on one output position.
+inline bool wgrad_accepts(int N, int IC, int OC, int posMajor, bool xElem, int bm, int bn)
+{
+    if (OC % 4 != 0) return false;
+    if (xElem) return !posMajor && bn == 64 && (bm == 64 || bm == 128);
+    if (IC % 4 != 0) return false;
+    if (posMajor && N % kBK != 0) return false;
+    return (bm == 128 || bm == 64) && (bn == 128 || bn == 64);
+}
+// Fast backward-weight kernel: "aligned" maps only - OW divides 32 and OH*OW divides or is a multiple
+// of 32, or OW is a multiple of 32 (wide rows; (n,oh,ow) order only).  (oh,ow,n) order keeps a 64-bit
+// mask of output positions and needs N to be a multiple of 32.
+inline bool wgrad_fast_accepts(int N, int OH, int OW, int IC, int OC, int posMajor, int bm, int bn)
+{
+    const int ohow = OH * OW;
+    const bool narrow = kBK % OW == 0 && (ohow % kBK == 0 || kBK % ohow == 0);
+    const bool wide = OW > kBK && OW % kBK == 0;
+    if (!narrow && !wide) return false;
+    if (IC % 4 != 0 || OC % 4 != 0) return false;
+    if (posMajor && (wide || N % kBK != 0 || ohow > 64)) return false;
+    return ((bm == 128 || bm == 64) && (bn == 128 || bn == 64)) || (bm == 32 && bn == 128);
+}
+inline bool bwd_data_small_ic_accepts(int IC, int OC, int FH, int FW, int sh, int sw)
+{
+    return sh == 1 && sw == 1 && IC <= 4 && FH * FW * IC <= 32 && OC % kBK == 0 && (4 + FH - 1) * (32 + FW - 1) <= 224;
+}
+inline bool patch_small_ic_accepts(int IC, int FH, int FW) { return FH * FW * IC <= 32; }   // forward, backward-weight
+
+// Once per device, outside any stream capture: raise the dynamic-LDS limit of the kernel
+// instantiations whose tiles exceed the 64 KB a kernel gets by default.
+hipError_t prepare_gather_gemm();
+hipError_t prepare_wgrad();
+hipError_t prepare_wgrad_fast();
+
 hipError_t launch_direct_fwd(const float *X, const float *W, float *Y, const Shape &s, hipStream_t st);
 hipError_t launch_direct_bwd_data(const float *G, const float *W, float *dX, const Shape &s, hipStream_t st);
 hipError_t launch_direct_bwd_weight(const float *X, const float *G, float *dW, const Shape &s, hipStream_t st);

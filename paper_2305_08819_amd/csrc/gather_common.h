@@ -2,9 +2,6 @@
 // element-wise loader): tile geometry, per-tile row tables, fragment reads + MFMAs, epilogue.
 #pragma once
 #include "conv_internal.h"
-#ifndef STAMP
-#define STAMP(i) do {} while (0)
-#endif
 
 namespace mi355conv {
 
@@ -155,9 +152,7 @@ __device__ __forceinline__ GatherTile gather_tile_setup(const P &p, int *rowBase
         }
         if (t.uHi < t.uLo || t.vHi < t.vLo) { t.uHi = -1; t.uLo = 0; t.vHi = -1; t.vLo = 0; }
     }
-    STAMP(6);
     __syncthreads();
-    STAMP(7);
     return t;
 }
 

@@ -159,6 +159,7 @@ static hipError_t launch_elem(const GatherGemmParams &p, int grid, hipStream_t s
 
 hipError_t launch_gather_elem(const GatherGemmParams &p, bool bwdData, int bm, int bn, int grid, hipStream_t st)
 {
+    if (!gather_elem_accepts(bm, bn)) return hipErrorInvalidValue;
 #define MI355_GE_CASE(BM_, BN_, WM_)                                                     \
     if (bm == BM_ && bn == BN_)                                                          \
         return bwdData ? launch_elem<BM_, BN_, WM_, true>(p, grid, st)                   \

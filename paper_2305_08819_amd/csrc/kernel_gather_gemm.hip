@@ -24,13 +24,6 @@
 // is free as long as A and B agree, so a lane reads FOUR consecutive k (one 16-byte LDS
 // read at k = 8*jj + 4*(l/32)) and uses them in four successive MFMAs.
 #include <hip/hip_runtime.h>
-// -DMI355CONV_TIMELINE compiles in a per-workgroup timeline (constant-rate clock at eight points).
-#if defined(MI355CONV_TIMELINE)
-namespace mi355conv { __device__ unsigned long long g_stamps[8192 * 8]; }
-#define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) mi355conv::g_stamps[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define STAMP(i) do {} while (0)
-#endif
 #include "gather_common.h"
 
 namespace mi355conv {
@@ -44,7 +37,6 @@ namespace mi355conv {
 template <int BM, int BN, int WAVES_M, bool BWD, bool BELEM = false, bool RAGGED = false>
 __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGemmParams params)
 {
-    STAMP(0);
     const GatherView p = gather_view(params);
     using T = GG<BM, BN, WAVES_M, BWD>;
     extern __shared__ f4 smem_raw[];
@@ -62,7 +54,6 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
 
     const GatherTile tile = gather_tile_setup<BM, BN, BWD>(p, rowBase, rowY, rowX, outRow);
     const int slice = tile.slice, n0 = tile.n0;
-    STAMP(1);
 
     // taps walked by this tile: the rectangle [uLo,uHi] x [vLo,vHi]
     const int uCnt = tile.uHi >= tile.uLo ? tile.uHi - tile.uLo + 1 : 0;
@@ -307,11 +298,9 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
             gload(gaS[1], gbS[1]);
             advance();
         }
-        STAMP(2);
         lds_store(0, gaS[0], gbS[0]);
         __syncthreads();
         read_group(0, 0, fa[0], fb[0]);
-        STAMP(3);
         int t = 0;
         // steady state: no branch around memory instructions, so every wait is an exact count
         for (; t + 3 < n; t += 2) {
@@ -326,45 +315,60 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
         }
     }
 
-    STAMP(4);
     // the stage buffers are free now (every wave read its last fragments before the last barrier;
     // what is still read from them is never used): each wave turns its blocks in its own part
     static_assert(4 * 32 * kLDT <= 2 * T::A_STAGE, "four turning buffers fit over the A stages");
     gather_tile_store<T>(p, slice, n0, outRow, acc, wm, wn, l32, lh, As + wave * 32 * kLDT);
-    STAMP(5);
 }
 
-#if defined(MI355CONV_TIMELINE)
-extern "C" int exp_read_stamps(unsigned long long *host, size_t count)
+template <int BM, int BN, int WAVES_M, bool BWD>
+constexpr size_t gather_smem_bytes()
 {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_stamps), count * sizeof(unsigned long long));
+    using T = GG<BM, BN, WAVES_M, BWD>;
+    return (2 * (T::A_STAGE + T::B_STAGE) + T::TABLE_INTS) * sizeof(float);
 }
-#endif
 
 template <int BM, int BN, int WAVES_M, bool BWD, bool BELEM = false, bool RAGGED = false>
 static hipError_t launch_one(const GatherGemmParams &p, int grid, hipStream_t st)
 {
-    using T = GG<BM, BN, WAVES_M, BWD>;
-    constexpr size_t kSmemBytes = (2 * (T::A_STAGE + T::B_STAGE) + T::TABLE_INTS) * sizeof(float);
-    auto kern = gather_gemm_kernel<BM, BN, WAVES_M, BWD, BELEM, RAGGED>;
-    static bool attrSet[16] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= 16 || !attrSet[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmemBytes);
-        if (e != hipSuccess) return e;
-        if (dev >= 0 && dev < 16) attrSet[dev] = true;
-    }
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kSmemBytes, st, p);
+    constexpr size_t kSmemBytes = gather_smem_bytes<BM, BN, WAVES_M, BWD>();
+    hipLaunchKernelGGL((gather_gemm_kernel<BM, BN, WAVES_M, BWD, BELEM, RAGGED>), dim3((unsigned)grid), dim3(kThreads),
+                       kSmemBytes, st, p);
     return hipGetLastError();
+}
+
+// Instantiations whose tiles need more LDS than a kernel gets by default (64 KB): the limit is
+// raised once per device, outside any stream capture (see prepare_device in the host API).
+template <int BM, int BN, int WAVES_M, bool BWD, bool RAGGED>
+static hipError_t raise_lds_limit()
+{
+    constexpr size_t bytes = gather_smem_bytes<BM, BN, WAVES_M, BWD>();
+    if (bytes <= 64 * 1024) return hipSuccess;
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(gather_gemm_kernel<BM, BN, WAVES_M, BWD, false, RAGGED>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+hipError_t prepare_gather_gemm()
+{
+    hipError_t e = hipSuccess;
+#define MI355_GG_PREP(BM_, BN_, WM_)                                                    \
+    if (e == hipSuccess) e = raise_lds_limit<BM_, BN_, WM_, false, false>();            \
+    if (e == hipSuccess) e = raise_lds_limit<BM_, BN_, WM_, false, true>();             \
+    if (e == hipSuccess) e = raise_lds_limit<BM_, BN_, WM_, true, false>();             \
+    if (e == hipSuccess) e = raise_lds_limit<BM_, BN_, WM_, true, true>();
+    MI355_GG_PREP(128, 128, 2)
+    MI355_GG_PREP(128, 64, 2)
+    MI355_GG_PREP(64, 64, 2)
+    MI355_GG_PREP(128, 32, 4)
+#undef MI355_GG_PREP
+    static_assert(gather_smem_bytes<128, 32, 4, true>() <= 64 * 1024, "the 4-byte filter loader's tile fits the default limit");
+    return e;
 }
 
 hipError_t launch_gather_gemm(const GatherGemmParams &p, bool bwdData, int bm, int bn, int grid,
                               hipStream_t st)
 {
-    if (p.SC % 4 != 0) return hipErrorInvalidValue;
+    if (!gather_gemm_accepts(p.SC, p.DC, bwdData, bm, bn)) return hipErrorInvalidValue;
     if (bwdData && p.DC % 4 != 0) {   // filter columns by 4-byte loads: on the narrow tile only
         if (bm == 128 && bn == 32) return launch_one<128, 32, 4, true, true, true>(p, grid, st);
         return hipErrorInvalidValue;

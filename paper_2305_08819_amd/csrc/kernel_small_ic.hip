@@ -154,21 +154,13 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_data_small_ic_kernel(const Sm
 hipError_t launch_bwd_data_small_ic(const SmallIcParams &p, hipStream_t st)
 {
     const int PR = kTR + p.FH - 1, PC = kTC + p.FW - 1;
-    if (PR * PC > kPRows || p.FH * p.FW * p.IC > 32 || p.IC > 4 || p.OC % kBK != 0) return hipErrorInvalidValue;
+    static_assert(kTR == 4 && kTC == 32 && kPRows == 224, "bwd_data_small_ic_accepts() states these tile sizes");
+    if (PR * PC > kPRows || !bwd_data_small_ic_accepts(p.IC, p.OC, p.FH, p.FW, 1, 1)) return hipErrorInvalidValue;
     const size_t smem = (size_t)(kPRows * LDA + 32 * LDA) * sizeof(float);
     static_assert(kPRows * kLDP <= kPRows * LDA, "P fits over the A tile");
-    auto kern = bwd_data_small_ic_kernel;
-    static bool attrSet[16] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= 16 || !attrSet[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        if (dev >= 0 && dev < 16) attrSet[dev] = true;
-    }
+    static_assert((size_t)(kPRows * LDA + 32 * LDA) * sizeof(float) <= 64 * 1024, "within the default dynamic LDS limit");
     const int grid = p.N * ((p.IH + kTR - 1) / kTR) * ((p.IW + kTC - 1) / kTC);
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), smem, st, p);
+    hipLaunchKernelGGL(bwd_data_small_ic_kernel, dim3((unsigned)grid), dim3(kThreads), smem, st, p);
     return hipGetLastError();
 }
 
@@ -293,7 +285,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_small_ic_kernel(const SmallIc
 
 hipError_t launch_fwd_small_ic(const SmallIcParams &p, hipStream_t st)
 {
-    if (p.FH * p.FW * p.IC > 32) return hipErrorInvalidValue;
+    if (!patch_small_ic_accepts(p.IC, p.FH, p.FW)) return hipErrorInvalidValue;
     const int grid = ((p.M + 127) / 128) * ((p.OC + 63) / 64);
     if (p.u8) hipLaunchKernelGGL(fwd_small_ic_kernel<true>, dim3((unsigned)grid), dim3(kThreads), 0, st, p);
     else hipLaunchKernelGGL(fwd_small_ic_kernel<false>, dim3((unsigned)grid), dim3(kThreads), 0, st, p);
@@ -330,12 +322,10 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_small_ic_kernel(const Small
     const int ch0 = (int)((long long)slice * chunksTotal / p.split), ch1 = (int)((long long)(slice + 1) * chunksTotal / p.split);
 
     constexpr int kOutOfRange = (int)0x80000000;
-    const __amdgpu_buffer_rsrc_t rsrcG =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.G), 0, (int)p.gBytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrcX =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.X), 0, (int)p.xBytes, 0x00020000);
 
-    // dY loader: 32 rows x 16 segments per stage, 2 per thread; rows past M are past the tensor and read zeros
+    // dY loader: 32 rows x 16 segments per stage, 2 per thread; rows past M read zeros (see gload)
     const int gSeg = tid & 15, gRow = tid >> 4;
     int gOff[2];
 #pragma unroll
@@ -356,10 +346,15 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_small_ic_kernel(const Small
             const int ch = chBase + s;
             const bool live = ch < ch1;      // uniform; stages past the slice load zeros
             const int m0 = ch * kBK;
+            // dY through a window that starts at the stage's first row and ends with the tensor (empty
+            // for stages past the slice): the range check of a raw buffer load covers the VGPR offset
+            // only, so this is what makes the rows past M of a partial last stage read zeros
+            const unsigned gStart = live ? (unsigned)m0 * (unsigned)p.OC * 4u : p.gBytes;
+            const __amdgpu_buffer_rsrc_t rsrcG = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<char *>(reinterpret_cast<const char *>(p.G)) + gStart, 0, (int)(p.gBytes - gStart), 0x00020000);
 #pragma unroll
             for (int i = 0; i < 2; ++i)
-                gg[s][i] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(
-                                                      rsrcG, live ? gOff[i] : kOutOfRange, live ? m0 * p.OC * 4 : 0, 0));
+                gg[s][i] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrcG, gOff[i], 0, 0));
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int m = m0 + xRow + 8 * i;
@@ -430,7 +425,7 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_small_ic_kernel(const Small
 
 hipError_t launch_wgrad_small_ic(const SmallIcParams &p, hipStream_t st)
 {
-    if (p.FH * p.FW * p.IC > 32 || p.split < 1) return hipErrorInvalidValue;
+    if (!patch_small_ic_accepts(p.IC, p.FH, p.FW) || p.split < 1) return hipErrorInvalidValue;
     constexpr size_t smem = (size_t)kSub * (kWsGStage + kWsXStage) * sizeof(float);
     static_assert(64 * 33 <= kSub * kWsGStage, "the reduction buffer fits over the dY stages");
     static_assert(smem <= 64 * 1024, "within the default dynamic LDS limit");

@@ -294,24 +294,36 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_kernel(const WgradParams p)
 template <int BM, int BN, bool XELEM>
 static hipError_t launch_one(const WgradParams &p, int grid, hipStream_t st)
 {
-    using T = WG<BM, BN>;
-    auto kern = wgrad_kernel<BM, BN, XELEM>;
-    static bool attrSet[16] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= 16 || !attrSet[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)T::SMEM_BYTES);
-        if (e != hipSuccess) return e;
-        if (dev >= 0 && dev < 16) attrSet[dev] = true;
-    }
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), T::SMEM_BYTES, st, p);
+    constexpr size_t kSmemBytes = WG<BM, BN>::SMEM_BYTES;
+    hipLaunchKernelGGL((wgrad_kernel<BM, BN, XELEM>), dim3((unsigned)grid), dim3(kThreads), kSmemBytes, st, p);
     return hipGetLastError();
+}
+
+// Tiles that need more LDS than a kernel gets by default (64 KB): limit raised once per device,
+// outside any stream capture (see prepare_device in the host API).
+template <int BM, int BN, bool XELEM>
+static hipError_t raise_lds_limit()
+{
+    constexpr size_t bytes = WG<BM, BN>::SMEM_BYTES;
+    if (bytes <= 64 * 1024) return hipSuccess;
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(wgrad_kernel<BM, BN, XELEM>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+hipError_t prepare_wgrad()
+{
+    hipError_t e = raise_lds_limit<128, 128, false>();
+    if (e == hipSuccess) e = raise_lds_limit<64, 128, false>();
+    if (e == hipSuccess) e = raise_lds_limit<128, 64, false>();
+    if (e == hipSuccess) e = raise_lds_limit<64, 64, false>();
+    if (e == hipSuccess) e = raise_lds_limit<128, 64, true>();
+    if (e == hipSuccess) e = raise_lds_limit<64, 64, true>();
+    return e;
 }
 
 hipError_t launch_wgrad(const WgradParams &p, int bm, int bn, bool xElem, int grid, hipStream_t st)
 {
+    if (!wgrad_accepts(p.N, p.IC, p.OC, p.posMajor, xElem, bm, bn)) return hipErrorInvalidValue;
     if (xElem) {   // narrow-channel layers: small tiles only
         if (bm == 64 && bn == 64) return launch_one<64, 64, true>(p, grid, st);
         if (bm == 128 && bn == 64) return launch_one<128, 64, true>(p, grid, st);

@@ -24,12 +24,6 @@
 // Accuracy: the accumulator is folded into a second one every `flushChunks` stages (512
 // products), so no fp32 chain is longer than that however long the slice is.
 #include <hip/hip_runtime.h>
-// -DMI355CONV_TIMELINE compiles in a per-workgroup timeline (constant-rate clock at five points,
-// the CU the workgroup ran on, shader cycles): the measurements behind the pipeline's design.
-#if defined(MI355CONV_TIMELINE)
-namespace mi355conv { __device__ unsigned long long g_wstamps[16384 * 8]; }
-#define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 16384) mi355conv::g_wstamps[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
-#endif
 #include "gather_common.h"
 
 namespace mi355conv {
@@ -61,15 +55,7 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
     float *Gs = reinterpret_cast<float *>(smem_raw);
     float *Xs = Gs + 2 * T::G_STAGE;
 
-    STAMP(0);
     const WgradView p = wgrad_view(params);
-#if defined(MI355CONV_TIMELINE)
-    if (threadIdx.x == 0 && blockIdx.x < 16384) {
-        g_wstamps[blockIdx.x * 8 + 5] = __builtin_amdgcn_s_getreg((31 << 11) | 4);    // HW_ID
-        g_wstamps[blockIdx.x * 8 + 6] = __builtin_amdgcn_s_getreg((31 << 11) | 20);   // XCC_ID
-    }
-    const long long expClk0 = clock64();
-#endif
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int tn, tmo, slice;
     if (PM && p.balance) {   // tiles enumerated tap by tap, taps with the most live positions first
@@ -96,8 +82,6 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
     int ch1 = (slice + 1) * chunksTotal / p.split;
 
     constexpr int kOutOfRange = (int)0x80000000;
-    const __amdgpu_buffer_rsrc_t rsrcG =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.G), 0, (int)p.gBytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrcX =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.X), 0, (int)p.xBytes, 0x00020000);
 
@@ -119,7 +103,8 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
         gVoff[i] = gOc < p.OC ? (pixel * p.OC + gOc) * 4 : kOutOfRange;
     }
     // X: element offset of the thread's part of the address; validity inputs.
-    // Rows past the last image need no test: their addresses lie past the end of X and of G.
+    // Rows past the last image need no test: their X addresses lie past the end of X (whole offset
+    // in the VGPR), and G is read through a per-stage window that ends with the tensor.
     int xPart[T::PX];
     int xWBase[WIDE ? T::PX : 1];           // WIDE: input column of the thread's tap when the stage starts at ow0 = 0
     int xHBase[T::PX];                      // !PM: input row relative to the stage's first one; far out of range
@@ -254,11 +239,17 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
     f4 ggS[2][T::PG], gxS[2][T::PX];
     constexpr int kItems = T::PG + T::PX;
     auto gload_item = [&](int q, f4 *gg, f4 *gx) __attribute__((always_inline)) {
-        // gSoff is uniform; saying so keeps it in an SGPR instead of a per-lane loop over its values
-        if (q < T::PG)
-            gg[q] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrcG, gVoff[q],
-                                                                                __builtin_amdgcn_readfirstlane(gSoff), 0));
-        else gx[q - T::PG] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrcX, xVoff[q - T::PG], 0, 0));
+        // The stage's rows of G are addressed through a descriptor that starts at the stage's first
+        // row and ends with the tensor: the range check of a raw buffer load covers the VGPR
+        // offset only, never the scalar offset, so a window that moves with the stage is what
+        // makes rows past the last one (a partial last stage) read zeros.  Scalar work only.
+        // gSoff is uniform; saying so keeps it in SGPRs instead of a per-lane loop over its values.
+        if (q < T::PG) {
+            const unsigned soff = (unsigned)__builtin_amdgcn_readfirstlane(gSoff);
+            const __amdgpu_buffer_rsrc_t rsrcG = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<char *>(reinterpret_cast<const char *>(p.G)) + soff, 0, (int)(p.gBytes - soff), 0x00020000);
+            gg[q] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrcG, gVoff[q], 0, 0));
+        } else gx[q - T::PG] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrcX, xVoff[q - T::PG], 0, 0));
     };
     auto lds_store_item = [&](int q, int buf, const f4 *gg, const f4 *gx) __attribute__((always_inline)) {
         if (q < T::PG)
@@ -354,7 +345,6 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
 
     // ---- main loop over the live stages of this slice --------------------------------------------
     // c0 is multiplied now, c1 sits in registers (other set), c2 is loaded during this stage.
-    STAMP(1);
     int c0 = next_live(ch0);
     if (c0 < ch1) {
         set_stage(c0);
@@ -371,7 +361,6 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
         __syncthreads();
 #pragma unroll
         for (int s = 0; s < kAhead; ++s) read_step(0, s, fa[s], fb[s]);
-        STAMP(2);
         // c0 is in LDS buffer 0, c1 in register set 1, c2 is the chunk the next stage loads (its
         // offsets are set), c3 the one after.
         int c2 = next_live(c1 + 1);
@@ -405,7 +394,6 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
         }
     }
 
-    STAMP(3);
     float *C = p.C + (long long)slice * p.sliceStride;
 #pragma unroll
     for (int i = 0; i < T::MB; ++i)
@@ -418,43 +406,47 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
                 if (oc < p.OC && col < Ktot) C[oc * Ktot + col] = acc2[i][j][r] + acc[i][j][r];
             }
         }
-    STAMP(4);
-#if defined(MI355CONV_TIMELINE)
-    if (threadIdx.x == 0 && blockIdx.x < 16384) g_wstamps[blockIdx.x * 8 + 7] = clock64() - expClk0;
-#endif
 }
-
-#if defined(MI355CONV_TIMELINE)
-extern "C" int exp_read_wstamps(unsigned long long *host, size_t count)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_wstamps), count * sizeof(unsigned long long));
-}
-#endif
 
 template <int BM, int BN, bool PM, bool WIDE = false>
 static hipError_t launch_fast_one(const WgradParams &p, int grid, hipStream_t st)
 {
-    using T = WF<BM, BN>;
-    auto kern = wgrad_fast_kernel<BM, BN, PM, WIDE>;
-    static bool attrSet[16] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= 16 || !attrSet[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)T::SMEM_BYTES);
-        if (e != hipSuccess) return e;
-        if (dev >= 0 && dev < 16) attrSet[dev] = true;
-    }
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), T::SMEM_BYTES, st, p);
+    constexpr size_t kSmemBytes = WF<BM, BN>::SMEM_BYTES;
+    hipLaunchKernelGGL((wgrad_fast_kernel<BM, BN, PM, WIDE>), dim3((unsigned)grid), dim3(kThreads), kSmemBytes, st, p);
     return hipGetLastError();
+}
+
+// Tiles that need more LDS than a kernel gets by default (64 KB): limit raised once per device,
+// outside any stream capture (see prepare_device in the host API).
+template <int BM, int BN>
+static hipError_t raise_lds_limit()
+{
+    constexpr size_t bytes = WF<BM, BN>::SMEM_BYTES;
+    if (bytes <= 64 * 1024) return hipSuccess;
+    const void *kerns[3] = {reinterpret_cast<const void *>(wgrad_fast_kernel<BM, BN, false, false>),
+                            reinterpret_cast<const void *>(wgrad_fast_kernel<BM, BN, true, false>),
+                            reinterpret_cast<const void *>(wgrad_fast_kernel<BM, BN, false, true>)};
+    for (const void *k : kerns) {
+        const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t prepare_wgrad_fast()
+{
+    hipError_t e = raise_lds_limit<128, 128>();
+    if (e == hipSuccess) e = raise_lds_limit<64, 128>();
+    if (e == hipSuccess) e = raise_lds_limit<128, 64>();
+    if (e == hipSuccess) e = raise_lds_limit<64, 64>();
+    if (e == hipSuccess) e = raise_lds_limit<32, 128>();
+    return e;
 }
 
 hipError_t launch_wgrad_fast(const WgradParams &p, int bm, int bn, int grid, hipStream_t st)
 {
-    if (p.posMajor && (p.N % kBK != 0 || p.OH * p.OW > 64)) return hipErrorInvalidValue;
-    const bool wide = p.OW > kBK;   // a multiple of 32 (host guarantees), row-major order only
-    if (wide && (p.posMajor || p.OW % kBK != 0)) return hipErrorInvalidValue;
+    if (!wgrad_fast_accepts(p.N, p.OH, p.OW, p.IC, p.OC, p.posMajor, bm, bn)) return hipErrorInvalidValue;
+    const bool wide = p.OW > kBK;   // then a multiple of 32, (n,oh,ow) order only
 #define MI355CONV_WF(BM_, BN_)                                                        \
     if (bm == BM_ && bn == BN_) {                                                     \
         if (wide) return launch_fast_one<BM_, BN_, false, true>(p, grid, st);         \

@@ -153,3 +153,78 @@ def test_longest_first_dealing_is_a_permutation_and_balances(lib):
     assert mc.conv2d_query_workgroup(mc.OP_FWD, d, 5) == (5, 1)
     with pytest.raises(mc.Mi355ConvError):
         mc.conv2d_query_workgroup(mc.OP_FWD, d, 1 << 20)
+
+
+def _launcher_takes(op, d, pl):
+    """The launchers' preconditions, restated from their documentation (not from the planner)."""
+    ohow = d.OH * d.OW
+    tile = (pl.tile_m, pl.tile_n)
+    if pl.kernel == mc.KERNEL_DIRECT:
+        return True
+    if pl.kernel == mc.KERNEL_FIRST_LAYER:
+        ok = d.FH * d.FW * d.IC <= 32
+        if op == mc.OP_BWD_DATA:
+            ok = ok and d.sh == 1 and d.sw == 1 and d.IC <= 4 and d.OC % 32 == 0 and (d.FH + 3) * (d.FW + 31) <= 224
+        return ok
+    if pl.kernel == mc.KERNEL_WGRAD_FAST:
+        narrow = 32 % d.OW == 0 and (ohow % 32 == 0 or 32 % ohow == 0)
+        wide = d.OW > 32 and d.OW % 32 == 0
+        if not (narrow or wide) or d.IC % 4 or d.OC % 4:
+            return False
+        if pl.pos_major and (wide or d.N % 32 or ohow > 64):
+            return False
+        return tile in ((128, 128), (64, 128), (128, 64), (64, 64), (32, 128))
+    if pl.kernel == mc.KERNEL_WGRAD:
+        if d.OC % 4:
+            return False
+        if d.IC % 4:
+            return not pl.pos_major and tile in ((64, 64), (128, 64))
+        if pl.pos_major and d.N % 32:
+            return False
+        return tile in ((128, 128), (64, 128), (128, 64), (64, 64))
+    if pl.pos_major and d.N % pl.tile_m:
+        return False
+    if pl.kernel == mc.KERNEL_GATHER_ELEM:
+        return tile in ((128, 64), (64, 64), (128, 32))
+    src, dst = (d.OC, d.IC) if op == mc.OP_BWD_DATA else (d.IC, d.OC)
+    if src % 4:
+        return False
+    if op == mc.OP_BWD_DATA and dst % 4:
+        return tile == (128, 32)
+    return tile in ((128, 128), (128, 64), (64, 64), (128, 32))
+
+
+def test_every_plan_is_one_its_launcher_takes(lib):
+    """Sweep of shapes x overrides through the host-only planner: every plan must meet the
+    preconditions of the launcher it names (a plan that does not would surface as a launch
+    error on the GPU).  Includes one-row maps of 64 pixels, where (oh,ow,n) order and the
+    wide-row backward-weight kernel used to be planned together."""
+    import itertools
+    shapes = []
+    for n, (ih, iw), ic, oc, (f, s_, p) in itertools.product(
+            (1, 3, 32, 128), ((1, 64), (2, 2), (4, 4), (8, 8), (16, 16), (5, 7), (1, 128), (2, 32), (32, 32), (3, 96)),
+            (3, 4, 6, 16, 48, 64), (4, 10, 32, 48, 160),
+            ((1, 1, 0), (3, 1, 1), (3, 2, 1), (5, 1, 2), ((1, 3), 1, (0, 1)), ((3, 1), (2, 1), (1, 0)))):
+        shapes.append((n, ih, iw, ic, oc) + ((f, f) if isinstance(f, int) else f) + (s_, p))
+    overrides = [(0, 0, -1, 0), (0, 0, 1, 0), (0, 0, 0, 3), (128, 128, 1, 2), (32, 128, -1, 0), (128, 64, -1, 5)]
+    checked = 0
+    try:
+        for bm, bn, pm, split in overrides:
+            mc.conv2d_set_tile(bm, bn, pm)
+            mc.conv2d_set_tuning(mc.VARIANT_AUTO, split)
+            for shp in shapes:
+                d = mc.make_desc(*shp)
+                if d.OH <= 0 or d.OW <= 0:
+                    continue
+                for op in (mc.OP_FWD, mc.OP_BWD_DATA, mc.OP_BWD_WEIGHT):
+                    pl = mc.conv2d_query_plan(op, d)       # raises if the library itself finds the plan unlaunchable
+                    assert _launcher_takes(op, d, pl), (shp, op, (bm, bn, pm, split), pl.kernel, pl.tile_m, pl.tile_n, pl.pos_major)
+                    assert pl.split >= 1 and (pl.grid >= 1 or pl.kernel == mc.KERNEL_DIRECT)
+                    checked += 1
+    finally:
+        mc.conv2d_set_tile(0, 0, -1)
+        mc.conv2d_set_tuning(mc.VARIANT_AUTO, 0)
+    assert checked > 10000
+    # the shape that used to get an unlaunchable plan
+    pl = mc.conv2d_query_plan(mc.OP_BWD_WEIGHT, mc.make_desc(32, 1, 64, 64, 64, 3, 3, 1, 1))
+    assert pl.kernel == mc.KERNEL_WGRAD_FAST and pl.pos_major == 0

@@ -206,6 +206,96 @@ def test_mfma_variant_shapes(shp, split):
     gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), label=str(shp))
 
 
+# ---- every compiled tile, forced ---------------------------------------------------------------
+# The planner rarely leaves the 64x64 tile on small problems, so each compiled (tile, row order,
+# loader) instantiation is forced here through conv2d_set_tile / conv2d_set_tuning, the plan is
+# checked to be the forced one, and the result is compared with the oracle.
+GATHER_TILES = [(128, 128), (128, 64), (64, 64), (128, 32)]
+GATHER_FORCED_SHAPES = [
+    (128, 4, 4, 64, 160, 3, 3, 1, 1),     # channels on the 32-grid, ragged column tiles, (y,x,n) order possible
+    (128, 3, 5, 48, 72, 3, 3, 1, 1),      # channel counts off the 32-grid: partly empty last stage per tap
+    (128, 6, 6, 32, 64, 3, 3, 2, 1),      # stride phases in backward-data
+    (5, 9, 7, 32, 96, 3, 3, 1, 1),        # ragged row tiles (315 rows), (n,y,x) order only
+]
+
+
+@pytest.mark.parametrize("split", [1, 3])
+@pytest.mark.parametrize("pm", [0, 1])
+@pytest.mark.parametrize("tile", GATHER_TILES, ids=lambda t: "%dx%d" % t)
+@pytest.mark.parametrize("shp", GATHER_FORCED_SHAPES)
+def test_forced_gather_tiles(shp, tile, pm, split):
+    d = mc.make_desc(*shp)
+    if pm and d.N % tile[0] != 0:
+        pytest.skip("(y,x,n) order needs a batch that is a multiple of the row tile")
+    say("forced gather %s tile %s pm %d split %d" % (shp, tile, pm, split))
+    mc.conv2d_set_tuning(mc.VARIANT_MFMA, split)
+    mc.conv2d_set_tile(tile[0], tile[1], pm)
+    for op in (mc.OP_FWD, mc.OP_BWD_DATA):
+        pl = mc.conv2d_query_plan(op, d)
+        assert pl.kernel == mc.KERNEL_GATHER and (pl.tile_m, pl.tile_n) == tile, (op, pl.tile_m, pl.tile_n)
+        # a forced slice count is clamped to half the tile's stages
+        assert pl.pos_major == pm and (pl.split == split or 1 < pl.split < split), (op, pl.pos_major, pl.split)
+    gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), ops=("fwd", "bwd_data"), label=str(shp))
+
+
+WGRAD_TILES = [(128, 128), (64, 128), (128, 64), (64, 64), (32, 128)]
+# shape, row order, kernel family the plan must name
+WGRAD_FORCED_SHAPES = [
+    ((8, 8, 8, 64, 160, 3, 3, 1, 1), 0, "fast"),       # aligned map, (n,oh,ow) order, ragged tiles both ways
+    ((64, 4, 4, 64, 160, 3, 3, 1, 1), 1, "fast"),      # (oh,ow,n) order with stage skipping
+    ((2, 4, 64, 16, 160, 3, 3, 1, 1), 0, "fast"),      # wide rows (OW = 64)
+    ((3, 4, 4, 16, 32, 3, 3, 1, 1), 0, "fast"),        # 48 rows: the last 32-row stage is half empty
+    ((5, 8, 4, 8, 16, 3, 3, 1, 1), 0, "fast"),         # 160 rows, five stages
+    ((3, 7, 5, 32, 160, 3, 3, 1, 1), 0, "generic"),    # map the fast kernel does not take
+    ((32, 3, 3, 64, 96, 3, 3, 1, 1), 1, "generic"),    # (oh,ow,n) order in the generic kernel
+    ((4, 8, 8, 6, 160, 3, 3, 1, 1), 0, "elem"),        # input channels not a multiple of 4
+]
+
+
+@pytest.mark.parametrize("split", [1, 3])
+@pytest.mark.parametrize("tile", WGRAD_TILES, ids=lambda t: "%dx%d" % t)
+@pytest.mark.parametrize("case", WGRAD_FORCED_SHAPES, ids=lambda c: "%s-%s" % (c[2], "x".join(map(str, c[0][:5]))))
+def test_forced_wgrad_tiles(case, tile, split):
+    shp, pm, family = case
+    if tile == (32, 128) and family != "fast":
+        pytest.skip("the one-block-row tile exists in the fast kernel only")
+    if family == "elem" and tile[1] != 64:
+        pytest.skip("the element-wise X loader is compiled for 64-wide tiles")
+    say("forced wgrad %s %s tile %s split %d" % (shp, family, tile, split))
+    d = mc.make_desc(*shp)
+    mc.conv2d_set_tuning(mc.VARIANT_MFMA, split)
+    mc.conv2d_set_tile(tile[0], tile[1], pm)
+    pl = mc.conv2d_query_plan(mc.OP_BWD_WEIGHT, d)
+    assert pl.kernel == (mc.KERNEL_WGRAD_FAST if family == "fast" else mc.KERNEL_WGRAD)
+    assert (pl.tile_m, pl.tile_n) == tile and pl.pos_major == pm
+    assert pl.split == split or (split > 1 and 1 <= pl.split < split), pl.split   # clamped to half the stages
+    gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), ops=("bwd_weight",), label=str(shp))
+
+
+# partial last stage of the first-layer backward-weight kernel (rows not a multiple of 32, more than 32)
+@pytest.mark.parametrize("shp", [(3, 9, 9, 3, 32, 3, 3, 2, 1), (7, 5, 5, 1, 64, 3, 3, 1, 1), (1, 10, 10, 3, 96, 3, 3, 1, 1)])
+@pytest.mark.parametrize("split", [1, 2])
+def test_bwd_weight_small_ic_partial_last_stage(shp, split):
+    say("small-ic wgrad partial stage %s split=%d" % (shp, split))
+    d = mc.make_desc(*shp)
+    assert (d.N * d.OH * d.OW) % 32 != 0 and d.N * d.OH * d.OW > 32
+    mc.conv2d_set_tuning(mc.VARIANT_MFMA, split)
+    assert mc.conv2d_query_plan(mc.OP_BWD_WEIGHT, d).kernel == mc.KERNEL_FIRST_LAYER
+    gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), ops=("bwd_weight",), label=str(shp))
+
+
+def test_bwd_weight_one_row_wide_map_keeps_row_major_order():
+    """An output map of one row of 64 pixels is small enough for (oh,ow,n) order, but the fast
+    kernel's wide-row variant runs in (n,oh,ow) order only: the plan must say so and run."""
+    d = mc.make_desc(32, 1, 64, 64, 64, 3, 3, 1, 1)
+    pl = mc.conv2d_query_plan(mc.OP_BWD_WEIGHT, d)
+    assert pl.kernel == mc.KERNEL_WGRAD_FAST and pl.pos_major == 0
+    gu.check_all_ops(d, *small_inputs(d, 99), label="1x64 map")
+    d = mc.make_desc(32, 1, 64, 16, 32, 1, 3, 1, (0, 1))
+    assert mc.conv2d_query_plan(mc.OP_BWD_WEIGHT, d).pos_major == 0
+    gu.check_all_ops(d, *small_inputs(d, 98), label="1x64 map, 1x3 filter")
+
+
 def test_mfma_and_direct_agree_with_plan_defaults():
     d = mc.make_desc(2, 9, 9, 64, 32, 3, 3, 1, 1)
     gu.check_all_ops(d, *small_inputs(d, 7))
@@ -476,5 +566,6 @@ def test_configuration_layers_full_size(layer):
     d = gu.desc_of(layer)
     # the VGG-16 stack takes its activations from a chain through the oracle (conv, ReLU, pooling)
     t = gu.vgg_chain_inputs(layer) if layer in wl.CFG5 else wl.make_inputs(layer)
-    stats = gu.check_all_ops(d, t["X"], t["W"], t["G"], label=layer.name)
+    # every operator runs twice: results must be bitwise reproducible
+    stats = gu.check_all_ops(d, t["X"], t["W"], t["G"], label=layer.name, twice=True)
     say("  %s" % {k: "rel=%.2e max=%.2e" % v for k, v in stats.items()})

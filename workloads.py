@@ -110,6 +110,19 @@ class Layer:
         return 2 * self.M * self.OC * self.K
 
     @property
+    def in_range_share(self) -> float:
+        """Share of the (output position, filter tap) pairs whose tap lies inside the image: the
+        part of the nominal multiplies that is not a multiplication by padding."""
+        rows = sum(1 for q in range(self.OH) for f in range(self.FH) if 0 <= q * self.stride - self.pad + f < self.IH)
+        cols = sum(1 for q in range(self.OW) for f in range(self.FW) if 0 <= q * self.stride - self.pad + f < self.IW)
+        return rows * cols / float(self.OH * self.OW * self.FH * self.FW)
+
+    @property
+    def effective_flops(self) -> float:
+        """FLOP of one operator over in-range taps only (what a kernel that skips padding executes at least)."""
+        return self.flops * self.in_range_share
+
+    @property
     def x_shape(self):
         return (self.N, self.IH, self.IW, self.IC)
 
