@@ -2,15 +2,17 @@
 """Benchmark of the fp32 convolution hot path on one MI355X.
 
 A step is one pass of the whole hot path over one batch of synthetic input: forward,
-backward-data and backward-weight of one layer, enqueued back to back on one stream with
-inputs resident in HBM.  The default workload is the ResNet-style down-sampling layer
-(N=128, 32x32x64 -> 16x16x128, 3x3, stride 2, pad 1).  Prints ONE JSON line on stdout.
+backward-data and backward-weight of every layer of the workload, enqueued back to back on one
+stream with inputs resident in HBM.  The default workload is the largest configuration, the
+VGG-16-shaped stack (13 layers of 3x3 convolutions, N=128: 39 operators per step).  Prints ONE
+JSON line on stdout.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|C2|...] [--no-cpu-baseline]
   python bench.py --table [cfg2 cfg3 ...] [--with-oracle]   per-layer, per-operator table (stderr + JSON line)
-  python bench.py --workload cfg5           a whole configuration back to back (VGG-16: 39 operators per step)
+  python bench.py --workload cfg5 --graph   the step captured once into a HIP graph and replayed
   python bench.py --regret C2,V8            planner pick against an exhaustive tile / order / slice sweep
   python bench.py --streams                 independent operators on separate streams vs one stream
+  python bench.py --mfma-peak               register-only fp32 MFMA loop: the matrix rate the chip sustains
 """
 from __future__ import annotations
 
@@ -27,15 +29,35 @@ sys.path.insert(0, ROOT)
 
 import workloads as wl  # noqa: E402
 
+METRIC = "TFLOP/s and % FP32 MFMA peak per conv op (fwd/dgrad/wgrad), CIFAR shapes"
 PEAK_FP32_MFMA_TFLOPS = 157.3   # 256 CU x 256 FLOP/clk x 2.4 GHz (published dense fp32 matrix peak)
 PEAK_HBM_GBS = 8000.0
 OPS = ("fwd", "bwd_data", "bwd_weight")
-# HBM bytes per operator launch of the default workload (C2), from FETCH_SIZE + WRITE_SIZE scaled by a
-# 256 MiB copy (profiles/bench_C2_kernel_trace.md); bwd_weight = main kernel + slice reduce.
-MEASURED_TRAFFIC_BYTES = {"C2": {"fwd": 56.3e6 + 16.8e6, "bwd_data": 43.0e6 + 33.6e6,
-                                 "bwd_weight": 84.4e6 + 8.3e6 + 8.3e6 + 0.3e6}}
-KERNEL_OF_OP = {"fwd": "gather_gemm_kernel<fwd>", "bwd_data": "gather_gemm_kernel<bwd_data>",
-                "bwd_weight": "wgrad_fast_kernel + slice_reduce_kernel"}
+# HBM bytes per launch of each kernel, written from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this
+# same command (the summary beside it gives the commands and the copy calibration)
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "bench_cfg5_hbm_traffic.json")
+
+
+def kernel_name(layer, op, plan, mc):
+    """Name of the main kernel a plan launches, spelled as rocprofv3 prints it."""
+    b = lambda v: "true" if v else "false"   # noqa: E731
+    t = (plan.tile_m, plan.tile_n)
+    if plan.kernel == mc.KERNEL_DIRECT:
+        return "direct_%s_kernel" % op
+    if plan.kernel == mc.KERNEL_FIRST_LAYER:
+        return {"fwd": "fwd_small_ic_kernel<false>", "bwd_data": "bwd_data_small_ic_kernel",
+                "bwd_weight": "wgrad_small_ic_kernel"}[op]
+    if plan.kernel == mc.KERNEL_WGRAD_FAST:
+        return "wgrad_fast_kernel<%d, %d, %s, %s>" % (t + (b(plan.pos_major), b(layer.OW > 32)))
+    if plan.kernel == mc.KERNEL_WGRAD:
+        return "wgrad_kernel<%d, %d, %s>" % (t + (b(layer.IC % 4),))
+    bwd = op == "bwd_data"
+    waves_m = 4 if plan.tile_n == 32 else 2
+    if plan.kernel == mc.KERNEL_GATHER_ELEM:
+        return "gather_elem_kernel<%d, %d, %d, %s>" % (t + (waves_m, b(bwd)))
+    src, dst = (layer.OC, layer.IC) if bwd else (layer.IC, layer.OC)
+    belem = bwd and dst % 4 != 0
+    return "gather_gemm_kernel<%d, %d, %d, %s, %s, %s>" % (t + (waves_m, b(bwd), b(belem), b(belem or src % 32 != 0)))
 
 
 def log(*a):
@@ -100,35 +122,39 @@ class LayerRunner:
             out.append(e0.elapsed_time(e1) / launches)
         return sorted(out)[len(out) // 2]
 
-    def spin_up(self, seconds=0.2):
+    def spin_up(self, seconds=0.2, step=None):
         """Keep the GPU busy until its clock governor has settled: the shader clock climbs for
         tens of milliseconds after an idle period, and kernels timed before that run 10-15 % slow."""
+        step = step or self.step
         t0 = time.perf_counter()
         while time.perf_counter() - t0 < seconds:
-            for _ in range(20):
-                self.step()
+            for _ in range(5):
+                step()
             self.torch.cuda.synchronize()
 
 
-def cpu_baseline(layer, host, min_seconds=12.0):
-    """The oracle as it stands, timed on the host cores on the same layer (all three operators),
-    repeated until about min_seconds of wall time have passed."""
+def cpu_baseline(runners, budget_seconds=25.0):
+    """The oracle as it stands, timed on the host cores: one pass of all three operators over the
+    workload's layers at full size, in layer order, stopping after the layer during which the
+    budget runs out (a bounded sample; what was covered is stated)."""
     import oracle
-    s, p = layer.stride, layer.pad
-    repeats = 0
+    flop, done = 0, []
     t0 = time.perf_counter()
-    while True:
+    for r in runners:
+        l, host = r.layer, r.host
+        s, p = l.stride, l.pad
         oracle.conv2d_fwd(host["X"], host["W"], s, p)
-        oracle.conv2d_bwd_data(host["G"], host["W"], (layer.IH, layer.IW), s, p)
-        oracle.conv2d_bwd_weight(host["X"], host["G"], (layer.FH, layer.FW), s, p)
-        repeats += 1
-        dt = time.perf_counter() - t0
-        if dt >= min_seconds or repeats >= 200:
+        oracle.conv2d_bwd_data(host["G"], host["W"], (l.IH, l.IW), s, p)
+        oracle.conv2d_bwd_weight(host["X"], host["G"], (l.FH, l.FW), s, p)
+        flop += 3 * l.flops
+        done.append(l.name)
+        if time.perf_counter() - t0 >= budget_seconds:
             break
-    return {"value": round(3 * layer.flops * repeats / dt / 1e12, 6), "unit": "TFLOP/s",
-            "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "%d x (fwd+bwd_data+bwd_weight) of %s at full size, %.1f s wall"
-                      % (repeats, layer.name, dt)}
+    dt = time.perf_counter() - t0
+    what = "all %d layers" % len(done) if len(done) == len(runners) else "layers %s..%s" % (done[0], done[-1])
+    return {"value": round(flop / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "one pass of fwd+bwd_data+bwd_weight over %s at full size, %.1f nominal GFLOP in %.1f s wall"
+                      % (what, flop / 1e9, dt)}
 
 
 def op_bytes(l, op):
@@ -140,16 +166,17 @@ def op_bytes(l, op):
 
 
 def oracle_ms(layer, host, op):
+    """(milliseconds, result) of the CPU oracle for one operator at full size."""
     import oracle
     s, p = layer.stride, layer.pad
     t0 = time.perf_counter()
     if op == "fwd":
-        oracle.conv2d_fwd(host["X"], host["W"], s, p)
+        ref = oracle.conv2d_fwd(host["X"], host["W"], s, p)
     elif op == "bwd_data":
-        oracle.conv2d_bwd_data(host["G"], host["W"], (layer.IH, layer.IW), s, p)
+        ref = oracle.conv2d_bwd_data(host["G"], host["W"], (layer.IH, layer.IW), s, p)
     else:
-        oracle.conv2d_bwd_weight(host["X"], host["G"], (layer.FH, layer.FW), s, p)
-    return (time.perf_counter() - t0) * 1e3
+        ref = oracle.conv2d_bwd_weight(host["X"], host["G"], (layer.FH, layer.FW), s, p)
+    return (time.perf_counter() - t0) * 1e3, ref
 
 
 def table(mc, torch, cfg_names, with_oracle=False, with_epilogue=False):
@@ -159,8 +186,8 @@ def table(mc, torch, cfg_names, with_oracle=False, with_epilogue=False):
     rows = []
     seen = set()
     ridge = PEAK_FP32_MFMA_TFLOPS * 1e3 / PEAK_HBM_GBS          # FLOP per byte
-    log("%-5s %-10s %9s %9s %7s %7s %9s %10s  %s" % ("layer", "op", "ms", "TFLOP/s", "%peak", "GB/s",
-                                                     "cold ms", "oracle ms", "plan"))
+    log("%-5s %-10s %9s %9s %7s %9s %7s %7s %9s %10s %9s %9s  %s"
+        % ("layer", "op", "ms", "TFLOP/s", "%peak", "eff TF/s", "%peak", "GB/s", "cold ms", "oracle ms", "rel-L2", "max-abs", "plan"))
     for cfg in cfg_names:
         for layer in wl.CONFIGS[cfg]:
             if layer.name in seen:
@@ -185,24 +212,33 @@ def table(mc, torch, cfg_names, with_oracle=False, with_epilogue=False):
                         state["i"] = (state["i"] + 1) % len(sets)
                         sets[state["i"]].run(op)
                     cold = r.event_ms(rotate)
-                tf = layer.flops / ms / 1e9
+                tf, tfe = layer.flops / ms / 1e9, layer.effective_flops / ms / 1e9
                 pl = r.plans[op]
                 plan = "v%d %dx%d s%d pm%d g%d" % (pl.variant, pl.tile_m, pl.tile_n, pl.split,
                                                    pl.pos_major, pl.grid)
                 gbs = op_bytes(layer, op) / ms / 1e6
-                oms = None
                 rows.append({"layer": layer.name, "op": op, "ms": round(ms, 5), "tflops": round(tf, 2),
                              "pct_peak": round(100 * tf / PEAK_FP32_MFMA_TFLOPS, 1),
+                             "tflops_effective": round(tfe, 2),
+                             "pct_peak_effective": round(100 * tfe / PEAK_FP32_MFMA_TFLOPS, 1),
                              "gbs": round(gbs, 1), "cold_ms": None if cold is None else round(cold, 5),
                              "cold_gbs": None if cold is None else round(op_bytes(layer, op) / cold / 1e6, 1),
-                             "oracle_ms": None if oms is None else round(oms, 2), "plan": plan})
-                log("%-5s %-10s %9.4f %9.2f %7.1f %7.0f %9s %10s  %s"
-                    % (layer.name, op, ms, tf, 100 * tf / PEAK_FP32_MFMA_TFLOPS, gbs,
-                       "-" if cold is None else "%.4f" % cold, "-" if oms is None else "%.1f" % oms, plan))
+                             "oracle_ms": None, "rel_l2": None, "max_abs": None, "plan": plan})
             if with_oracle:      # after the layer's GPU timing, so that it does not cool the clocks in between
                 for row in rows[-len(OPS):]:
-                    row["oracle_ms"] = round(oracle_ms(layer, r.host, row["op"]), 2)
-                    log("%-5s %-10s oracle %.1f ms" % (layer.name, row["op"], row["oracle_ms"]))
+                    oms, ref = oracle_ms(layer, r.host, row["op"])
+                    got = {"fwd": r.Y, "bwd_data": r.dX, "bwd_weight": r.dW}[row["op"]].cpu().numpy().astype(np.float64)
+                    diff = got - ref
+                    row["oracle_ms"] = round(oms, 2)
+                    row["rel_l2"] = float("%.3g" % (np.linalg.norm(diff.ravel()) / np.linalg.norm(ref.ravel())))
+                    row["max_abs"] = float("%.3g" % np.abs(diff).max())
+            for row in rows[-len(OPS):]:
+                log("%-5s %-10s %9.4f %9.2f %7.1f %9.2f %7.1f %7.0f %9s %10s %9s %9s  %s"
+                    % (row["layer"], row["op"], row["ms"], row["tflops"], row["pct_peak"], row["tflops_effective"],
+                       row["pct_peak_effective"], row["gbs"], "-" if row["cold_ms"] is None else "%.4f" % row["cold_ms"],
+                       "-" if row["oracle_ms"] is None else "%.1f" % row["oracle_ms"],
+                       "-" if row["rel_l2"] is None else "%.2e" % row["rel_l2"],
+                       "-" if row["max_abs"] is None else "%.2e" % row["max_abs"], row["plan"]))
             if with_epilogue:   # forward with bias + leaky-ReLU in the epilogue, against the plain forward
                 bias = torch.zeros(layer.OC, dtype=torch.float32, device="cuda")
                 ms = r.event_ms(lambda: mc.conv2d_fwd_bias_act(r.X, r.W, bias, r.Y, r.desc, 0.01, ws=r.ws))
@@ -336,15 +372,20 @@ def regret_report(mc, torch, names):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1000)
-    ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg5", help="a configuration (cfg1..cfg8) or one layer (C2, V9, ...)")
+    ap.add_argument("--no-op-events", action="store_true",
+                    help="skip the per-operator event timing behind the timed region (no per_op / roofline in the output)")
+    ap.add_argument("--op-reps", type=int, default=50, help="launches per event-timed batch of one operator")
+    ap.add_argument("--mfma-peak", action="store_true",
+                    help="register-only fp32 MFMA loop with 0..96 interleaved VALU instructions per 8 MFMAs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--table", nargs="*", default=None, metavar="CFG")
     ap.add_argument("--regret", default=None, metavar="LAYER,LAYER",
                     help="planner pick against an exhaustive sweep of tiles, row orders and slice counts")
     ap.add_argument("--graph", action="store_true",
-                    help="with --workload cfgN: capture one step into a HIP graph and time its replay")
+                    help="capture one step into a HIP graph and time its replay (no per-operator events)")
     ap.add_argument("--streams", action="store_true",
                     help="independent operators on separate streams vs one stream (inception branches, "
                          "backward-data next to backward-weight)")
@@ -389,96 +430,165 @@ def main():
         print(json.dumps({"table": rows}))
         return
 
-    if args.workload in wl.CONFIGS:
-        # a whole configuration back to back on one stream (e.g. cfg5: the 39 operators of VGG-16)
-        layers = wl.CONFIGS[args.workload]
-        rs = [LayerRunner(l, mc, torch, random_fill=True) for l in layers]
-        rs[0].spin_up()
-
-        def stack():
-            for r in rs:
-                r.step()
-        for _ in range(max(args.warmup // 10, 5)):
-            stack()
-        steps = max(args.steps // 10, 10)
-        run = stack
-        if args.graph:
-            # the library only enqueues kernels (no allocation, no memset, no synchronisation), so a
-            # whole step can be captured once and replayed with one launch
-            side = torch.cuda.Stream()
-            side.wait_stream(torch.cuda.current_stream())
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.stream(side):
-                stack()                              # first call on this stream outside the capture
-                torch.cuda.synchronize()
-                with torch.cuda.graph(graph, stream=side):
-                    stack()
-            torch.cuda.synchronize()
-            run = graph.replay
-            for _ in range(5):
-                run()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            run()
-        torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) * 1e3 / steps
-        flop = 3 * sum(l.flops for l in layers)
-        print(json.dumps({"metric": "TFLOP/s and % FP32 MFMA peak per conv op (fwd/dgrad/wgrad), CIFAR shapes",
-                          "value": round(flop / ms / 1e9, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": steps,
-                          "ms_per_step": round(ms, 5), "higher_is_better": True, "dtype": "f32", "data": "synthetic",
-                          "config": {"workload": "%s: %d layers x (fwd+bwd_data+bwd_weight) back to back on one stream%s"
-                                                 % (args.workload, len(layers), ", replayed as one HIP graph" if args.graph else ""),
-                                     "flop_per_step": flop,
-                                     "pct_fp32_mfma_peak": round(100 * flop / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 2)}}))
+    if args.mfma_peak:
+        print(json.dumps({"mfma_peak": mfma_peak_report(mc, torch)}))
         return
 
-    layer = {l.name: l for l in wl.all_layers()}[args.workload]
-    r = LayerRunner(layer, mc, torch)
+    layers = wl.CONFIGS[args.workload] if args.workload in wl.CONFIGS else \
+        [{l.name: l for l in wl.all_layers()}[args.workload]]
+    rs = [LayerRunner(l, mc, torch, random_fill=True) for l in layers]
+    items = [(r, op) for r in rs for op in OPS]           # the launch order of a step
 
-    r.spin_up()          # clock governor settled before anything is timed
-    for _ in range(args.warmup):
-        r.step()
+    def step():
+        for r, op in items:
+            r.run(op)
+
+    rs[0].spin_up(step=step)     # clock governor settled before anything is timed
+    steps, warmup = args.steps, args.warmup
+    run = step
+    if args.graph:
+        # the library only enqueues kernels (no allocation, no memset, no synchronisation), so a
+        # whole step can be captured once and replayed with one launch
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step()                                   # first call on this stream outside the capture
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.synchronize()
+        run = graph.replay
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+
+    # ---- the timed region: exactly `steps` steps between two synchronisations ------------------------
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        r.step()
+    e0.record()
+    for _ in range(steps):
+        run()
+    e1.record()
     torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_step = dt * 1e3 / args.steps
-    value = 3 * layer.flops / (ms_step * 1e-3) / 1e12
+    ms_step = (time.perf_counter() - t0) * 1e3 / steps
+    ms_step_events = e0.elapsed_time(e1) / steps
+    flop_step = 3 * sum(l.flops for l in layers)
+    eff_step = 3 * sum(l.effective_flops for l in layers)
+    value = flop_step / ms_step / 1e9
 
-    # per-operator event timing (each operator alone on the launch stream); the slowest is the
-    # dominant kernel of the step
-    per_op = {op: r.event_ms(lambda op=op: r.run(op)) for op in OPS}
-    dom = max(per_op, key=per_op.get)
-    achieved = layer.flops / per_op[dom] / 1e9
+    # ---- per-operator durations, right behind the timed region (clocks still settled) -----------------
+    # Each operator of the step is launched `reps` times back to back between two events on the launch
+    # stream, five times over; the median batch gives its average launch duration (main kernel plus,
+    # for a sliced reduction, the combine kernel), which is what a kernel trace of this command shows.
+    # Events between the operators of a step are not used: each costs about 3.5 us of idle GPU.
+    per_op_ms = None
+    if not args.no_op_events:
+        per_op_ms = [r.event_ms(lambda r=r, op=op: r.run(op), launches=args.op_reps, warm=3, batches=5)
+                     for r, op in items]
+
     out = {
-        "metric": "TFLOP/s and % FP32 MFMA peak per conv op (fwd/dgrad/wgrad), CIFAR shapes",
-        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_step, 5), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: N=%d %dx%dx%d -> %dx%dx%d, %dx%d filter, stride %d, pad %d, "
-                               "fwd+bwd_data+bwd_weight per step"
-                               % (layer.name, layer.N, layer.IH, layer.IW, layer.IC, layer.OH, layer.OW,
-                                  layer.OC, layer.FH, layer.FW, layer.stride, layer.pad),
-                   "flop_per_step": 3 * layer.flops,
-                   "pct_fp32_mfma_peak": round(100 * value / PEAK_FP32_MFMA_TFLOPS, 2)},
-        "per_op": {op: {"ms": round(per_op[op], 5),
-                        "tflops": round(layer.flops / per_op[op] / 1e9, 2),
-                        "pct_peak": round(100 * layer.flops / per_op[op] / 1e9 / PEAK_FP32_MFMA_TFLOPS, 1),
-                        "split": r.plans[op].split, "tile": [r.plans[op].tile_m, r.plans[op].tile_n]}
-                   for op in OPS},
-        # achieved = nominal FLOP of the slowest operator / its event-timed duration; for a sliced
-        # operator that duration includes the slice-reduce kernel, so the figure is conservative
-        "roofline": {"bound": "mfma", "kernel": KERNEL_OF_OP[dom], "operator": dom,
-                     "achieved": round(achieved, 2), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(layer.name, {}).get(dom)},
+        "metric": METRIC, "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": round(ms_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": workload_text(args.workload, layers, args.graph),
+                   "operators_per_step": len(items), "flop_per_step": flop_step,
+                   "effective_flop_per_step": round(eff_step),
+                   "pct_fp32_mfma_peak": round(100 * value / PEAK_FP32_MFMA_TFLOPS, 2),
+                   "effective_tflops": round(eff_step / ms_step / 1e9, 3),
+                   "pct_fp32_mfma_peak_effective": round(100 * eff_step / ms_step / 1e9 / PEAK_FP32_MFMA_TFLOPS, 2)},
     }
+    out["ms_per_step_events"] = round(ms_step_events, 5)
+    if per_op_ms is not None:
+        per = []
+        for (r, op), ms in zip(items, per_op_ms):
+            l, pl = r.layer, r.plans[op]
+            tf, tfe = l.flops / ms / 1e9, l.effective_flops / ms / 1e9
+            per.append({"layer": l.name, "op": op, "ms": round(ms, 5), "tflops": round(tf, 2),
+                        "pct_peak": round(100 * tf / PEAK_FP32_MFMA_TFLOPS, 1),
+                        "tflops_effective": round(tfe, 2), "pct_peak_effective": round(100 * tfe / PEAK_FP32_MFMA_TFLOPS, 1),
+                        "gbs": round(op_bytes(l, op) / ms / 1e6, 1),
+                        "kernel": kernel_name(l, op, pl, mc), "tile": [pl.tile_m, pl.tile_n], "split": pl.split,
+                        "pos_major": pl.pos_major, "grid": pl.grid})
+        out["per_op"] = per
+        out["per_op_sum_ms"] = round(sum(p["ms"] for p in per), 5)
+        out["roofline"] = roofline(per, layers)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(layer, r.host)
+        out["cpu_baseline"] = cpu_baseline(rs)
     print(json.dumps(out))
+
+
+def workload_text(name, layers, graph):
+    if len(layers) == 1:
+        l = layers[0]
+        return ("%s: N=%d %dx%dx%d -> %dx%dx%d, %dx%d filter, stride %d, pad %d, fwd+bwd_data+bwd_weight per step"
+                % (l.name, l.N, l.IH, l.IW, l.IC, l.OH, l.OW, l.OC, l.FH, l.FW, l.stride, l.pad))
+    what = {"cfg5": "VGG-16-shaped conv stack, N=128, 32x32x3 input, 13 layers of 3x3 pad-1 convolutions "
+                    "(64,64,128,128,256x3,512x3,512x3 channels, maps 32x32 down to 2x2)"}.get(name, name)
+    return "%s: %s; %d layers x (fwd+bwd_data+bwd_weight) back to back on one stream%s" % (
+        name, what, len(layers), ", replayed as one HIP graph" if graph else "")
+
+
+def roofline(per, layers):
+    """The kernel with the largest share of the step: its launches' effective FLOP (in-range taps
+    only; nominal x in-range share) over their event-timed durations, against the fp32 MFMA peak -
+    or, where the step is dominated by an HBM-bound kernel, its algorithmic bytes against 8 TB/s."""
+    by_layer = {l.name: l for l in layers}
+    groups = {}
+    for p in per:
+        groups.setdefault(p["kernel"], []).append(p)
+    kern, rows = max(groups.items(), key=lambda kv: sum(p["ms"] for p in kv[1]))
+    ms = sum(p["ms"] for p in rows)
+    nominal = sum(by_layer[p["layer"]].flops for p in rows)
+    eff = sum(by_layer[p["layer"]].effective_flops for p in rows)
+    nbytes = sum(op_bytes(by_layer[p["layer"]], p["op"]) for p in rows)
+    ridge = PEAK_FP32_MFMA_TFLOPS * 1e3 / PEAK_HBM_GBS
+    traffic = None
+    if os.path.exists(TRAFFIC_FILE):
+        t = json.load(open(TRAFFIC_FILE)).get("kernels", {}).get(kern)
+        traffic = None if t is None else t["hbm_bytes_per_launch"]
+    common = {"kernel": kern, "launches_per_step": len(rows), "avg_launch_us": round(1e3 * ms / len(rows), 3),
+              "share_of_step": round(ms / sum(p["ms"] for p in per), 4),
+              "includes_combine_pass_of_sliced_launches": any(p["split"] > 1 for p in rows),
+              "traffic": traffic}
+    if nominal / nbytes < ridge:
+        a = nbytes / ms / 1e6
+        return dict({"bound": "hbm", "achieved": round(a, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": round(a / PEAK_HBM_GBS, 4)}, **common)
+    a = eff / ms / 1e9
+    return dict({"bound": "mfma", "achieved": round(a, 2), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                 "frac": round(a / PEAK_FP32_MFMA_TFLOPS, 4),
+                 "achieved_nominal": round(nominal / ms / 1e9, 2),
+                 "flop_counted": "effective: taps inside the image only (nominal 2*M*OC*K x in-range share)"}, **common)
+
+
+def mfma_peak_report(mc, torch):
+    """Register-only v_mfma_f32_32x32x2_f32 loop with 0 / 16 / 48 / 96 ordinary vector instructions
+    per 8 matrix instructions, one and two workgroups per CU."""
+    rows = []
+    out = torch.empty(512 * 256, dtype=torch.float32, device="cuda")
+    iters = 20000
+    for wg_per_cu in (1, 2):
+        for nv in (0, 16, 48, 96):
+            wgs = 256 * wg_per_cu
+            for _ in range(3):
+                flop = mc.conv2d_probe_mfma_rate(nv, wgs, iters, out)
+            torch.cuda.synchronize()
+            best = 1e30
+            for _ in range(5):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                mc.conv2d_probe_mfma_rate(nv, wgs, iters, out)
+                e1.record()
+                torch.cuda.synchronize()
+                best = min(best, e0.elapsed_time(e1))
+            tf = flop / best / 1e9
+            rows.append({"valu_per_8_mfma": nv, "workgroups_per_cu": wg_per_cu, "ms": round(best, 4),
+                         "tflops": round(tf, 2), "pct_of_157.3": round(100 * tf / PEAK_FP32_MFMA_TFLOPS, 1)})
+            log("MFMA loop, %2d VALU per 8 MFMA, %d workgroup(s) per CU: %8.3f ms  %6.1f TFLOP/s  (%.1f %% of 157.3)"
+                % (nv, wg_per_cu, best, tf, 100 * tf / PEAK_FP32_MFMA_TFLOPS))
+    return rows
 
 
 if __name__ == "__main__":
