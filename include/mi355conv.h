@@ -28,7 +28,8 @@
  *   - Return value: MI355CONV_OK (0) or a negative mi355conv_status.
  *   - Stream capture: the operator entry points only enqueue kernels (no allocation, no
  *     memset, no synchronisation), so they may be recorded into a HIP graph.  The first
- *     operator call on a device also does one-time device set-up (kernel attributes), which must not happen inside a capture: call conv2d_init() - or any operator
+ *     operator call on a device also does one-time device set-up (kernel attributes, address
+ *     look-up), which must not happen inside a capture: call conv2d_init() - or any operator
  *     once - on that device before capturing.
  *   - Process-global tuning: conv2d_set_tuning / conv2d_set_tile change what
  *     conv2d_workspace_bytes, conv2d_query_plan, conv2d_query_workgroup and every operator
@@ -97,7 +98,7 @@ enum {
 };
 
 /* One-time set-up of the CURRENT device (idempotent, thread-safe): raises the LDS limit of the
- * large-tile kernels.  Optional - the first operator
+ * large-tile kernels and looks up the library's own device memory.  Optional - the first operator
  * call on a device does the same - except before stream capture, where it (or one operator call)
  * is required.  Must not be called while a capture is under way. */
 int conv2d_init(void);
@@ -171,6 +172,21 @@ int deconv2d(const float *dY, const float *W, float *dX, const conv2d_desc *d,
  * order, so results are bitwise reproducible either way. */
 int conv2d_bwd_weight(const float *X, const float *dY, float *dW, const conv2d_desc *d,
                       void *ws, size_t ws_bytes, void *stream);
+
+/* Backward-weight for callers that cannot allocate device memory or bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operator,
+ * same plan and same kernels as conv2d_bwd_weight; the slice partials go to a device array that is
+ * part of the library (conv2d_noalloc_scratch_bytes() bytes, 32 MiB, held by every GPU the library
+ * runs on until the process ends) instead of a caller workspace.  The call allocates nothing and
+ * frees nothing.  Returns MI355CONV_ERR_WORKSPACE, before any HIP call, when the shape needs more
+ * than that (conv2d_workspace_bytes(MI355CONV_OP_BWD_WEIGHT, d) tells).  All calls on one GPU share
+ * that GPU's array: two such calls that may run at the same time on one GPU (different streams)
+ * race; calls on one stream are ordered and safe.  Nothing in the array needs clearing between
+ * calls (every partial that is read was written by the same call).  As with every operator, the
+ * first call on a device must not be inside a stream capture (conv2d_init). */
+int conv2d_bwd_weight_noalloc(const float *X, const float *dY, float *dW, const conv2d_desc *d,
+                              void *stream);
+size_t conv2d_noalloc_scratch_bytes(void);
 
 /* Measurement aid (not an operator): launches a register-only v_mfma_f32_32x32x2_f32 loop with
  * valu_per_8_mfma in {0, 16, 48, 96} ordinary vector instructions per 8 matrix instructions, on

@@ -20,7 +20,7 @@ KERNEL_DIRECT, KERNEL_GATHER, KERNEL_GATHER_ELEM, KERNEL_FIRST_LAYER, KERNEL_WGR
 EXPORTS = ("conv2d_workspace_bytes", "conv2d_query_plan", "conv2d_query_workgroup", "conv2d_set_tuning", "conv2d_set_tile", "conv2d_fwd",
            "conv2d_fwd_bias_act", "conv2d_fwd_u8",
            "conv2d_bwd_data", "deconv2d", "conv2d_bwd_weight", "conv2d_status_string",
-           "conv2d_last_hip_error", "conv2d_init",
+           "conv2d_last_hip_error", "conv2d_init", "conv2d_bwd_weight_noalloc", "conv2d_noalloc_scratch_bytes",
            "conv2d_probe_mfma_rate")
 
 
@@ -86,6 +86,10 @@ def load() -> ctypes.CDLL:
         lib.conv2d_fwd_u8.restype = ctypes.c_int
         lib.conv2d_init.argtypes = []
         lib.conv2d_init.restype = ctypes.c_int
+        lib.conv2d_bwd_weight_noalloc.argtypes = [vp, vp, vp, dp, vp]
+        lib.conv2d_bwd_weight_noalloc.restype = ctypes.c_int
+        lib.conv2d_noalloc_scratch_bytes.argtypes = []
+        lib.conv2d_noalloc_scratch_bytes.restype = ctypes.c_size_t
         lib.conv2d_probe_mfma_rate.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
         lib.conv2d_probe_mfma_rate.restype = ctypes.c_int
         lib.conv2d_status_string.argtypes = [ctypes.c_int]
@@ -146,6 +150,10 @@ def conv2d_init() -> None:
     rc = load().conv2d_init()
     if rc != 0:
         raise Mi355ConvError(rc, "conv2d_init")
+
+
+def conv2d_noalloc_scratch_bytes() -> int:
+    return int(load().conv2d_noalloc_scratch_bytes())
 
 
 def _ptr(t):
@@ -255,6 +263,18 @@ def conv2d_bwd_weight(X, dY, dW, desc: ConvDesc, ws=None, stream=None):
     _check(dY, (desc.N, desc.OH, desc.OW, desc.OC), "dY")
     _check(dW, (desc.OC, desc.FH, desc.FW, desc.IC), "dW")
     return _call("conv2d_bwd_weight", OP_BWD_WEIGHT, X, dY, dW, desc, ws, stream)
+
+
+def conv2d_bwd_weight_noalloc(X, dY, dW, desc: ConvDesc, stream=None):
+    """conv2d_bwd_weight with the slice partials in the library's own device array: no workspace
+    argument, no allocation anywhere (this binding allocates nothing either)."""
+    _check(X, (desc.N, desc.IH, desc.IW, desc.IC), "X")
+    _check(dY, (desc.N, desc.OH, desc.OW, desc.OC), "dY")
+    _check(dW, (desc.OC, desc.FH, desc.FW, desc.IC), "dW")
+    rc = load().conv2d_bwd_weight_noalloc(_ptr(X), _ptr(dY), _ptr(dW), ctypes.byref(desc), _stream_handle(stream))
+    if rc != 0:
+        raise Mi355ConvError(rc, "conv2d_bwd_weight_noalloc")
+    return dW
 
 
 def conv2d_probe_mfma_rate(valu_per_8_mfma, workgroups, iters, out, stream=None):

@@ -14,6 +14,14 @@
 
 using namespace mi355conv;
 
+// Device memory of the library's own for conv2d_bwd_weight_noalloc: the slice partials of callers
+// that cannot bring (or allocate) a workspace.  Every GPU the library runs on holds its own copy
+// until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the address of each device's copy is looked up once and kept
+// (prepare_device), and only that address is ever handed to kernels.
+constexpr size_t kScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
 
 std::atomic<int> g_forceVariant{MI355CONV_VARIANT_AUTO};
@@ -604,9 +612,10 @@ int hip_fail(hipError_t e)
 constexpr int kMaxDevices = 64;
 std::mutex g_deviceMutex;
 std::atomic<int> g_deviceReady[kMaxDevices];
+void *g_scratchPtr[kMaxDevices];
 
 // Once per device, with that device current and no stream capture under way: raises the LDS limit
-// of the large-tile kernels.
+// of the large-tile kernels and looks up the device's scratch array.
 int prepare_device(int *devOut)
 {
     int dev = 0;
@@ -620,7 +629,11 @@ int prepare_device(int *devOut)
     e = prepare_gather_gemm();
     if (e == hipSuccess) e = prepare_wgrad();
     if (e == hipSuccess) e = prepare_wgrad_fast();
+    void *ptr = nullptr;
+    if (e == hipSuccess) e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
     if (e != hipSuccess) return hip_fail(e);
+    if (!ptr) return hip_fail(hipErrorInvalidSymbol);
+    g_scratchPtr[dev] = ptr;
     g_deviceReady[dev].store(1, std::memory_order_release);
     return MI355CONV_OK;
 }
@@ -1188,8 +1201,10 @@ int deconv2d(const float *dY, const float *W, float *dX, const conv2d_desc *d, v
     return conv2d_bwd_data(dY, W, dX, d, ws, ws_bytes, stream);
 }
 
-int conv2d_bwd_weight(const float *X, const float *dY, float *dW, const conv2d_desc *d, void *ws,
-                      size_t ws_bytes, void *stream)
+// ownWorkspace: the slice partials go to the library's per-device scratch array instead of a
+// caller workspace (conv2d_bwd_weight_noalloc)
+static int bwd_weight_impl(const float *X, const float *dY, float *dW, const conv2d_desc *d, void *ws,
+                           size_t ws_bytes, void *stream, bool ownWorkspace)
 {
     Shape s;
     Plan pl;
@@ -1197,10 +1212,18 @@ int conv2d_bwd_weight(const float *X, const float *dY, float *dW, const conv2d_d
     if (rc != MI355CONV_OK) return rc;
     rc = make_plan(MI355CONV_OP_BWD_WEIGHT, s, &pl);
     if (rc != MI355CONV_OK) return rc;
-    rc = check_buffers(X, dY, dW, pl, ws, ws_bytes);
+    if (ownWorkspace) {
+        if (pl.wsBytes > kScratchBytes) return MI355CONV_ERR_WORKSPACE;   // before any HIP call
+        if (!X || !dY || !dW) return MI355CONV_ERR_NULL_PTR;
+        if (!aligned16(X) || !aligned16(dY) || !aligned16(dW)) return MI355CONV_ERR_ALIGNMENT;
+    } else {
+        rc = check_buffers(X, dY, dW, pl, ws, ws_bytes);
+        if (rc != MI355CONV_OK) return rc;
+    }
+    int dev = 0;
+    rc = prepare_device(&dev);
     if (rc != MI355CONV_OK) return rc;
-    rc = prepare_device(nullptr);
-    if (rc != MI355CONV_OK) return rc;
+    if (ownWorkspace) ws = g_scratchPtr[dev];   // the device's copy of `scratch`, never the array's name
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (pl.variant == MI355CONV_VARIANT_DIRECT) {
         hipError_t e = launch_direct_bwd_weight(X, dY, dW, s, st);
@@ -1271,6 +1294,19 @@ int conv2d_bwd_weight(const float *X, const float *dY, float *dW, const conv2d_d
     }
     return MI355CONV_OK;
 }
+
+int conv2d_bwd_weight(const float *X, const float *dY, float *dW, const conv2d_desc *d, void *ws,
+                      size_t ws_bytes, void *stream)
+{
+    return bwd_weight_impl(X, dY, dW, d, ws, ws_bytes, stream, false);
+}
+
+int conv2d_bwd_weight_noalloc(const float *X, const float *dY, float *dW, const conv2d_desc *d, void *stream)
+{
+    return bwd_weight_impl(X, dY, dW, d, nullptr, 0, stream, true);
+}
+
+size_t conv2d_noalloc_scratch_bytes(void) { return kScratchBytes; }
 
 int conv2d_init(void) { return prepare_device(nullptr); }
 

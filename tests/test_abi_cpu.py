@@ -228,3 +228,25 @@ def test_every_plan_is_one_its_launcher_takes(lib):
     # the shape that used to get an unlaunchable plan
     pl = mc.conv2d_query_plan(mc.OP_BWD_WEIGHT, mc.make_desc(32, 1, 64, 64, 64, 3, 3, 1, 1))
     assert pl.kernel == mc.KERNEL_WGRAD_FAST and pl.pos_major == 0
+
+
+def test_noalloc_argument_errors_before_any_hip_call(lib):
+    good = mc.make_desc(4, 8, 8, 3, 16, 3, 3, 1, 1)
+
+    def call(x, g, w, desc):
+        return lib.conv2d_bwd_weight_noalloc(ctypes.c_void_p(x), ctypes.c_void_p(g), ctypes.c_void_p(w),
+                                             ctypes.byref(desc) if desc is not None else None, None)
+    assert call(0, 512, 768, good) == -1
+    assert call(256, 512, 768, None) == -1
+    assert call(256, 516, 768, good) == -4
+    bad = mc.make_desc(4, 8, 8, 3, 16, 3, 3, 1, 1)
+    bad.N = 0
+    assert call(256, 512, 768, bad) == -2
+    assert mc.conv2d_noalloc_scratch_bytes() == 32 << 20
+    mc.conv2d_set_tuning(mc.VARIANT_MFMA, 64)
+    try:
+        big = mc.make_desc(128, 4, 4, 512, 512, 3, 3, 1, 1)
+        assert mc.conv2d_workspace_bytes(mc.OP_BWD_WEIGHT, big) > mc.conv2d_noalloc_scratch_bytes()
+        assert call(256, 512, 768, big) == -3       # needs more than the library's array
+    finally:
+        mc.conv2d_set_tuning(mc.VARIANT_AUTO, 0)
