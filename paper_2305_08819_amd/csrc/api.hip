@@ -665,6 +665,12 @@ void fill_gather_params(GatherGemmParams &g, const Plan &pl)
     }
     g.divTilesN = make_fastdiv((unsigned)pl.tilesN);
     g.divSplit = make_fastdiv((unsigned)pl.split);
+    g.divXcdUnit = make_fastdiv((unsigned)g.xcdUnit);
+    const int span = 8 * g.xcdUnit;
+    g.xcdWhole = (pl.grid / span) * span;
+    g.grid = pl.grid;
+    g.runsN = 0;
+    for (int i = 0; i < kMaxBalanceRuns; ++i) g.runs.idStart[i] = 0x7fffffff;   // unused run entries never match
 }
 
 // Longest-first dealing of a launch's workgroups to the 256 CUs.  unitWork[u] is the length of
@@ -983,6 +989,8 @@ int run_gather(const float *A, const float *B, float *out, const Shape &s, const
     g.sh = s.sh; g.sw = s.sw; g.ph = s.ph; g.pw = s.pw;
     g.divN = make_fastdiv((unsigned)s.N);
     g.divChunksPerTap = make_fastdiv((unsigned)ceil_div(g.SC, kBK));
+    g.divDHW = make_fastdiv((unsigned)(g.DH * g.DW));
+    g.divDW = make_fastdiv((unsigned)g.DW);
     g.aBytes = (unsigned)((long long)g.Nimg * g.SH * g.SW * g.SC * 4);
     g.bBytes = (unsigned)((long long)s.OC * s.FH * s.FW * s.IC * 4);
     fill_gather_params(g, pl);
@@ -993,7 +1001,11 @@ int run_gather(const float *A, const float *B, float *out, const Shape &s, const
     g.rowTilesPerPos = 1;
     if (pl.balance) {
         g.rowTilesPerPos = s.N / pl.bm;
-        g.runs = pl.runs;
+        g.runs.n = g.runsN = pl.runs.n;
+        for (int i = 0; i < pl.runs.n; ++i) {
+            g.runs.idStart[i] = pl.runs.idStart[i];
+            g.runs.rankStart[i] = pl.runs.rankStart[i];
+        }
         memcpy(g.posOrder, pl.order, sizeof g.posOrder);
     }
     g.divRowTilesPerPos = make_fastdiv((unsigned)g.rowTilesPerPos);
@@ -1278,12 +1290,22 @@ static int bwd_weight_impl(const float *X, const float *dY, float *dW, const con
     w.divSplit = make_fastdiv((unsigned)pl.split);
     w.balance = pl.balance;
     w.tilesM = pl.tilesM;
+    w.grid = pl.grid;
+    w.divXcdUnit = make_fastdiv((unsigned)w.xcdUnit);
+    w.xcdWhole = (pl.grid / (8 * w.xcdUnit)) * (8 * w.xcdUnit);
+    w.divTilesPerTap = w.divPerTap = make_fastdiv(1u);
+    for (int i = 0; i < kMaxBalanceRuns; ++i) w.runs.idStart[i] = 0x7fffffff;   // unused run entries never match
     if (pl.balance) {
         w.tilesPerTap = s.IC / pl.bn;
         w.divTilesPerTap = make_fastdiv((unsigned)w.tilesPerTap);
         w.divPerTap = make_fastdiv((unsigned)(w.tilesPerTap * pl.tilesM * pl.split));
-        w.runs = pl.runs;
-        memcpy(w.tapOrder, pl.order, sizeof w.tapOrder);
+        w.runs.n = w.runsN = pl.runs.n;
+        for (int i = 0; i < pl.runs.n; ++i) {
+            w.runs.idStart[i] = pl.runs.idStart[i];
+            w.runs.rankStart[i] = pl.runs.rankStart[i];
+        }
+        static_assert(sizeof pl.order >= kMaxBalancedTaps && sizeof w.tapOrder >= kMaxBalancedTaps, "tap order fits");
+        memcpy(w.tapOrder, pl.order, kMaxBalancedTaps);
     }
     hipError_t e = pl.fast ? launch_wgrad_fast(w, pl.bm, pl.bn, pl.grid, st)
                            : launch_wgrad(w, pl.bm, pl.bn, pl.elem != 0, pl.grid, st);

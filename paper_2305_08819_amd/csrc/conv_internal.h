@@ -98,6 +98,11 @@ struct GatherGemmParams {
     const float *bias;    // may be null
     FastDiv divN;         // by Nimg
     FastDiv divTilesN, divSplit, divRowTilesPerPos, divChunksPerTap;   // chunks per tap = SC / kBK
+    FastDiv divDHW, divDW;   // by DH*DW and DW: the row decode of single-phase launches (forward, unit-stride backward-data)
+    FastDiv divXcdUnit;      // by xcdUnit
+    int xcdWhole;            // workgroup ids below this are remapped (a whole number of 8 * xcdUnit)
+    int grid;                // workgroups of the launch
+    int runsN;               // runs.n, among the scalars fetched first
     int phaseStart[kMaxPhases];   // first row tile of each phase; INT_MAX past the last phase
     GatherPhase phase[kMaxPhases];
     BalanceRuns runs;
@@ -119,7 +124,8 @@ struct GatherView {
     int tilesN, xcdUnit, nPhases, balance, rowTilesPerPos, epilogue;
     float slope;
     const float *bias;
-    FastDiv divN, divTilesN, divSplit, divRowTilesPerPos, divChunksPerTap;
+    FastDiv divN, divTilesN, divSplit, divRowTilesPerPos, divChunksPerTap, divDHW, divDW, divXcdUnit;
+    int xcdWhole, grid, runsN;
     const int *phaseStart;
     const GatherPhase *phase;
     const BalanceRuns &runs;
@@ -132,7 +138,7 @@ __device__ __forceinline__ GatherView gather_view(const GatherGemmParams &p)
     GatherView v{p.A, p.B, p.C, p.aBytes, p.bBytes, p.Nimg, p.SH, p.SW, p.SC, p.DH, p.DW, p.DC, p.FH, p.FW,
                  p.sh, p.sw, p.ph, p.pw, p.posMajor, p.split, p.sliceStride, p.tilesN, p.xcdUnit, p.nPhases,
                  p.balance, p.rowTilesPerPos, p.epilogue, p.slope, p.bias, p.divN, p.divTilesN, p.divSplit, p.divRowTilesPerPos,
-                 p.divChunksPerTap, p.phaseStart, p.phase, p.runs, p.posOrder};
+                 p.divChunksPerTap, p.divDHW, p.divDW, p.divXcdUnit, p.xcdWhole, p.grid, p.runsN, p.phaseStart, p.phase, p.runs, p.posOrder};
     MI355CONV_PIN(v.A); MI355CONV_PIN(v.B); MI355CONV_PIN(v.C);
     MI355CONV_PIN(v.aBytes); MI355CONV_PIN(v.bBytes);
     MI355CONV_PIN(v.Nimg); MI355CONV_PIN(v.SH); MI355CONV_PIN(v.SW); MI355CONV_PIN(v.SC);
@@ -145,6 +151,11 @@ __device__ __forceinline__ GatherView gather_view(const GatherGemmParams &p)
     MI355CONV_PIN(v.divTilesN.mul); MI355CONV_PIN(v.divTilesN.sh1); MI355CONV_PIN(v.divTilesN.sh2);
     MI355CONV_PIN(v.divSplit.mul); MI355CONV_PIN(v.divSplit.sh1); MI355CONV_PIN(v.divSplit.sh2);
     MI355CONV_PIN(v.divChunksPerTap.mul); MI355CONV_PIN(v.divChunksPerTap.sh1); MI355CONV_PIN(v.divChunksPerTap.sh2);
+    MI355CONV_PIN(v.divRowTilesPerPos.mul); MI355CONV_PIN(v.divRowTilesPerPos.sh1); MI355CONV_PIN(v.divRowTilesPerPos.sh2);
+    MI355CONV_PIN(v.divDHW.mul); MI355CONV_PIN(v.divDHW.sh1); MI355CONV_PIN(v.divDHW.sh2);
+    MI355CONV_PIN(v.divDW.mul); MI355CONV_PIN(v.divDW.sh1); MI355CONV_PIN(v.divDW.sh2);
+    MI355CONV_PIN(v.divXcdUnit.mul); MI355CONV_PIN(v.divXcdUnit.sh1); MI355CONV_PIN(v.divXcdUnit.sh2);
+    MI355CONV_PIN(v.xcdWhole); MI355CONV_PIN(v.grid); MI355CONV_PIN(v.runsN);
     return v;
 }
 #endif
@@ -176,8 +187,12 @@ struct WgradParams {
     int tilesPerTap;      // IC / BN
     int tilesM;
     FastDiv divTilesPerTap, divPerTap;   // by tilesPerTap and by tilesPerTap * tilesM * split
+    int grid;             // workgroups of the launch
+    int runsN;            // runs.n, among the scalars fetched first
+    int xcdWhole;         // workgroup ids below this are remapped (a whole number of 8 * xcdUnit)
+    FastDiv divXcdUnit;
     BalanceRuns runs;
-    unsigned char tapOrder[kMaxBalancedTaps];
+    unsigned char tapOrder[256];   // kMaxBalancedTaps entries used; sized for one 4-byte load per lane
 };
 
 // Scalar fields of WgradParams in SGPRs from the kernel's first instructions on (see GatherView).
@@ -193,6 +208,8 @@ struct WgradView {
     FastDiv divOHOW, divOW, divN, divIC, divFW, divTilesN, divSplit;
     int balance, tilesPerTap, tilesM;
     FastDiv divTilesPerTap, divPerTap;
+    int grid, runsN, xcdWhole;
+    FastDiv divXcdUnit;
     const BalanceRuns &runs;
     const unsigned char *tapOrder;
 };
@@ -206,7 +223,7 @@ __device__ __forceinline__ WgradView wgrad_view(const WgradParams &p)
     WgradView v{p.X, p.G, p.C, p.N, p.IH, p.IW, p.IC, p.OC, p.OH, p.OW, p.FH, p.FW, p.sh, p.sw, p.ph, p.pw,
                 p.posMajor, p.split, p.sliceStride, p.tilesN, p.xcdUnit, p.M, p.flushChunks, p.xBytes, p.gBytes,
                 p.divOHOW, p.divOW, p.divN, p.divIC, p.divFW, p.divTilesN, p.divSplit, p.balance, p.tilesPerTap,
-                p.tilesM, p.divTilesPerTap, p.divPerTap, p.runs, p.tapOrder};
+                p.tilesM, p.divTilesPerTap, p.divPerTap, p.grid, p.runsN, p.xcdWhole, p.divXcdUnit, p.runs, p.tapOrder};
     MI355CONV_PIN(v.X); MI355CONV_PIN(v.G); MI355CONV_PIN(v.C);
     MI355CONV_PIN(v.N); MI355CONV_PIN(v.IH); MI355CONV_PIN(v.IW); MI355CONV_PIN(v.IC); MI355CONV_PIN(v.OC);
     MI355CONV_PIN(v.OH); MI355CONV_PIN(v.OW); MI355CONV_PIN(v.FH); MI355CONV_PIN(v.FW);
@@ -217,6 +234,8 @@ __device__ __forceinline__ WgradView wgrad_view(const WgradParams &p)
     pin_fastdiv(v.divOHOW); pin_fastdiv(v.divOW); pin_fastdiv(v.divN); pin_fastdiv(v.divIC);
     pin_fastdiv(v.divFW); pin_fastdiv(v.divTilesN); pin_fastdiv(v.divSplit);
     MI355CONV_PIN(v.balance); MI355CONV_PIN(v.tilesPerTap); MI355CONV_PIN(v.tilesM);
+    pin_fastdiv(v.divTilesPerTap); pin_fastdiv(v.divPerTap); pin_fastdiv(v.divXcdUnit);
+    MI355CONV_PIN(v.grid); MI355CONV_PIN(v.runsN); MI355CONV_PIN(v.xcdWhole);
     return v;
 }
 #endif
@@ -267,6 +286,44 @@ __device__ __forceinline__ int balanced_rank(int bid, int grid, const BalanceRun
     const int start = lane < b.n ? b.idStart[lane] : 0x7fffffff;
     const int r = __popcll(__ballot(slot >= start)) - 1;   // idStart[0] == 0
     return b.rankStart[r] + (slot - b.idStart[r]);
+}
+
+// The per-lane pieces of the workgroup-id decode (run table of the dealing, order of positions
+// or taps), requested by every wave with its very first instructions so that they travel
+// together with the scalar kernel arguments instead of one dependent load after the other.
+// Unused run entries hold idStart = INT_MAX (the host fills them), so no count is needed.
+struct BalancePrefetch {
+    int runId, runRank;   // lane i: run i
+    unsigned order4;      // lane i: entries 4i .. 4i+3 of the 256-entry order table
+};
+__device__ __forceinline__ BalancePrefetch balance_prefetch(const BalanceRuns &runs, const unsigned char *order)
+{
+    static_assert(kMaxBalanceRuns < 64, "one lane per run");
+    const int lane = threadIdx.x & 63;
+    BalancePrefetch b;
+    b.runId = lane < kMaxBalanceRuns ? runs.idStart[lane] : 0x7fffffff;
+    b.runRank = lane < kMaxBalanceRuns ? runs.rankStart[lane] : 0;
+    b.order4 = reinterpret_cast<const unsigned *>(order)[lane];
+    return b;
+}
+__device__ __forceinline__ int balanced_rank(int bid, int grid, const BalancePrefetch &b)
+{
+    const int slot = balance_slot(bid, grid);
+    const int r = __popcll(__ballot(slot >= b.runId)) - 1;   // idStart[0] == 0
+    return __builtin_amdgcn_readlane(b.runRank, r) + (slot - __builtin_amdgcn_readlane(b.runId, r));
+}
+__device__ __forceinline__ int balance_order(const BalancePrefetch &b, int rank)   // rank < 256, uniform
+{
+    return (int)((__builtin_amdgcn_readlane((int)b.order4, rank >> 2) >> ((rank & 3) * 8)) & 255u);
+}
+
+// xcd_remap with the division by `unit` and the remapped range precomputed on the host
+__device__ __forceinline__ int xcd_remap_fast(int bid, int whole, int unit, const FastDiv &divUnit)
+{
+    if (bid >= whole) return bid;
+    const int x = bid & 7, q = bid >> 3;
+    const int g = (int)fast_div((unsigned)q, divUnit);
+    return (g * 8 + x) * unit + (q - g * unit);
 }
 
 __device__ __forceinline__ int xcd_remap(int bid, int grid, int unit)

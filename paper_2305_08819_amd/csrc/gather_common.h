@@ -48,26 +48,34 @@ struct GatherTile {
 // range, which only adds taps whose operands load as zeros.  All threads must call it; it
 // contains one barrier.
 template <int BM, int BN, bool BWD, class P>
-__device__ __forceinline__ GatherTile gather_tile_setup(const P &p, int *rowBase, int *rowY,
+__device__ __forceinline__ GatherTile gather_tile_setup(const P &p, const BalancePrefetch &pre, int *rowBase, int *rowY,
                                                         int *rowX, int *outRow)
 {
     const int tid = threadIdx.x;
-    int bid = p.balance && p.runs.n ? balanced_rank(blockIdx.x, gridDim.x, p.runs)
-                                    : xcd_remap(blockIdx.x, gridDim.x, p.xcdUnit);
+    int bid = p.balance && p.runsN ? balanced_rank(blockIdx.x, p.grid, pre)
+                                    : xcd_remap_fast(blockIdx.x, p.xcdWhole, p.xcdUnit, p.divXcdUnit);
     const int rest = (int)fast_div((unsigned)bid, p.divTilesN);
     const int tn = bid - rest * p.tilesN;
     int tmGlobal = (int)fast_div((unsigned)rest, p.divSplit);
     const int slice = rest - tmGlobal * p.split;
     if (p.balance) {   // row tiles are enumerated by position rank
         const int rank = (int)fast_div((unsigned)tmGlobal, p.divRowTilesPerPos);
-        tmGlobal = p.posOrder[rank] * p.rowTilesPerPos + (tmGlobal - rank * p.rowTilesPerPos);
+        tmGlobal = balance_order(pre, rank) * p.rowTilesPerPos + (tmGlobal - rank * p.rowTilesPerPos);
     }
-    int phase = 0;
-    if (BWD) {   // phase starts are ascending: the phase is the number of starts not above this tile
+    // Forward and unit-stride backward-data have one phase that holds all pixels and all taps: its
+    // record is made up from the scalar arguments.  Only strided backward-data
+    // fetches the record of the tile's phase, a load that depends on the decoded tile.
+    GatherPhase ph;
+    if (!BWD || (p.sh == 1 && p.sw == 1)) {
+        ph.tileStart = 0; ph.ra = 0; ph.rb = 0; ph.y0 = 0; ph.x0 = 0;
+        ph.dh = p.DH; ph.dw = p.DW; ph.nU = p.FH; ph.nV = p.FW;
+        ph.divHW = p.divDHW; ph.divW = p.divDW;
+    } else {   // phase starts are ascending: the phase is the number of starts not above this tile
+        int phase = 0;
 #pragma unroll
         for (int i = 1; i < kMaxPhases; ++i) phase += tmGlobal >= p.phaseStart[i] ? 1 : 0;
+        ph = p.phase[phase];
     }
-    const GatherPhase ph = p.phase[phase];
     const int tmLocal = tmGlobal - ph.tileStart;
     const int hw = ph.dh * ph.dw;
     const int Mphase = p.Nimg * hw;
@@ -181,12 +189,17 @@ __device__ __forceinline__ void gather_tile_store(const P &p, int slice, int n0,
         for (int j = 0; j < T::NB; ++j) {
             const int colBase = n0 + wn * T::WTN + j * 32;
             if (scratch && (p.DC & 3) == 0 && colBase + 32 <= p.DC) {   // uniform
-                const float b = epi && p.bias ? p.bias[colBase + l32] : 0.f;
+                if (epi) {   // uniform: the plain operator pays no vector arithmetic here
+                    const float b = p.bias ? p.bias[colBase + l32] : 0.f;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float v = acc[i][j][r] + b;
-                    v = v > 0.f ? v : v * slope;
-                    scratch[(8 * (r / 4) + 4 * lh + (r % 4)) * kLDT + l32] = v;
+                    for (int r = 0; r < 16; ++r) {
+                        float v = acc[i][j][r] + b;
+                        v = v > 0.f ? v : v * slope;
+                        scratch[(8 * (r / 4) + 4 * lh + (r % 4)) * kLDT + l32] = v;
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) scratch[(8 * (r / 4) + 4 * lh + (r % 4)) * kLDT + l32] = acc[i][j][r];
                 }
                 // the LDS pipeline keeps a wave's accesses in order; no other wave touches this buffer
 #pragma unroll

@@ -37,6 +37,7 @@ namespace mi355conv {
 template <int BM, int BN, int WAVES_M, bool BWD, bool BELEM = false, bool RAGGED = false>
 __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGemmParams params)
 {
+    const BalancePrefetch pre = balance_prefetch(params.runs, params.posOrder);   // in flight with the scalar arguments
     const GatherView p = gather_view(params);
     using T = GG<BM, BN, WAVES_M, BWD>;
     extern __shared__ f4 smem_raw[];
@@ -52,7 +53,7 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     const int lane = tid & 63;
     const int wave = tid >> 6;
 
-    const GatherTile tile = gather_tile_setup<BM, BN, BWD>(p, rowBase, rowY, rowX, outRow);
+    const GatherTile tile = gather_tile_setup<BM, BN, BWD>(p, pre, rowBase, rowY, rowX, outRow);
     const int slice = tile.slice, n0 = tile.n0;
 
     // taps walked by this tile: the rectangle [uLo,uHi] x [vLo,vHi]

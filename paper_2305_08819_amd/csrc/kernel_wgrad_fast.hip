@@ -55,19 +55,20 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
     float *Gs = reinterpret_cast<float *>(smem_raw);
     float *Xs = Gs + 2 * T::G_STAGE;
 
+    const BalancePrefetch pre = balance_prefetch(params.runs, params.tapOrder);   // in flight with the scalar arguments
     const WgradView p = wgrad_view(params);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int tn, tmo, slice;
     if (PM && p.balance) {   // tiles enumerated tap by tap, taps with the most live positions first
-        const int rank = p.runs.n ? balanced_rank(blockIdx.x, gridDim.x, p.runs) : (int)blockIdx.x;
+        const int rank = p.runsN ? balanced_rank(blockIdx.x, p.grid, pre) : (int)blockIdx.x;
         const int tapRank = (int)fast_div((unsigned)rank, p.divPerTap);
         const int inner = rank - tapRank * (p.tilesPerTap * p.tilesM * p.split);
         const int r2 = (int)fast_div((unsigned)inner, p.divTilesPerTap);
-        tn = p.tapOrder[tapRank] * p.tilesPerTap + (inner - r2 * p.tilesPerTap);
+        tn = balance_order(pre, tapRank) * p.tilesPerTap + (inner - r2 * p.tilesPerTap);
         tmo = (int)fast_div((unsigned)r2, p.divSplit);
         slice = r2 - tmo * p.split;
     } else {
-        const int bid = xcd_remap(blockIdx.x, gridDim.x, p.xcdUnit);
+        const int bid = xcd_remap_fast(blockIdx.x, p.xcdWhole, p.xcdUnit, p.divXcdUnit);
         const int rest = (int)fast_div((unsigned)bid, p.divTilesN);
         tn = bid - rest * p.tilesN;
         tmo = (int)fast_div((unsigned)rest, p.divSplit);

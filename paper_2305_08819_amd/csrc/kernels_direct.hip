@@ -230,8 +230,10 @@ hipError_t launch_slice_reduce(const float *ws, float *out, long long count, int
     const long long count4 = count >> 2;
     if (count4 > 0) {
         // more thread groups per column when there are few columns and many slices
+        // at least 8 float4 columns (128 bytes) of a slice per workgroup row: a narrower strip would pull a
+        // whole cache line for every 16 bytes it uses
         int G = 1;
-        while (G < 256 && G * 2 <= split && count4 * G < (1 << 17)) G *= 2;
+        while (G < 32 && G * 2 <= split && count4 * G < (1 << 17)) G *= 2;
         const long long perWg = 256 / G;   // float4 columns per workgroup
         const unsigned grid = (unsigned)((count4 + perWg - 1) / perWg);
         const long long stride4 = stride >> 2;
@@ -241,10 +243,9 @@ hipError_t launch_slice_reduce(const float *ws, float *out, long long count, int
                            stride4, bias, slope, cols);                                                   \
         break;
         switch (G) {
-            MI355CONV_SR(1) MI355CONV_SR(2) MI355CONV_SR(4) MI355CONV_SR(8) MI355CONV_SR(16) MI355CONV_SR(32)
-            MI355CONV_SR(64) MI355CONV_SR(128)
+            MI355CONV_SR(1) MI355CONV_SR(2) MI355CONV_SR(4) MI355CONV_SR(8) MI355CONV_SR(16)
         default:
-            hipLaunchKernelGGL(slice_reduce_kernel<256>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4,
+            hipLaunchKernelGGL(slice_reduce_kernel<32>, dim3(grid), dim3(256), 0, st, ws, out, count4, split, stride4,
                                bias, slope, cols);
             break;
         }
