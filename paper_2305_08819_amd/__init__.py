@@ -63,6 +63,10 @@ def load() -> ctypes.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError("%s not built: run `python -m paper_2305_08819_amd.build`" % LIB_PATH)
+        # torch ships its own HIP runtime; it has to be in the process before this library is, so that
+        # both use that one runtime (loaded the other way round, the first operator call fails with
+        # "no ROCm-capable device is detected")
+        import torch  # noqa: F401
         lib = ctypes.CDLL(LIB_PATH)
         vp, dp = ctypes.c_void_p, ctypes.POINTER(ConvDesc)
         lib.conv2d_workspace_bytes.argtypes = [ctypes.c_int, dp]
