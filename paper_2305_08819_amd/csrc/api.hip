@@ -27,7 +27,6 @@ namespace {
 std::atomic<int> g_forceVariant{MI355CONV_VARIANT_AUTO};
 std::atomic<int> g_forceSplit{0};
 std::atomic<int> g_forceBM{0}, g_forceBN{0}, g_forcePosMajor{-1};
-std::atomic<int> g_waveSplit{1};
 thread_local char t_hipError[256] = "";
 
 constexpr long long kMaxElems = (1LL << 31) - 1;
@@ -1089,13 +1088,6 @@ int conv2d_set_tuning(int variant, int split)
     return MI355CONV_OK;
 }
 
-int conv2d_set_wave_split(int parts)
-{
-    if (parts != 1 && parts != 2) return MI355CONV_ERR_UNSUPPORTED;
-    g_waveSplit.store(parts);
-    return MI355CONV_OK;
-}
-
 int conv2d_set_tile(int tile_m, int tile_n, int pos_major)
 {
     if (tile_m < 0 || tile_n < 0 || pos_major < -1 || pos_major > 1 || (tile_m == 0) != (tile_n == 0))
@@ -1298,7 +1290,6 @@ static int bwd_weight_impl(const float *X, const float *dY, float *dW, const con
     w.divSplit = make_fastdiv((unsigned)pl.split);
     w.balance = pl.balance;
     w.tilesM = pl.tilesM;
-    w.waveSplit = g_waveSplit.load();
     w.grid = pl.grid;
     w.divXcdUnit = make_fastdiv((unsigned)w.xcdUnit);
     w.xcdWhole = (pl.grid / (8 * w.xcdUnit)) * (8 * w.xcdUnit);

@@ -187,7 +187,6 @@ struct WgradParams {
     int tilesPerTap;      // IC / BN
     int tilesM;
     FastDiv divTilesPerTap, divPerTap;   // by tilesPerTap and by tilesPerTap * tilesM * split
-    int waveSplit;        // fast kernel, 64x64 tile: 2 = the waves of a pair split every stage's rows (host-side switch)
     int grid;             // workgroups of the launch
     int runsN;            // runs.n, among the scalars fetched first
     int xcdWhole;         // workgroup ids below this are remapped (a whole number of 8 * xcdUnit)

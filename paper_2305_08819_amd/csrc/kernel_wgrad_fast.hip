@@ -29,14 +29,9 @@
 namespace mi355conv {
 
 namespace {
-// KS = 2: the four waves are 2 (halves of the tile's output channels) x 2 (halves of every stage's rows):
-// the two waves of a pair own different rows m of the same half tile and are added through LDS, in a
-// fixed order, before the one store - a wavefront-level reduction inside the workgroup.  A wave then
-// reads 3 operand fragments per 2 MFMAs instead of 2 per MFMA.
-template <int BM, int BN, int KS = 1>
+template <int BM, int BN>
 struct WF {
-    static constexpr int WAVES_M = BM >= 64 ? 2 : 1, WAVES_N = 4 / (WAVES_M * KS);   // a 32-row tile is one block row
-    static_assert(KS == 1 || (KS == 2 && WAVES_M == 2), "row halves pair up with the two channel halves");
+    static constexpr int WAVES_M = BM >= 64 ? 2 : 1, WAVES_N = 4 / WAVES_M;   // a 32-row tile is one block row
     static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     static constexpr int MB = WTM / 32, NB = WTN / 32;
     static constexpr int LDG = BM + 8, LDX = BN + 8;
@@ -52,10 +47,10 @@ struct WF {
 // WIDE (with PM false): OW is a multiple of 32 instead of a divisor, so a stage is 32 neighbouring
 // pixels of one output row that starts at column ow0 = 0, 32, 64, ...: the column validity of a
 // thread's tap then depends on ow0 and is tested per stage (two more VALU per load).
-template <int BM, int BN, bool PM, bool WIDE = false, int KS = 1>
+template <int BM, int BN, bool PM, bool WIDE = false>
 __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 64 * 64) ? 4 : 2) void wgrad_fast_kernel(const WgradParams params)
 {
-    using T = WF<BM, BN, KS>;
+    using T = WF<BM, BN>;
     extern __shared__ f4 smem_raw[];
     float *Gs = reinterpret_cast<float *>(smem_raw);
     float *Xs = Gs + 2 * T::G_STAGE;
@@ -290,8 +285,7 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
         }
     };
 
-    const int wk = wave % KS;                 // which part of a stage's rows this wave multiplies
-    const int wm = (wave / KS) / T::WAVES_N, wn = (wave / KS) % T::WAVES_N;
+    const int wm = wave / T::WAVES_N, wn = wave % T::WAVES_N;
     const int l32 = lane & 31, lh = lane >> 5;
 
     // Fragment ring: the LDS reads of MFMA step s+kAhead are issued before the MFMAs of step s, so a
@@ -301,15 +295,14 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
     // first fragments of the next buffer arrive.
     // volatile: the compiler would otherwise pair the reads into two-address LDS reads, each pair
     // needing a VALU add for its base - and VALU instructions cost matrix time, LDS reads do not
-    constexpr int kSteps = kBK / 2 / KS, kRing = 4, kAhead = kRing - 1;   // MFMA steps of this wave per stage
+    constexpr int kSteps = kBK / 2, kRing = 4, kAhead = kRing - 1;
     static_assert(kSteps % kRing == 0, "ring slots must line up across stages");
     float fa[kRing][T::MB], fb[kRing][T::NB];
-    // wave part wk takes the stage's rows [wk * 32 / KS, (wk + 1) * 32 / KS)
-    const float *gFrag = Gs + (wk * (kBK / KS) + lh * 4) * T::LDG + wm * T::WTM + l32;
-    const float *xFrag = Xs + (wk * (kBK / KS) + lh * 4) * T::LDX + wn * T::WTN + l32;
+    const float *gFrag = Gs + (lh * 4) * T::LDG + wm * T::WTM + l32;
+    const float *xFrag = Xs + (lh * 4) * T::LDX + wn * T::WTN + l32;
     auto read_step = [&](int buf, int s, float *a, float *b) __attribute__((always_inline)) {
         const int row = (s / 4) * 8 + s % 4;   // the lane's upper half adds 4: both operands use the same rows
-        lds_cvptr g = (lds_cvptr)(gFrag + buf * T::G_STAGE + row * T::LDG);   // (gFrag, xFrag start at this wave's rows)
+        lds_cvptr g = (lds_cvptr)(gFrag + buf * T::G_STAGE + row * T::LDG);
         lds_cvptr x = (lds_cvptr)(xFrag + buf * T::X_STAGE + row * T::LDX);
 #pragma unroll
         for (int i = 0; i < T::MB; ++i) a[i] = g[i * 32];
@@ -403,36 +396,6 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
     }
 
     float *C = p.C + (long long)slice * p.sliceStride;
-    if constexpr (KS == 2) {
-        // the pair's second wave hands its blocks over through LDS (lane-contiguous, over the stage
-        // buffers, which nobody reads any more after the barrier); the first adds them to its own
-        static_assert(2 * T::MB * T::NB * 16 * 64 <= 2 * (T::G_STAGE + T::X_STAGE), "hand-over fits the stage buffers");
-        float *red = Gs + ((wave / KS) * T::MB * T::NB) * 16 * 64 + lane;
-        __syncthreads();
-        if (wk == 1) {
-#pragma unroll
-            for (int i = 0; i < T::MB; ++i)
-#pragma unroll
-                for (int j = 0; j < T::NB; ++j)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) red[((i * T::NB + j) * 16 + r) * 64] = acc2[i][j][r] + acc[i][j][r];
-        }
-        __syncthreads();
-        if (wk == 1) return;
-#pragma unroll
-        for (int i = 0; i < T::MB; ++i)
-#pragma unroll
-            for (int j = 0; j < T::NB; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc2[i][j][r] = (acc2[i][j][r] + acc[i][j][r]) + red[((i * T::NB + j) * 16 + r) * 64];
-    } else {
-#pragma unroll
-        for (int i = 0; i < T::MB; ++i)
-#pragma unroll
-            for (int j = 0; j < T::NB; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc2[i][j][r] += acc[i][j][r];
-    }
 #pragma unroll
     for (int i = 0; i < T::MB; ++i)
 #pragma unroll
@@ -441,16 +404,16 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int oc = oc0 + wm * T::WTM + i * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
-                if (oc < p.OC && col < Ktot) C[oc * Ktot + col] = acc2[i][j][r];
+                if (oc < p.OC && col < Ktot) C[oc * Ktot + col] = acc2[i][j][r] + acc[i][j][r];
             }
         }
 }
 
-template <int BM, int BN, bool PM, bool WIDE = false, int KS = 1>
+template <int BM, int BN, bool PM, bool WIDE = false>
 static hipError_t launch_fast_one(const WgradParams &p, int grid, hipStream_t st)
 {
-    constexpr size_t kSmemBytes = WF<BM, BN, KS>::SMEM_BYTES;
-    hipLaunchKernelGGL((wgrad_fast_kernel<BM, BN, PM, WIDE, KS>), dim3((unsigned)grid), dim3(kThreads), kSmemBytes, st, p);
+    constexpr size_t kSmemBytes = WF<BM, BN>::SMEM_BYTES;
+    hipLaunchKernelGGL((wgrad_fast_kernel<BM, BN, PM, WIDE>), dim3((unsigned)grid), dim3(kThreads), kSmemBytes, st, p);
     return hipGetLastError();
 }
 
@@ -490,11 +453,6 @@ hipError_t launch_wgrad_fast(const WgradParams &p, int bm, int bn, int grid, hip
         if (wide) return launch_fast_one<BM_, BN_, false, true>(p, grid, st);         \
         return p.posMajor ? launch_fast_one<BM_, BN_, true>(p, grid, st)              \
                           : launch_fast_one<BM_, BN_, false>(p, grid, st);            \
-    }
-    if (bm == 64 && bn == 64 && p.waveSplit == 2) {   // row halves of a stage on two waves, added through LDS
-        if (wide) return launch_fast_one<64, 64, false, true, 2>(p, grid, st);
-        return p.posMajor ? launch_fast_one<64, 64, true, false, 2>(p, grid, st)
-                          : launch_fast_one<64, 64, false, false, 2>(p, grid, st);
     }
     MI355CONV_WF(128, 128)
     MI355CONV_WF(64, 128)
