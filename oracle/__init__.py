@@ -44,8 +44,12 @@ def build(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = ctypes.CDLL(_LIB)
+        # ORACLE_CONV_LIB: another build of conv_oracle.c (the sanitizer test's instrumented one)
+        path = os.environ.get("ORACLE_CONV_LIB")
+        if not path:
+            build()
+            path = _LIB
+        lib = ctypes.CDLL(path)
         fp = ctypes.POINTER(ctypes.c_float)
         dp = ctypes.POINTER(ctypes.c_double)
         ints = [ctypes.c_int] * 11

@@ -11,7 +11,8 @@ import ctypes
 import os
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libmi355conv.so")
+# MI355CONV_LIB: another build of the same sources (the sanitizer test's host-instrumented one)
+LIB_PATH = os.environ.get("MI355CONV_LIB") or os.path.join(_PKG, "libmi355conv.so")
 
 OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT = 0, 1, 2
 VARIANT_AUTO, VARIANT_DIRECT, VARIANT_MFMA = -1, 0, 1

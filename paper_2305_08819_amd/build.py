@@ -42,6 +42,26 @@ def _compile(src: str, force: bool) -> str:
     return obj
 
 
+def build_host_sanitized(out_dir: str) -> str:
+    """A HOST-ONLY build of the library under AddressSanitizer + UndefinedBehaviorSanitizer: api.hip
+    (argument checks, planner, dealing, launch set-up) compiled as plain C++ with g++, the kernel
+    launchers replaced by stand-ins that report hipErrorNotSupported (host_only_stubs.cpp).  For the
+    CPU test that runs the host-only ABI tests under the sanitizers; it holds no device code and is
+    never used on a GPU."""
+    os.makedirs(out_dir, exist_ok=True)
+    lib = os.path.join(out_dir, "libmi355conv_hostsan.so")
+    rocm = os.path.dirname(os.path.dirname(os.path.realpath(HIPCC)))
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-fPIC", "-shared", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-D__HIP_PLATFORM_AMD__",
+           "-I" + os.path.join(rocm, "include"), "-x", "c++", os.path.join(CSRC, "api.hip"),
+           os.path.join(CSRC, "host_only_stubs.cpp"), "-o", lib, "-L" + os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("host-only sanitizer build failed:\n%s" % r.stderr[-4000:])
+    return lib
+
+
 def build(force: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=4) as ex:

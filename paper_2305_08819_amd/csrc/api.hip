@@ -20,6 +20,10 @@ using namespace mi355conv;
 // hipGetSymbolAddress; the address of each device's copy is looked up once and kept
 // (prepare_device), and only that address is ever handed to kernels.
 constexpr size_t kScratchBytes = (size_t)32 << 20;
+#if !defined(__HIPCC__)   // host-only sanitizer build (plain C++ compiler): the two HIP spellings below, as that compiler needs them
+#define __align__(n) __attribute__((aligned(n)))
+#define HIP_SYMBOL(x) (&(x))
+#endif
 static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 namespace {

@@ -48,11 +48,13 @@ inline FastDiv make_fastdiv(unsigned d)
     f.d = d;
     return f;
 }
+#if defined(__HIPCC__)
 __device__ __forceinline__ unsigned fast_div(unsigned n, const FastDiv &f)
 {
     const unsigned t = __umulhi(f.mul, n);
     return (t + ((n - t) >> f.sh1)) >> f.sh2;
 }
+#endif
 
 // ---- gather-GEMM (forward and backward-data) ------------------------------------------
 // C[row, col] = sum over taps t of the tile's tap set, channels c:
@@ -276,6 +278,7 @@ __host__ __device__ __forceinline__ int balance_slot(int bid, int grid)
     return (lap << 8) + (c & 7) * 32 + (c >> 3);
 }
 
+#if defined(__HIPCC__)   // device-side decode of the workgroup id
 // Rank of workgroup id `bid` under the host's longest-first dealing.  Lane i looks at run i
 // (there are fewer than 64): the run is the last one that starts at or before the slot.
 __device__ __forceinline__ int balanced_rank(int bid, int grid, const BalanceRuns &b)
@@ -335,6 +338,7 @@ __device__ __forceinline__ int xcd_remap(int bid, int grid, int unit)
     const int x = bid % kXcds, q = bid / kXcds;
     return ((q / unit) * kXcds + x) * unit + q % unit;
 }
+#endif   // __HIPCC__
 
 // ---- what each launcher takes, as host-side predicates ---------------------------------------
 // The planner checks every plan against the same predicate that the launcher applies, so a plan
