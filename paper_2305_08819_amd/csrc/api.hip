@@ -60,6 +60,10 @@ struct Plan {
     BalanceRuns runs = {};
     unsigned char order[256] = {};   // rank -> position (gather) or tap (backward-weight)
     unsigned char unitWork[256] = {}; // length of unit u (taps / live positions), by rank
+    // classes of units of equal length (gather operators): first unit and unit count of each
+    int nClasses = 0;
+    int classFirstUnit[kMaxBalanceClasses] = {};
+    int classUnits[kMaxBalanceClasses] = {};
 };
 
 int out_extent(int in, int pad, int f, int stride)
@@ -674,6 +678,8 @@ void fill_gather_params(GatherGemmParams &g, const Plan &pl)
     g.xcdWhole = (pl.grid / span) * span;
     g.grid = pl.grid;
     g.runsN = 0;
+    g.classesN = 0;
+    for (int c = 0; c < kMaxBalanceClasses; ++c) g.classes.rankStart[c] = 0x7fffffff;   // unused classes never match
     for (int i = 0; i < kMaxBalanceRuns; ++i) g.runs.idStart[i] = 0x7fffffff;   // unused run entries never match
 }
 
@@ -848,6 +854,22 @@ void plan_balance_gather(const Shape &s, Plan &pl, bool bwd)
     const int resident = pl.bm * pl.bn <= 64 * 64 ? 4 : 2;
     build_balance_runs(work, nPos, pl.itemsPerClassUnit, pl.grid, resident, &pl.runs);
     pl.balance = 1;
+    // Classes of positions with equal tap counts (neighbours in the ranking).  The class-wise rank
+    // order keeps a filter slice on one XCD at the price of spreading a row tile's column tiles over
+    // XCDs, so it is used where the filter is the larger operand and does not fit an XCD's 4 MB L2.
+    pl.nClasses = 0;
+    const long long wBytes = 4LL * s.OC * s.FH * s.FW * s.IC;
+    const long long aBytes = 4LL * s.N * (bwd ? (long long)s.OH * s.OW * s.OC : (long long)s.IH * s.IW * s.IC);
+    const bool filterHeavy = wBytes > (2LL << 20) && wBytes >= aBytes;
+    for (int i = 0; i < nPos && filterHeavy; ++i) {
+        if (i == 0 || work[i] != work[i - 1]) {
+            if (pl.nClasses == kMaxBalanceClasses) { pl.nClasses = 0; break; }   // too many: unit-wise order
+            pl.classFirstUnit[pl.nClasses] = i;
+            pl.classUnits[pl.nClasses] = 0;
+            ++pl.nClasses;
+        }
+        ++pl.classUnits[pl.nClasses - 1];
+    }
 }
 
 // Backward-weight in (oh,ow,n) order: rank the taps by the number of output positions at which
@@ -1011,6 +1033,12 @@ int run_gather(const float *A, const float *B, float *out, const Shape &s, const
             g.runs.rankStart[i] = pl.runs.rankStart[i];
         }
         memcpy(g.posOrder, pl.order, sizeof g.posOrder);
+        g.classes.n = g.classesN = pl.nClasses;
+        for (int c = 0; c < pl.nClasses; ++c) {
+            g.classes.rankStart[c] = pl.classFirstUnit[c] * pl.itemsPerClassUnit;
+            g.classes.firstUnit[c] = pl.classFirstUnit[c];
+            g.classes.divRows[c] = make_fastdiv((unsigned)(pl.classUnits[c] * g.rowTilesPerPos));
+        }
     }
     g.divRowTilesPerPos = make_fastdiv((unsigned)g.rowTilesPerPos);
     hipError_t e = pl.elem ? launch_gather_elem(g, bwd, pl.bm, pl.bn, pl.grid, st)

@@ -31,6 +31,13 @@ struct BalanceRuns {
     int rankStart[kMaxBalanceRuns];
 };
 
+// Work items of equal length form a class (a contiguous range of ranks).  Inside a class the ranks
+// enumerate the items with the operand-sharing index slowest: consecutive ranks - which the dealing
+// keeps on one XCD - differ in the pixel position / row tile and share the filter slice, so a slice
+// of W is fetched into an XCD's L2 once for all positions instead of once per position.
+constexpr int kMaxBalanceClasses = 32;
+struct BalanceClasses;   // defined after FastDiv
+
 // Division by a launch-invariant divisor with one multiply-high and two shifts (round-up
 // method of Granlund & Montgomery, "Division by invariant integers using multiplication").
 // Exact for every 32-bit unsigned n and 1 <= d < 2^31.
@@ -55,6 +62,13 @@ __device__ __forceinline__ unsigned fast_div(unsigned n, const FastDiv &f)
     return (t + ((n - t) >> f.sh1)) >> f.sh2;
 }
 #endif
+
+struct BalanceClasses {
+    int n;                                  // 0: ranks enumerate unit by unit (no class-wise order)
+    int rankStart[kMaxBalanceClasses];      // first rank of the class; INT_MAX for unused entries
+    int firstUnit[kMaxBalanceClasses];      // first unit (position rank) of the class
+    FastDiv divRows[kMaxBalanceClasses];    // by units of the class * row tiles per unit
+};
 
 // ---- gather-GEMM (forward and backward-data) ------------------------------------------
 // C[row, col] = sum over taps t of the tile's tap set, channels c:
@@ -105,11 +119,15 @@ struct GatherGemmParams {
     int xcdWhole;            // workgroup ids below this are remapped (a whole number of 8 * xcdUnit)
     int grid;                // workgroups of the launch
     int runsN;               // runs.n, among the scalars fetched first
+    int classesN;            // classes.n, likewise
     int phaseStart[kMaxPhases];   // first row tile of each phase; INT_MAX past the last phase
     GatherPhase phase[kMaxPhases];
     BalanceRuns runs;
     unsigned char posOrder[kMaxBalancedPositions];
+    BalanceClasses classes;
 };
+
+static_assert(sizeof(GatherGemmParams) <= 4096, "kernel arguments are limited to 4 KB");
 
 // The scalar fields of GatherGemmParams held in SGPRs from the kernel's first instructions on:
 // the compiler otherwise fetches each kernel argument where it is first used, one dependent
@@ -127,7 +145,7 @@ struct GatherView {
     float slope;
     const float *bias;
     FastDiv divN, divTilesN, divSplit, divRowTilesPerPos, divChunksPerTap, divDHW, divDW, divXcdUnit;
-    int xcdWhole, grid, runsN;
+    int xcdWhole, grid, runsN, classesN;
     const int *phaseStart;
     const GatherPhase *phase;
     const BalanceRuns &runs;
@@ -140,7 +158,7 @@ __device__ __forceinline__ GatherView gather_view(const GatherGemmParams &p)
     GatherView v{p.A, p.B, p.C, p.aBytes, p.bBytes, p.Nimg, p.SH, p.SW, p.SC, p.DH, p.DW, p.DC, p.FH, p.FW,
                  p.sh, p.sw, p.ph, p.pw, p.posMajor, p.split, p.sliceStride, p.tilesN, p.xcdUnit, p.nPhases,
                  p.balance, p.rowTilesPerPos, p.epilogue, p.slope, p.bias, p.divN, p.divTilesN, p.divSplit, p.divRowTilesPerPos,
-                 p.divChunksPerTap, p.divDHW, p.divDW, p.divXcdUnit, p.xcdWhole, p.grid, p.runsN, p.phaseStart, p.phase, p.runs, p.posOrder};
+                 p.divChunksPerTap, p.divDHW, p.divDW, p.divXcdUnit, p.xcdWhole, p.grid, p.runsN, p.classesN, p.phaseStart, p.phase, p.runs, p.posOrder};
     MI355CONV_PIN(v.A); MI355CONV_PIN(v.B); MI355CONV_PIN(v.C);
     MI355CONV_PIN(v.aBytes); MI355CONV_PIN(v.bBytes);
     MI355CONV_PIN(v.Nimg); MI355CONV_PIN(v.SH); MI355CONV_PIN(v.SW); MI355CONV_PIN(v.SC);
@@ -157,7 +175,7 @@ __device__ __forceinline__ GatherView gather_view(const GatherGemmParams &p)
     MI355CONV_PIN(v.divDHW.mul); MI355CONV_PIN(v.divDHW.sh1); MI355CONV_PIN(v.divDHW.sh2);
     MI355CONV_PIN(v.divDW.mul); MI355CONV_PIN(v.divDW.sh1); MI355CONV_PIN(v.divDW.sh2);
     MI355CONV_PIN(v.divXcdUnit.mul); MI355CONV_PIN(v.divXcdUnit.sh1); MI355CONV_PIN(v.divXcdUnit.sh2);
-    MI355CONV_PIN(v.xcdWhole); MI355CONV_PIN(v.grid); MI355CONV_PIN(v.runsN);
+    MI355CONV_PIN(v.xcdWhole); MI355CONV_PIN(v.grid); MI355CONV_PIN(v.runsN); MI355CONV_PIN(v.classesN);
     return v;
 }
 #endif
@@ -298,6 +316,8 @@ __device__ __forceinline__ int balanced_rank(int bid, int grid, const BalanceRun
 struct BalancePrefetch {
     int runId, runRank;   // lane i: run i
     unsigned order4;      // lane i: entries 4i .. 4i+3 of the 256-entry order table
+    int clsRank, clsFirst;                      // lane i: class i
+    unsigned clsMul, clsSh1, clsSh2, clsD;      // lane i: class i's divisor
 };
 __device__ __forceinline__ BalancePrefetch balance_prefetch(const BalanceRuns &runs, const unsigned char *order)
 {
@@ -307,7 +327,35 @@ __device__ __forceinline__ BalancePrefetch balance_prefetch(const BalanceRuns &r
     b.runId = lane < kMaxBalanceRuns ? runs.idStart[lane] : 0x7fffffff;
     b.runRank = lane < kMaxBalanceRuns ? runs.rankStart[lane] : 0;
     b.order4 = reinterpret_cast<const unsigned *>(order)[lane];
+    b.clsRank = 0x7fffffff;
+    b.clsFirst = 0;
+    b.clsMul = b.clsSh1 = b.clsSh2 = b.clsD = 0;
     return b;
+}
+__device__ __forceinline__ void balance_prefetch_classes(BalancePrefetch &b, const BalanceClasses &c)
+{
+    static_assert(kMaxBalanceClasses <= 64, "one lane per class");
+    const int lane = threadIdx.x & 63;
+    if (lane < kMaxBalanceClasses) {
+        b.clsRank = c.rankStart[lane];
+        b.clsFirst = c.firstUnit[lane];
+        b.clsMul = c.divRows[lane].mul; b.clsSh1 = c.divRows[lane].sh1; b.clsSh2 = c.divRows[lane].sh2; b.clsD = c.divRows[lane].d;
+    }
+}
+// Class of a rank and, from there, the rank's place inside it: q = rank - first rank of the class,
+// inner = q / rows (rows = units of the class * row tiles per unit), row = q % rows.
+__device__ __forceinline__ void balance_class_decode(const BalancePrefetch &b, int rank, int *firstUnit, int *inner, int *row)
+{
+    const int c = __popcll(__ballot(rank >= b.clsRank)) - 1;   // rankStart[0] == 0, unused entries INT_MAX
+    const int q = rank - __builtin_amdgcn_readlane(b.clsRank, c);
+    FastDiv f;
+    f.mul = (unsigned)__builtin_amdgcn_readlane((int)b.clsMul, c);
+    f.sh1 = (unsigned)__builtin_amdgcn_readlane((int)b.clsSh1, c);
+    f.sh2 = (unsigned)__builtin_amdgcn_readlane((int)b.clsSh2, c);
+    f.d = (unsigned)__builtin_amdgcn_readlane((int)b.clsD, c);
+    *firstUnit = __builtin_amdgcn_readlane(b.clsFirst, c);
+    *inner = (int)fast_div((unsigned)q, f);
+    *row = q - *inner * (int)f.d;
 }
 __device__ __forceinline__ int balanced_rank(int bid, int grid, const BalancePrefetch &b)
 {

@@ -54,13 +54,24 @@ __device__ __forceinline__ GatherTile gather_tile_setup(const P &p, const Balanc
     const int tid = threadIdx.x;
     int bid = p.balance && p.runsN ? balanced_rank(blockIdx.x, p.grid, pre)
                                     : xcd_remap_fast(blockIdx.x, p.xcdWhole, p.xcdUnit, p.divXcdUnit);
-    const int rest = (int)fast_div((unsigned)bid, p.divTilesN);
-    const int tn = bid - rest * p.tilesN;
-    int tmGlobal = (int)fast_div((unsigned)rest, p.divSplit);
-    const int slice = rest - tmGlobal * p.split;
-    if (p.balance) {   // row tiles are enumerated by position rank
-        const int rank = (int)fast_div((unsigned)tmGlobal, p.divRowTilesPerPos);
-        tmGlobal = balance_order(pre, rank) * p.rowTilesPerPos + (tmGlobal - rank * p.rowTilesPerPos);
+    int tn, tmGlobal, slice;
+    if (p.balance && p.classesN) {
+        // class-wise enumeration: (slice, column tile) slow, (position, row tile) fast - see BalanceClasses
+        int firstUnit, inner, row;
+        balance_class_decode(pre, bid, &firstUnit, &inner, &row);
+        slice = (int)fast_div((unsigned)inner, p.divTilesN);
+        tn = inner - slice * p.tilesN;
+        const int unit = (int)fast_div((unsigned)row, p.divRowTilesPerPos);
+        tmGlobal = balance_order(pre, firstUnit + unit) * p.rowTilesPerPos + (row - unit * p.rowTilesPerPos);
+    } else {
+        const int rest = (int)fast_div((unsigned)bid, p.divTilesN);
+        tn = bid - rest * p.tilesN;
+        tmGlobal = (int)fast_div((unsigned)rest, p.divSplit);
+        slice = rest - tmGlobal * p.split;
+        if (p.balance) {   // row tiles are enumerated by position rank
+            const int rank = (int)fast_div((unsigned)tmGlobal, p.divRowTilesPerPos);
+            tmGlobal = balance_order(pre, rank) * p.rowTilesPerPos + (tmGlobal - rank * p.rowTilesPerPos);
+        }
     }
     // Forward and unit-stride backward-data have one phase that holds all pixels and all taps: its
     // record is made up from the scalar arguments.  Only strided backward-data

@@ -23,7 +23,8 @@ __global__ __launch_bounds__(kThreads, 2) void gather_elem_kernel(const GatherGe
     int *outRow = rowX + BM;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const BalancePrefetch pre = balance_prefetch(p.runs, p.posOrder);
+    BalancePrefetch pre = balance_prefetch(p.runs, p.posOrder);
+    balance_prefetch_classes(pre, p.classes);
     const GatherTile tile = gather_tile_setup<BM, BN, BWD>(p, pre, rowBase, rowY, rowX, outRow);
     const int slice = tile.slice, n0 = tile.n0;
 

@@ -37,7 +37,8 @@ namespace mi355conv {
 template <int BM, int BN, int WAVES_M, bool BWD, bool BELEM = false, bool RAGGED = false>
 __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGemmParams params)
 {
-    const BalancePrefetch pre = balance_prefetch(params.runs, params.posOrder);   // in flight with the scalar arguments
+    BalancePrefetch pre = balance_prefetch(params.runs, params.posOrder);   // in flight with the scalar arguments
+    balance_prefetch_classes(pre, params.classes);
     const GatherView p = gather_view(params);
     using T = GG<BM, BN, WAVES_M, BWD>;
     extern __shared__ f4 smem_raw[];

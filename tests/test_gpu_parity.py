@@ -393,7 +393,10 @@ def test_fully_connected_as_1x1_convolution():
 
 
 @pytest.mark.parametrize("shp,split", [((128, 5, 3, 64, 256, 3, 3, 1, 1), 8), ((128, 3, 3, 64, 192, 3, 3, 1, 1), 5),
-                                       ((64, 6, 6, 32, 128, 5, 5, 1, 2), 4)])
+                                       ((64, 6, 6, 32, 128, 5, 5, 1, 2), 4),
+                                       # filter larger than the activations and than an XCD's L2: ranks enumerate
+                                       # class by class with the (slice, column tile) index slowest
+                                       ((64, 3, 3, 256, 512, 3, 3, 1, 1), 8), ((128, 4, 3, 160, 544, 3, 3, 1, 1), 3)])
 def test_balanced_dealing_odd_grids(shp, split):
     """(y,x,n) row order with grids that are not multiples of 256 and maps that are not square: the
     longest-first dealing (a permutation of the workgroups) must leave every result intact."""
