@@ -14,7 +14,10 @@ and leaky-ReLU of the paper's layer constructors on top of ``conv2d_fwd`` in
 plain numpy fp64 and is pinned by hand-computed values and its special cases
 (slope 1, slope 0, zero bias); ``conv2d_fwd_u8`` converts 8-bit pixels to
 fp32 (byte * scale, rounded once to fp32) before ``conv2d_fwd`` and is pinned
-by hand values, the scale-1 case and its linearity in the scale.
+by hand values, the scale-1 case and its linearity in the scale; ``matmul``
+(the fully-connected layer's matrix multiply, plain C loops in fp64) is pinned
+by hand values, identity and all-ones closed forms, its transposition
+identities, numpy's fp64 matmul and the 1x1 convolution on a 1x1 map.
 """
 from __future__ import annotations
 
@@ -57,6 +60,8 @@ def _load():
             fn = getattr(lib, name)
             fn.argtypes = [fp, fp, dp] + ints
             fn.restype = None
+        lib.oracle_matmul.argtypes = [fp, fp, dp] + [ctypes.c_int] * 5
+        lib.oracle_matmul.restype = None
         lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -166,3 +171,17 @@ def conv2d_fwd_u8(X8, scale, W, stride=1, pad=0):
     assert x8.dtype == np.uint8 and x8.ndim == 4
     x = x8.astype(np.float32) * np.float32(scale)
     return conv2d_fwd(x, W, stride, pad)
+
+
+def matmul(A, B, transpose_a=False, transpose_b=False):
+    """C = op(A) @ op(B) in fp64 for fp32 row-major matrices (op = transpose where asked): the matrix
+    multiply of the paper's fully-connected layer (Fig. 2 ``fullconnect``; Sec. II ``matMul`` /
+    ``matMulT1``), as plain C loops with one fp64 accumulator per output element."""
+    A, B = _f32(A, 2), _f32(B, 2)
+    M, K = (A.shape[1], A.shape[0]) if transpose_a else A.shape
+    K2, N = (B.shape[1], B.shape[0]) if transpose_b else B.shape
+    assert K == K2, (A.shape, B.shape, transpose_a, transpose_b)
+    C = np.zeros((M, N), dtype=np.float64)
+    if C.size and K:
+        _load().oracle_matmul(_fp(A), _fp(B), _dp(C), M, N, K, int(bool(transpose_a)), int(bool(transpose_b)))
+    return C

@@ -145,3 +145,23 @@ void oracle_conv2d_bwd_weight(const float *X, const float *G, double *dW,
             }
     }
 }
+
+/* Matrix multiply of the paper's fully-connected layer (Fig. 2 fullconnect; Sec. II names the
+ * operator family matMul / matMulT1): C[M,N] = op(A) * op(B) in fp64, row-major operands,
+ *   ta == 0: op(A)[i,k] = A[i*K + k]  (A is M x K)      ta != 0: op(A)[i,k] = A[k*M + i]  (A is K x M)
+ *   tb == 0: op(B)[k,j] = B[k*N + j]  (B is K x N)      tb != 0: op(B)[k,j] = B[j*K + k]  (B is N x K)
+ * One accumulator per output element, the definition written out. */
+void oracle_matmul(const float *A, const float *B, double *C, int M, int N, int K, int ta, int tb)
+{
+#pragma omp parallel for schedule(static)
+    for (i64 i = 0; i < M; ++i)
+        for (int j = 0; j < N; ++j) {
+            double acc = 0.0;
+            for (int k = 0; k < K; ++k) {
+                const double a = ta ? (double)A[(i64)k * M + i] : (double)A[i * K + k];
+                const double b = tb ? (double)B[(i64)j * K + k] : (double)B[(i64)k * N + j];
+                acc += a * b;
+            }
+            C[i * N + j] = acc;
+        }
+}

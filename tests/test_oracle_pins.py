@@ -373,3 +373,78 @@ def test_planted_mistakes_fail_the_pins():
     for mistake in ("flipped filter", "transposed filter", "swapped stride", "swapped padding",
                     "padding on the far side", "dropped last tap"):
         assert not _pins_hold(lambda X, W, s, p: _fwd_with_mistake(X, W, s, p, mistake)), mistake
+
+
+# ---- matrix multiply of the fully-connected layer -------------------------------------------------
+def test_matmul_hand_values_and_closed_forms():
+    # values worked out by hand: [[1,2,3],[4,5,6]] x [[1,0],[0,1],[2,-1]] = [[7,-1],[16,-1]]
+    A = np.array([[1, 2, 3], [4, 5, 6]], dtype=np.float32)
+    B = np.array([[1, 0], [0, 1], [2, -1]], dtype=np.float32)
+    assert np.array_equal(oracle.matmul(A, B), np.array([[7, -1], [16, -1]], dtype=np.float64))
+    # the same product with either operand stored transposed
+    assert np.array_equal(oracle.matmul(np.ascontiguousarray(A.T), B, transpose_a=True), [[7, -1], [16, -1]])
+    assert np.array_equal(oracle.matmul(A, np.ascontiguousarray(B.T), transpose_b=True), [[7, -1], [16, -1]])
+    # identity and all-ones closed forms (M, N, K all different, so a swapped extent cannot pass)
+    X = wl.uniform_pm1(wl.stream_key("mm-id"), (5, 7))
+    assert np.array_equal(oracle.matmul(X, np.eye(7, dtype=np.float32)), X.astype(np.float64))
+    assert np.array_equal(oracle.matmul(np.eye(5, dtype=np.float32), X), X.astype(np.float64))
+    assert np.array_equal(oracle.matmul(np.ones((3, 11), np.float32), np.ones((11, 4), np.float32)), np.full((3, 4), 11.0))
+
+
+def test_matmul_against_numpy_and_transposition_identities():
+    k = wl.stream_key("mm")
+    for i, (M, N, K) in enumerate([(1, 1, 1), (3, 5, 7), (17, 2, 33), (8, 40, 5), (64, 10, 512)]):
+        A = wl.uniform_pm1(k + 2 * i, (M, K))
+        B = wl.uniform_pm1(k + 2 * i + 1, (K, N))
+        ref = A.astype(np.float64) @ B.astype(np.float64)          # library routine
+        for ta in (False, True):
+            for tb in (False, True):
+                a = np.ascontiguousarray(A.T) if ta else A
+                b = np.ascontiguousarray(B.T) if tb else B
+                got = oracle.matmul(a, b, ta, tb)
+                assert got.shape == (M, N)
+                assert np.max(np.abs(got - ref)) <= 1e-12 * max(1.0, np.max(np.abs(ref))), (M, N, K, ta, tb)
+        # (A B)^T = B^T A^T
+        assert np.allclose(oracle.matmul(A, B).T, oracle.matmul(np.ascontiguousarray(B.T), np.ascontiguousarray(A.T)), rtol=0, atol=1e-12)
+
+
+def test_matmul_is_the_1x1_convolution_on_a_1x1_map():
+    """Y = X W^T of a fully-connected layer equals the forward convolution of a 1x1 map with a 1x1
+    filter, and its two gradients equal backward-data and backward-weight of that convolution."""
+    k = wl.stream_key("mm-conv")
+    M, K, N = 6, 20, 9
+    X = wl.uniform_pm1(k, (M, K))
+    W = wl.uniform_pm1(k + 1, (N, K))
+    G = wl.uniform_pm1(k + 2, (M, N))
+    y = oracle.conv2d_fwd(X.reshape(M, 1, 1, K), W.reshape(N, 1, 1, K)).reshape(M, N)
+    assert np.max(np.abs(oracle.matmul(X, W, transpose_b=True) - y)) <= 1e-12
+    dx = oracle.conv2d_bwd_data(G.reshape(M, 1, 1, N), W.reshape(N, 1, 1, K), (1, 1)).reshape(M, K)
+    assert np.max(np.abs(oracle.matmul(G, W) - dx)) <= 1e-12
+    dw = oracle.conv2d_bwd_weight(X.reshape(M, 1, 1, K), G.reshape(M, 1, 1, N), (1, 1)).reshape(N, K)
+    assert np.max(np.abs(oracle.matmul(G, X, transpose_a=True) - dw)) <= 1e-12
+
+
+def test_matmul_planted_mistakes_fail_the_pins():
+    """Copies of the definition with one mistake each (wrong transposition flag, swapped extents)
+    must disagree with the hand values or numpy."""
+    A = np.array([[1, 2, 3], [4, 5, 6]], dtype=np.float32)
+    B = np.array([[1, 0], [0, 1], [2, -1]], dtype=np.float32)
+    want = np.array([[7, -1], [16, -1]], dtype=np.float64)
+
+    def mm(A, B, ta, tb, M, N, K):
+        C = np.zeros((M, N))
+        for i in range(M):
+            for j in range(N):
+                for kk in range(K):
+                    a = A.ravel()[kk * M + i] if ta else A.ravel()[i * K + kk]
+                    b = B.ravel()[j * K + kk] if tb else B.ravel()[kk * N + j]
+                    C[i, j] += float(a) * float(b)
+        return C
+    assert np.array_equal(mm(A, B, 0, 0, 2, 2, 3), want)                   # the faithful copy passes
+    assert not np.array_equal(mm(A, B, 1, 0, 2, 2, 3), want)               # A read as if stored transposed
+    assert not np.array_equal(mm(A, B, 0, 1, 2, 2, 3), want)               # B read as if stored transposed
+    A2 = wl.uniform_pm1(wl.stream_key("mm-plant"), (3, 4))
+    B2 = wl.uniform_pm1(wl.stream_key("mm-plant") + 1, (4, 5))
+    ref = A2.astype(np.float64) @ B2.astype(np.float64)
+    assert np.allclose(mm(A2, B2, 0, 0, 3, 5, 4), ref)
+    assert not np.allclose(mm(A2, B2, 0, 0, 3, 5, 3), ref)                 # one reduction term dropped
