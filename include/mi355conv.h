@@ -188,6 +188,19 @@ int conv2d_bwd_weight_noalloc(const float *X, const float *dY, float *dW, const 
                               void *stream);
 size_t conv2d_noalloc_scratch_bytes(void);
 
+/* Matrix multiply of the paper's fully-connected layer (Fig. 2 fullconnect; Sec. II names the
+ * operator family matMul / matMulT1), served by the 1x1 operators on a 1x1 map - dense fp32
+ * row-major matrices, device pointers, 16-byte aligned, C overwritten:
+ *   MI355CONV_MATMUL_NT  C[M,N] = A[M,K] * B[N,K]^T    the layer's forward      Y  = X  W^T
+ *   MI355CONV_MATMUL_NN  C[M,N] = A[M,K] * B[K,N]      its input gradient       dX = dY W
+ *   MI355CONV_MATMUL_TN  C[M,N] = A[K,M]^T * B[K,N]    its weight gradient      dW = dY^T X
+ * Workspace, stream, errors and enqueue-only behaviour as for the convolution entry points;
+ * matmul_workspace_bytes gives the workspace size (0 on invalid arguments). */
+enum { MI355CONV_MATMUL_NT = 0, MI355CONV_MATMUL_NN = 1, MI355CONV_MATMUL_TN = 2 };
+size_t matmul_workspace_bytes(int kind, int M, int N, int K);
+int matmul_f32(int kind, const float *A, const float *B, float *C, int M, int N, int K,
+               void *ws, size_t ws_bytes, void *stream);
+
 /* Measurement aid (not an operator): launches a register-only v_mfma_f32_32x32x2_f32 loop with
  * valu_per_8_mfma in {0, 16, 48, 96} ordinary vector instructions per 8 matrix instructions, on
  * `workgroups` workgroups of 256 threads, `iters` x 8 matrix instructions per wave, i.e.

@@ -22,7 +22,8 @@ EXPORTS = ("conv2d_workspace_bytes", "conv2d_query_plan", "conv2d_query_workgrou
            "conv2d_fwd_bias_act", "conv2d_fwd_u8",
            "conv2d_bwd_data", "deconv2d", "conv2d_bwd_weight", "conv2d_status_string",
            "conv2d_last_hip_error", "conv2d_init", "conv2d_bwd_weight_noalloc", "conv2d_noalloc_scratch_bytes",
-           "conv2d_probe_mfma_rate")
+           "conv2d_probe_mfma_rate", "matmul_workspace_bytes", "matmul_f32")
+MATMUL_NT, MATMUL_NN, MATMUL_TN = 0, 1, 2
 
 
 class ConvDesc(ctypes.Structure):
@@ -97,6 +98,10 @@ def load() -> ctypes.CDLL:
         lib.conv2d_noalloc_scratch_bytes.restype = ctypes.c_size_t
         lib.conv2d_probe_mfma_rate.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
         lib.conv2d_probe_mfma_rate.restype = ctypes.c_int
+        lib.matmul_workspace_bytes.argtypes = [ctypes.c_int] * 4
+        lib.matmul_workspace_bytes.restype = ctypes.c_size_t
+        lib.matmul_f32.argtypes = [ctypes.c_int, vp, vp, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t, vp]
+        lib.matmul_f32.restype = ctypes.c_int
         lib.conv2d_status_string.argtypes = [ctypes.c_int]
         lib.conv2d_status_string.restype = ctypes.c_char_p
         lib.conv2d_last_hip_error.argtypes = []
@@ -288,3 +293,24 @@ def conv2d_probe_mfma_rate(valu_per_8_mfma, workgroups, iters, out, stream=None)
     if rc != 0:
         raise Mi355ConvError(rc, "conv2d_probe_mfma_rate")
     return workgroups * 4 * iters * 8 * 4096
+
+
+def matmul_workspace_bytes(kind: int, M: int, N: int, K: int) -> int:
+    return int(load().matmul_workspace_bytes(kind, M, N, K))
+
+
+def matmul_f32(kind, A, B, C, ws=None, stream=None):
+    """C[M,N] <- A B^T (MATMUL_NT), A B (MATMUL_NN) or A^T B (MATMUL_TN): the fully-connected layer's
+    forward, input gradient and weight gradient; enqueue only."""
+    M, N = C.shape
+    K = A.shape[0] if kind == MATMUL_TN else A.shape[1]
+    _check(A, (K, M) if kind == MATMUL_TN else (M, K), "A")
+    _check(B, (N, K) if kind == MATMUL_NT else (K, N), "B")
+    _check(C, (M, N), "C")
+    if ws is None:
+        ws = _own_workspace(matmul_workspace_bytes(kind, M, N, K), C, stream)
+    nbytes = ws.numel() * ws.element_size() if ws is not None else 0
+    rc = load().matmul_f32(kind, _ptr(A), _ptr(B), _ptr(C), M, N, K, _ptr(ws), nbytes, _stream_handle(stream))
+    if rc != 0:
+        raise Mi355ConvError(rc, "matmul_f32")
+    return C

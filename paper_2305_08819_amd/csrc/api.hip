@@ -1174,9 +1174,10 @@ static int fwd_impl(const float *X, const float *W, float *Y, const conv2d_desc 
         q.divOW = make_fastdiv((unsigned)s.OW);
         q.divIC = make_fastdiv((unsigned)s.IC);
         q.divFW = make_fastdiv((unsigned)s.FW);
+        q.epilogue = epi.on ? 1 : 0;
+        q.bias = epi.bias;
+        q.slope = epi.slope;
         hipError_t e = launch_fwd_small_ic(q, st);
-        if (e == hipSuccess && epi.on)
-            e = launch_bias_act(Y, (long long)s.N * s.OH * s.OW * s.OC, epi.bias, epi.slope, s.OC, st);
         return e == hipSuccess ? MI355CONV_OK : hip_fail(e);
     }
     return run_gather(X, W, Y, s, pl, false, ws, st, epi);
@@ -1363,6 +1364,42 @@ int conv2d_bwd_weight_noalloc(const float *X, const float *dY, float *dW, const 
 size_t conv2d_noalloc_scratch_bytes(void) { return kScratchBytes; }
 
 int conv2d_init(void) { return prepare_device(nullptr); }
+
+// The matrix multiplies of a fully-connected layer as the 1x1 operators on a 1x1 map: the rows of the
+// left matrix are the "images".
+static int matmul_desc(int kind, int M, int N, int K, conv2d_desc *d, int *op)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return MI355CONV_ERR_BAD_DIM;
+    conv2d_desc t = {0, 1, 1, 0, 0, 1, 1, 1, 1, 0, 0};
+    switch (kind) {
+    case MI355CONV_MATMUL_NT: t.N = M; t.IC = K; t.OC = N; *op = MI355CONV_OP_FWD; break;         // Y[M,N] = X[M,K] W[N,K]^T
+    case MI355CONV_MATMUL_NN: t.N = M; t.IC = N; t.OC = K; *op = MI355CONV_OP_BWD_DATA; break;    // dX[M,N] = dY[M,K] W[K,N]
+    case MI355CONV_MATMUL_TN: t.N = K; t.IC = N; t.OC = M; *op = MI355CONV_OP_BWD_WEIGHT; break;  // dW[M,N] = dY[K,M]^T X[K,N]
+    default: return MI355CONV_ERR_UNSUPPORTED;
+    }
+    *d = t;
+    return MI355CONV_OK;
+}
+
+size_t matmul_workspace_bytes(int kind, int M, int N, int K)
+{
+    conv2d_desc d;
+    int op = 0;
+    if (matmul_desc(kind, M, N, K, &d, &op) != MI355CONV_OK) return 0;
+    return conv2d_workspace_bytes(op, &d);
+}
+
+int matmul_f32(int kind, const float *A, const float *B, float *C, int M, int N, int K, void *ws, size_t ws_bytes,
+               void *stream)
+{
+    conv2d_desc d;
+    int op = 0;
+    const int rc = matmul_desc(kind, M, N, K, &d, &op);
+    if (rc != MI355CONV_OK) return rc;
+    if (op == MI355CONV_OP_FWD) return conv2d_fwd(A, B, C, &d, ws, ws_bytes, stream);
+    if (op == MI355CONV_OP_BWD_DATA) return conv2d_bwd_data(A, B, C, &d, ws, ws_bytes, stream);
+    return conv2d_bwd_weight(B, A, C, &d, ws, ws_bytes, stream);   // (X, dY, dW) = (B, A, C)
+}
 
 const char *conv2d_status_string(int status)
 {

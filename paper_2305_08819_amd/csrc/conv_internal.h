@@ -277,6 +277,10 @@ struct SmallIcParams {
     // forward only: X holds unsigned bytes, converted on load as (float)byte * scale
     int u8;
     float scale;
+    // forward only: out = act(acc + bias[oc]) before the store (epilogue == 0: plain store)
+    int epilogue;
+    float slope;
+    const float *bias;    // may be null
 };
 
 // MI355X spreads consecutive workgroup ids round-robin over its 8 XCDs, each with its own

@@ -246,6 +246,18 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_small_ic_kernel(const SmallIc
             acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa, b[j * 32 * LDf + 2 * step], acc[j], 0, 0, 0);
     }
     // accumulator register q of lane l is row 8*(q/4)+4*(l/32)+q%4, column l%32
+    if (p.epilogue) {   // uniform: bias add and leaky-ReLU in the accumulator registers
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int col = oc0 + j * 32 + l32;
+            const float b = p.bias && col < p.OC ? p.bias[col] : 0.f;
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const float v = acc[j][q] + b;
+                acc[j][q] = v > 0.f ? v : v * p.slope;
+            }
+        }
+    }
     if ((p.OC & 3) == 0) {
         // the kernel is bound by writing Y: turn each 32x32 block through LDS (the tiles are done
         // with) so that a lane stores 16 bytes and a store instruction covers eight 128-byte runs

@@ -22,7 +22,7 @@ def lib():
 def test_exports_match_header(lib):
     hdr = open(os.path.join(ROOT, "include", "mi355conv.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    declared = set(re.findall(r"\b(conv2d_\w+|deconv2d)\s*\(", hdr))
+    declared = set(re.findall(r"\b(conv2d_\w+|deconv2d|matmul_\w+)\s*\(", hdr))
     assert declared == set(mc.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
@@ -250,3 +250,15 @@ def test_noalloc_argument_errors_before_any_hip_call(lib):
         assert call(256, 512, 768, big) == -3       # needs more than the library's array
     finally:
         mc.conv2d_set_tuning(mc.VARIANT_AUTO, 0)
+
+
+def test_matmul_argument_errors_and_plans_before_any_hip_call(lib):
+    def call(kind, a, b, c, M, N, K):
+        return lib.matmul_f32(kind, ctypes.c_void_p(a), ctypes.c_void_p(b), ctypes.c_void_p(c), M, N, K, ctypes.c_void_p(0), 0, None)
+    assert call(mc.MATMUL_NT, 0, 512, 768, 4, 4, 4) == -1
+    assert call(mc.MATMUL_NN, 256, 516, 768, 4, 4, 4) == -4
+    assert call(mc.MATMUL_TN, 256, 512, 768, 0, 4, 4) == -2
+    assert call(7, 256, 512, 768, 4, 4, 4) == -5
+    assert mc.matmul_workspace_bytes(7, 4, 4, 4) == 0
+    # the weight gradient of a 512 -> 10 classifier head over a batch of 128 is a sliced reduction or a single tile
+    assert mc.matmul_workspace_bytes(mc.MATMUL_TN, 10, 512, 128) % 16 == 0

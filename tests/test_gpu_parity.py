@@ -392,6 +392,34 @@ def test_fully_connected_as_1x1_convolution():
     gu.check_all_ops(d, *small_inputs(d, 78), label="fc 512->512")
 
 
+# M, N, K of C[M,N]: classifier head, square, ragged everything, K not a multiple of 4, a long reduction
+MATMUL_SHAPES = [(128, 10, 512), (256, 512, 512), (33, 7, 50), (100, 36, 27), (64, 64, 4096), (5, 1000, 64), (1, 1, 1)]
+
+
+@pytest.mark.parametrize("split", [0, 3])
+@pytest.mark.parametrize("shape", MATMUL_SHAPES)
+def test_matmul_fully_connected(shape, split):
+    """The fully-connected layer's three matrix multiplies (paper Fig. 2 fullconnect; Sec. II matMul /
+    matMulT1) through matmul_f32 against the oracle's matrix multiply."""
+    M, N, K = shape
+    say("matmul %s split=%d" % (shape, split))
+    mc.conv2d_set_tuning(mc.VARIANT_AUTO, split)
+    k = wl.stream_key("matmul", M, N, K)
+    cases = [(mc.MATMUL_NT, (M, K), (N, K), False, True), (mc.MATMUL_NN, (M, K), (K, N), False, False),
+             (mc.MATMUL_TN, (K, M), (K, N), True, False)]
+    for i, (kind, sa, sb, ta, tb) in enumerate(cases):
+        A = wl.uniform_pm1(k + 2 * i, sa)
+        B = wl.uniform_pm1(k + 2 * i + 1, sb)
+        buf, out = gu.guarded((M, N))
+        need = mc.matmul_workspace_bytes(kind, M, N, K)
+        ws = torch.full((max(need, 16) // 4,), float("nan"), dtype=torch.float32, device="cuda")
+        mc.matmul_f32(kind, gu.nan_fenced(A), gu.nan_fenced(B), out, ws=ws)
+        torch.cuda.synchronize()
+        assert gu.guards_intact(buf)
+        rel, mx = gu.errors(out.cpu().numpy(), gu.oracle.matmul(A, B, ta, tb))
+        assert rel <= gu.REL_L2_TOL and mx <= gu.MAX_ABS_TOL, (kind, rel, mx)
+
+
 @pytest.mark.parametrize("shp,split", [((128, 5, 3, 64, 256, 3, 3, 1, 1), 8), ((128, 3, 3, 64, 192, 3, 3, 1, 1), 5),
                                        ((64, 6, 6, 32, 128, 5, 5, 1, 2), 4),
                                        # filter larger than the activations and than an XCD's L2: ranks enumerate

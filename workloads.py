@@ -218,8 +218,17 @@ CFG8 = [Layer("R1", 128, 32, 32, 3, 64, 3, 3, 1, 1),
         Layer("R7s", 128, 8, 8, 256, 512, 1, 1, 2, 0),
         Layer("R8", 128, 4, 4, 512, 512, 3, 3, 1, 1)]
 
+# An AlexNet-shaped CIFAR layer set (the first network family of the paper's Table III; the paper does
+# not print its layer list, so this is the usual CIFAR adaptation: 3x3 filters, 2x2 pooling after the
+# first, second and fifth convolution), batch 128.  Synthetic stand-in like every other set.
+CFG9 = [Layer("A1", 128, 32, 32, 3, 64, 3, 3, 1, 1),
+        Layer("A2", 128, 16, 16, 64, 192, 3, 3, 1, 1),
+        Layer("A3", 128, 8, 8, 192, 384, 3, 3, 1, 1),
+        Layer("A4", 128, 8, 8, 384, 256, 3, 3, 1, 1),
+        Layer("A5", 128, 8, 8, 256, 256, 3, 3, 1, 1)]
+
 CONFIGS = {"cfg1": CFG1, "cfg2": CFG2, "cfg3": CFG3, "cfg4": CFG4, "cfg5": CFG5, "cfg6": CFG6,
-           "cfg7": CFG7, "cfg8": CFG8}
+           "cfg7": CFG7, "cfg8": CFG8, "cfg9": CFG9}
 
 
 def all_layers():
