@@ -26,12 +26,6 @@ constexpr size_t kScratchBytes = (size_t)32 << 20;
 #endif
 static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
-// Tile counters of sliced launches that combine their slices inside the kernel.  Zero when the
-// module is loaded; every launch leaves its counters at zero again.
-constexpr int kMaxFusedTiles = 8192;
-constexpr int kMaxFusedSplit = 8;
-static __device__ unsigned fuseCounters[kMaxFusedTiles];
-
 namespace {
 
 std::atomic<int> g_forceVariant{MI355CONV_VARIANT_AUTO};
@@ -627,8 +621,6 @@ constexpr int kMaxDevices = 64;
 std::mutex g_deviceMutex;
 std::atomic<int> g_deviceReady[kMaxDevices];
 void *g_scratchPtr[kMaxDevices];
-unsigned *g_fuseCountersPtr[kMaxDevices];
-std::atomic<int> g_fuseOn{0};
 
 // Once per device, with that device current and no stream capture under way: raises the LDS limit
 // of the large-tile kernels and looks up the device's scratch array.
@@ -650,10 +642,6 @@ int prepare_device(int *devOut)
     if (e != hipSuccess) return hip_fail(e);
     if (!ptr) return hip_fail(hipErrorInvalidSymbol);
     g_scratchPtr[dev] = ptr;
-    void *cptr = nullptr;
-    e = hipGetSymbolAddress(&cptr, HIP_SYMBOL(fuseCounters));
-    if (e != hipSuccess || !cptr) return hip_fail(e != hipSuccess ? e : hipErrorInvalidSymbol);
-    g_fuseCountersPtr[dev] = static_cast<unsigned *>(cptr);
     g_deviceReady[dev].store(1, std::memory_order_release);
     return MI355CONV_OK;
 }
@@ -1053,19 +1041,10 @@ int run_gather(const float *A, const float *B, float *out, const Shape &s, const
         }
     }
     g.divRowTilesPerPos = make_fastdiv((unsigned)g.rowTilesPerPos);
-    int dev = 0;
-    bool fused = false;
-    if (g_fuseOn.load() && pl.split > 1 && pl.split <= kMaxFusedSplit && !pl.elem && g.DC % 4 == 0 &&
-        (long long)pl.tilesM * pl.tilesN <= kMaxFusedTiles && hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices) {
-        fused = true;
-        g.fuse = 1;
-        g.fuseOut = out;
-        g.fuseCounters = g_fuseCountersPtr[dev];
-    }
     hipError_t e = pl.elem ? launch_gather_elem(g, bwd, pl.bm, pl.bn, pl.grid, st)
                            : launch_gather_gemm(g, bwd, pl.bm, pl.bn, pl.grid, st);
     if (e != hipSuccess) return hip_fail(e);
-    if (pl.split > 1 && !fused) {
+    if (pl.split > 1) {
         e = launch_slice_reduce(static_cast<const float *>(ws), out, pl.outElems, pl.split, pl.sliceStride, st,
                                 epi.bias, epi.slope, epi.on ? g.DC : 0);
         if (e != hipSuccess) return hip_fail(e);
@@ -1138,12 +1117,6 @@ int conv2d_set_tuning(int variant, int split)
         return MI355CONV_ERR_UNSUPPORTED;
     g_forceVariant.store(variant);
     g_forceSplit.store(split);
-    return MI355CONV_OK;
-}
-
-int conv2d_set_fuse(int on)
-{
-    g_fuseOn.store(on ? 1 : 0);
     return MI355CONV_OK;
 }
 

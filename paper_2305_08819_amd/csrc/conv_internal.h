@@ -120,12 +120,6 @@ struct GatherGemmParams {
     int grid;                // workgroups of the launch
     int runsN;               // runs.n, among the scalars fetched first
     int classesN;            // classes.n, likewise
-    // Sliced launch with the combine step inside the kernel: the workgroup that finishes a tile's
-    // last slice (a counter per tile tells) adds the tile's partials in slice order and stores the
-    // result to fuseOut.  fuseCounters: zero before the launch, zero again after it.
-    int fuse;
-    float *fuseOut;
-    unsigned *fuseCounters;
     int phaseStart[kMaxPhases];   // first row tile of each phase; INT_MAX past the last phase
     GatherPhase phase[kMaxPhases];
     BalanceRuns runs;
@@ -151,9 +145,7 @@ struct GatherView {
     float slope;
     const float *bias;
     FastDiv divN, divTilesN, divSplit, divRowTilesPerPos, divChunksPerTap, divDHW, divDW, divXcdUnit;
-    int xcdWhole, grid, runsN, classesN, fuse;
-    float *fuseOut;
-    unsigned *fuseCounters;
+    int xcdWhole, grid, runsN, classesN;
     const int *phaseStart;
     const GatherPhase *phase;
     const BalanceRuns &runs;
@@ -166,8 +158,7 @@ __device__ __forceinline__ GatherView gather_view(const GatherGemmParams &p)
     GatherView v{p.A, p.B, p.C, p.aBytes, p.bBytes, p.Nimg, p.SH, p.SW, p.SC, p.DH, p.DW, p.DC, p.FH, p.FW,
                  p.sh, p.sw, p.ph, p.pw, p.posMajor, p.split, p.sliceStride, p.tilesN, p.xcdUnit, p.nPhases,
                  p.balance, p.rowTilesPerPos, p.epilogue, p.slope, p.bias, p.divN, p.divTilesN, p.divSplit, p.divRowTilesPerPos,
-                 p.divChunksPerTap, p.divDHW, p.divDW, p.divXcdUnit, p.xcdWhole, p.grid, p.runsN, p.classesN, p.fuse, p.fuseOut,
-                 p.fuseCounters, p.phaseStart, p.phase, p.runs, p.posOrder};
+                 p.divChunksPerTap, p.divDHW, p.divDW, p.divXcdUnit, p.xcdWhole, p.grid, p.runsN, p.classesN, p.phaseStart, p.phase, p.runs, p.posOrder};
     MI355CONV_PIN(v.A); MI355CONV_PIN(v.B); MI355CONV_PIN(v.C);
     MI355CONV_PIN(v.aBytes); MI355CONV_PIN(v.bBytes);
     MI355CONV_PIN(v.Nimg); MI355CONV_PIN(v.SH); MI355CONV_PIN(v.SW); MI355CONV_PIN(v.SC);

@@ -14,7 +14,6 @@ constexpr int kInvalidCoord = -(1 << 28);
 
 template <int BM, int BN, int WAVES_M, bool BWD>
 struct GG {
-    static constexpr int BM_ = BM, BN_ = BN;
     static constexpr int WAVES_N = 4 / WAVES_M;
     static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;   // wave tile
     static constexpr int MB = WTM / 32, NB = WTN / 32;             // 32x32 MFMA blocks per wave
@@ -33,7 +32,6 @@ struct GG {
 };
 
 struct GatherTile {
-    int tileId;                 // index of the output tile (row tile * column tiles + column tile)
     int slice;                  // reduction slice of this workgroup
     int n0;                     // first output column
     int ra, rb;                 // stride-phase residues (backward-data)
@@ -127,7 +125,6 @@ __device__ __forceinline__ GatherTile gather_tile_setup(const P &p, const Balanc
 
     // ---- tap rectangle from the first and last row of the tile (uniform) ----------------
     GatherTile t;
-    t.tileId = tmGlobal * p.tilesN + tn;
     t.slice = slice;
     t.n0 = tn * BN;
     t.ra = ph.ra;
@@ -242,47 +239,6 @@ __device__ __forceinline__ void gather_tile_store(const P &p, int slice, int n0,
             }
         }
     }
-}
-
-// Combine step inside a sliced launch.  Called by all threads after the tile's partial has been
-// stored to slice `slice` of the workspace.  The workgroup that raises the tile's counter to
-// `split` is the last one: every other slice of the tile is complete and - through the fence
-// before the increment and the one after it - visible, so it adds the `split` partials in slice
-// order (fp64, rounded once: the same arithmetic as the separate combine kernel), applies the
-// bias / activation if asked, stores the tile to the output and puts the counter back to zero.
-template <class T, class P>
-__device__ __forceinline__ void fused_slice_combine(const P &p, int tileId, int n0, const int *outRow, int *flag)
-{
-    const int tid = threadIdx.x;
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) *flag = atomicAdd(p.fuseCounters + tileId, 1u) == (unsigned)(p.split - 1) ? 1 : 0;
-    __syncthreads();
-    if (!*flag) return;
-    __threadfence();
-    constexpr int SEGS = T::BN_ / 4;                      // 16-byte segments per tile row
-    const bool epi = p.epilogue != 0;
-    for (int idx = tid; idx < T::BM_ * SEGS; idx += kThreads) {
-        const int row = idx / SEGS, col = n0 + (idx - row * SEGS) * 4;
-        const int o = outRow[row];
-        if (o < 0 || col >= p.DC) continue;               // DC is a multiple of 4 here
-        const long long off = (long long)o * p.DC + col;
-        double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
-        for (int s = 0; s < p.split; ++s) {
-            const f4 v = *reinterpret_cast<const f4 *>(p.C + (long long)s * p.sliceStride + off);
-            a0 += v[0]; a1 += v[1]; a2 += v[2]; a3 += v[3];
-        }
-        f4 r = {(float)a0, (float)a1, (float)a2, (float)a3};
-        if (epi) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float v = r[e] + (p.bias ? p.bias[col + e] : 0.f);
-                r[e] = v > 0.f ? v : v * p.slope;
-            }
-        }
-        *reinterpret_cast<f4 *>(p.fuseOut + off) = r;
-    }
-    if (tid == 0) p.fuseCounters[tileId] = 0u;
 }
 
 }  // namespace mi355conv

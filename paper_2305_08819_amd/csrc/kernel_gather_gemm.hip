@@ -321,7 +321,6 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     // what is still read from them is never used): each wave turns its blocks in its own part
     static_assert(4 * 32 * kLDT <= 2 * T::A_STAGE, "four turning buffers fit over the A stages");
     gather_tile_store<T>(p, slice, n0, outRow, acc, wm, wn, l32, lh, As + wave * 32 * kLDT);
-    if (p.fuse) fused_slice_combine<T>(p, tile.tileId, n0, outRow, outRow + BM);   // the table's spare words hold the flag
 }
 
 template <int BM, int BN, int WAVES_M, bool BWD>
