@@ -85,7 +85,15 @@ typedef struct conv2d_plan_info {
     int grid;           /* workgroups of the main kernel                                    */
     size_t workspace_bytes;
     int kernel;         /* MI355CONV_KERNEL_*: which kernel family runs the plan            */
+    int order;          /* MI355CONV_ORDER_*: how workgroup ids map to tiles                */
 } conv2d_plan_info;
+
+/* Workgroup orders (conv2d_plan_info.order). */
+enum {
+    MI355CONV_ORDER_PLAIN = 0,     /* tiles in id order (ids regrouped so that neighbours share an XCD) */
+    MI355CONV_ORDER_LONGEST = 1,   /* unequal tiles dealt longest first to the 256 CUs                 */
+    MI355CONV_ORDER_REGIONS = 2    /* every XCD owns a region x image group x filter-slice group       */
+};
 
 /* Kernel families (conv2d_plan_info.kernel); for tests, which force every compiled variant. */
 enum {
@@ -127,6 +135,14 @@ int conv2d_set_tuning(int variant, int split);
  * (tile_m x tile_n must be a compiled pair, 0 x 0 = auto) and the row order
  * (pos_major = -1 auto, 0 (n,y,x) rows, 1 (y,x,n) rows where the shape allows it). */
 int conv2d_set_tile(int tile_m, int tile_n, int pos_major);
+
+/* Third process-wide override for tests and sweeps: the order in which the workgroups of a
+ * (y,x,n)-row forward / unit-stride backward-data launch are dealt to the chip.
+ * region_wise = 1 (default): every XCD (workgroup id modulo 8, one L2 each) owns a spatial
+ * region x image group x filter-slice group of the tiles wherever the shape allows it;
+ * 0: the older order (longest tiles first over the whole chip).  Results are bitwise equal
+ * either way. */
+int conv2d_set_order(int region_wise);
 
 /* Forward convolution (Sec. III Layer-1; Fig. 2 conv3D arguments):
  *   Y[n,oh,ow,oc] = sum_{fh,fw,ic} X[n, oh*sh-ph+fh, ow*sw-pw+fw, ic] * W[oc,fh,fw,ic],

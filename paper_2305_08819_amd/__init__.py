@@ -17,8 +17,9 @@ LIB_PATH = os.environ.get("MI355CONV_LIB") or os.path.join(_PKG, "libmi355conv.s
 OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT = 0, 1, 2
 VARIANT_AUTO, VARIANT_DIRECT, VARIANT_MFMA = -1, 0, 1
 KERNEL_DIRECT, KERNEL_GATHER, KERNEL_GATHER_ELEM, KERNEL_FIRST_LAYER, KERNEL_WGRAD, KERNEL_WGRAD_FAST = range(6)
+ORDER_PLAIN, ORDER_LONGEST, ORDER_REGIONS = range(3)
 
-EXPORTS = ("conv2d_workspace_bytes", "conv2d_query_plan", "conv2d_query_workgroup", "conv2d_set_tuning", "conv2d_set_tile", "conv2d_fwd",
+EXPORTS = ("conv2d_workspace_bytes", "conv2d_query_plan", "conv2d_query_workgroup", "conv2d_set_tuning", "conv2d_set_tile", "conv2d_set_order", "conv2d_fwd",
            "conv2d_fwd_bias_act", "conv2d_fwd_u8",
            "conv2d_bwd_data", "deconv2d", "conv2d_bwd_weight", "conv2d_status_string",
            "conv2d_last_hip_error", "conv2d_init", "conv2d_bwd_weight_noalloc", "conv2d_noalloc_scratch_bytes",
@@ -44,7 +45,7 @@ class PlanInfo(ctypes.Structure):
     """Mirror of ``conv2d_plan_info``."""
     _fields_ = [("variant", ctypes.c_int), ("tile_m", ctypes.c_int), ("tile_n", ctypes.c_int),
                 ("split", ctypes.c_int), ("pos_major", ctypes.c_int), ("grid", ctypes.c_int),
-                ("workspace_bytes", ctypes.c_size_t), ("kernel", ctypes.c_int)]
+                ("workspace_bytes", ctypes.c_size_t), ("kernel", ctypes.c_int), ("order", ctypes.c_int)]
 
 
 class Mi355ConvError(RuntimeError):
@@ -82,6 +83,8 @@ def load() -> ctypes.CDLL:
         lib.conv2d_set_tuning.restype = ctypes.c_int
         lib.conv2d_set_tile.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
         lib.conv2d_set_tile.restype = ctypes.c_int
+        lib.conv2d_set_order.argtypes = [ctypes.c_int]
+        lib.conv2d_set_order.restype = ctypes.c_int
         for name in ("conv2d_fwd", "conv2d_bwd_data", "deconv2d", "conv2d_bwd_weight"):
             fn = getattr(lib, name)
             fn.argtypes = [vp, vp, vp, dp, vp, ctypes.c_size_t, vp]
@@ -153,6 +156,12 @@ def conv2d_set_tile(tile_m: int = 0, tile_n: int = 0, pos_major: int = -1) -> No
     rc = load().conv2d_set_tile(tile_m, tile_n, pos_major)
     if rc != 0:
         raise Mi355ConvError(rc, "conv2d_set_tile")
+
+
+def conv2d_set_order(region_wise: int = 1) -> None:
+    rc = load().conv2d_set_order(region_wise)
+    if rc != 0:
+        raise Mi355ConvError(rc, "conv2d_set_order")
 
 
 def conv2d_init() -> None:

@@ -31,6 +31,7 @@ namespace {
 std::atomic<int> g_forceVariant{MI355CONV_VARIANT_AUTO};
 std::atomic<int> g_forceSplit{0};
 std::atomic<int> g_forceBM{0}, g_forceBN{0}, g_forcePosMajor{-1};
+std::atomic<int> g_regionalOrder{1};   // 0: region-wise workgroup order off (conv2d_set_order)
 thread_local char t_hipError[256] = "";
 
 constexpr long long kMaxElems = (1LL << 31) - 1;
@@ -64,6 +65,10 @@ struct Plan {
     int nClasses = 0;
     int classFirstUnit[kMaxBalanceClasses] = {};
     int classUnits[kMaxBalanceClasses] = {};
+    // region-wise order of the gather operators (see GatherGemmParams::regional); uses order / unitWork
+    int regional = 0, regSnake = 0, regPerPos = 0, regCsPer = 0, regRowTiles = 0, regW = 0;
+    unsigned char regLut[8] = {};
+    int chunksPerSlice = 0;   // gather operators: slices by source channels (0: by stages)
 };
 
 int out_extent(int in, int pad, int f, int stride)
@@ -872,6 +877,105 @@ void plan_balance_gather(const Shape &s, Plan &pl, bool bwd)
     }
 }
 
+// Region-wise order for (y,x,n) launches of one phase.  Workgroup ids go round-robin to the 8 XCDs, each with
+// its own L2, so the tiles of a launch are divided among the XCDs as a product of (spatial regions) x
+// (image groups) x (groups of (slice, column tile) pairs), the factors chosen for the fewest bytes
+// fetched: a spatial region re-reads only its halo of the gathered tensor, an image group shares
+// nothing with the others, and a (slice, column) group reads its own part of the filter (and, with
+// slices by channels, its own channels of the gathered tensor).  Regions are halves / quarters of the
+// map mirrored onto the first one, which needs even extents and tap counts that mirror.
+bool plan_regional_gather(const Shape &s, Plan &pl, bool bwd)
+{
+    pl.regional = 0;
+    if (!pl.posMajor || pl.elem || pl.nPhases != 1 || s.N % pl.bm != 0) return false;
+    if (bwd && (s.sh != 1 || s.sw != 1)) return false;
+    if (pl.grid < 256 || pl.grid % 8 != 0) return false;
+    const int dh = bwd ? s.IH : s.OH, dw = bwd ? s.IW : s.OW;
+    const int srcH = bwd ? s.OH : s.IH, srcW = bwd ? s.OW : s.IW, srcC = bwd ? s.OC : s.IC;
+    const int yStep = bwd ? 1 : s.sh, xStep = bwd ? 1 : s.sw;
+    if ((long long)dh * dw > 1024) return false;
+    int taps[1024];
+    for (int i = 0; i < dh; ++i)
+        for (int j = 0; j < dw; ++j) {
+            int th = 0, tw = 0;
+            for (int f = 0; f < s.FH; ++f)
+                th += bwd ? (unsigned)(i + s.ph - f) < (unsigned)s.OH : (unsigned)(i * s.sh - s.ph + f) < (unsigned)s.IH;
+            for (int f = 0; f < s.FW; ++f)
+                tw += bwd ? (unsigned)(j + s.pw - f) < (unsigned)s.OW : (unsigned)(j * s.sw - s.pw + f) < (unsigned)s.IW;
+            taps[i * dw + j] = th * tw;
+        }
+    bool symY = dh % 2 == 0, symX = dw % 2 == 0;
+    for (int i = 0; i < dh; ++i)
+        for (int j = 0; j < dw; ++j) {
+            if (taps[(dh - 1 - i) * dw + j] != taps[i * dw + j]) symY = false;
+            if (taps[i * dw + dw - 1 - j] != taps[i * dw + j]) symX = false;
+        }
+    const int rtpp = s.N / pl.bm, cs = pl.tilesN * pl.split;
+    const double aBytes = 4.0 * s.N * srcH * srcW * srcC, wBytes = 4.0 * s.OC * s.FH * s.FW * s.IC;
+    double bestCost = 0;
+    int bRy = 0, bRx = 0, bG = 0, bC = 0;
+    for (int Ry = 2; Ry >= 1; --Ry)          // ties go to the split along y (regions of whole rows)
+        for (int Rx = 1; Rx <= 2; ++Rx)
+            for (int G = 1; G <= 8; G *= 2) {
+                if ((Ry == 2 && !symY) || (Rx == 2 && !symX) || rtpp % G != 0) continue;
+                // measured: an XCD whose tiles cover the whole map runs 2-4 % slower than one that owns
+                // a half or a quarter of it, whatever the other two factors are
+                if (Ry * Rx == 1 && (symY || symX)) continue;
+                const int RG = Ry * Rx * G;
+                if (8 % RG != 0) continue;
+                const int C = 8 / RG;
+                if (cs % C != 0 || (dh / Ry) * (dw / Rx) > kMaxBalancedPositions) continue;
+                const int needY = Ry == 1 ? srcH : std::min(srcH, (dh / Ry - 1) * yStep + s.FH);
+                const int needX = Rx == 1 ? srcW : std::min(srcW, (dw / Rx - 1) * xStep + s.FW);
+                const int csPer = cs / C;
+                const int slices = std::min(pl.split, (csPer + pl.tilesN - 1) / pl.tilesN + (csPer > pl.tilesN && csPer % pl.tilesN ? 1 : 0));
+                const double chanFrac = pl.chunksPerSlice ? (double)slices / pl.split : 1.0;
+                const double aTot = 8.0 * aBytes * ((double)needY / srcH) * ((double)needX / srcW) / G * chanFrac;
+                const double wTot = wBytes * RG;
+                if (!bRy || aTot + wTot < bestCost) {
+                    bestCost = aTot + wTot;
+                    bRy = Ry; bRx = Rx; bG = G; bC = C;
+                }
+            }
+    if (!bRy) return false;
+    const int rh = dh / bRy, rw = dw / bRx, nPos = rh * rw;
+    int order[kMaxBalancedPositions];
+    for (int i = 0; i < nPos; ++i) order[i] = i;
+    auto tapsAt = [&](int l) { return taps[(l / rw) * dw + l % rw]; };
+    std::stable_sort(order, order + nPos, [&](int a, int b) { return tapsAt(a) > tapsAt(b); });
+    for (int i = 0; i < nPos; ++i) {
+        pl.order[i] = (unsigned char)order[i];
+        const int t = tapsAt(order[i]);
+        pl.unitWork[i] = (unsigned char)(t < 255 ? t : 255);
+    }
+    for (int x = 0; x < 8; ++x) {
+        const int c = x % bC, g = (x / bC) % bG, r = x / (bC * bG);
+        pl.regLut[x] = (unsigned char)(c | (g << 3) | ((r % bRx) << 6) | ((r / bRx) << 7));
+    }
+    pl.regCsPer = cs / bC;
+    pl.regRowTiles = rtpp / bG;
+    pl.regPerPos = pl.regRowTiles * pl.regCsPer;
+    pl.regW = rw;
+    pl.itemsPerClassUnit = pl.regPerPos;
+    const int resident = pl.bm * pl.bn <= 64 * 64 ? 4 : 2;
+    pl.regSnake = pl.grid / 8 <= 32 * resident;
+    pl.regional = 1;
+    return true;
+}
+
+// Slicing and workgroup order of a gather-operator plan.
+void plan_order_gather(const Shape &s, Plan &pl, bool bwd)
+{
+    pl.balance = 0;
+    pl.regional = 0;
+    pl.chunksPerSlice = 0;
+    if (pl.smallIc) return;
+    const int chunks = ceil_div(bwd ? s.OC : s.IC, kBK);
+    if (!pl.elem && pl.split > 1 && chunks % pl.split == 0) pl.chunksPerSlice = chunks / pl.split;
+    if (g_regionalOrder.load() && plan_regional_gather(s, pl, bwd)) return;
+    plan_balance_gather(s, pl, bwd);
+}
+
 // Backward-weight in (oh,ow,n) order: rank the taps by the number of output positions at which
 // they are inside the image.
 void plan_balance_wgrad(const Shape &s, Plan &pl)
@@ -931,14 +1035,14 @@ bool plan_launchable(int op, const Shape &s, const Plan &pl)
 // that the enqueue path does not repeat the search (and the longest-first dealing, which takes
 // a good fraction of a millisecond) on every call.
 struct PlanKey {
-    int v[17];
+    int v[18];
     bool operator==(const PlanKey &o) const { return memcmp(v, o.v, sizeof v) == 0; }
 };
 struct PlanKeyHash {
     size_t operator()(const PlanKey &k) const
     {
         unsigned h = 2166136261u;
-        for (int i = 0; i < 17; ++i) h = (h ^ (unsigned)k.v[i]) * 16777619u;
+        for (int i = 0; i < 18; ++i) h = (h ^ (unsigned)k.v[i]) * 16777619u;
         return h;
     }
 };
@@ -951,9 +1055,9 @@ int make_plan(int op, const Shape &s, Plan *pl)
     if (op != MI355CONV_OP_FWD && op != MI355CONV_OP_BWD_DATA && op != MI355CONV_OP_BWD_WEIGHT)
         return MI355CONV_ERR_UNSUPPORTED;
     PlanKey k;
-    const int vals[17] = {op, s.N, s.IH, s.IW, s.IC, s.OC, s.FH, s.FW, s.sh, s.sw, s.ph, s.pw,
+    const int vals[18] = {op, s.N, s.IH, s.IW, s.IC, s.OC, s.FH, s.FW, s.sh, s.sw, s.ph, s.pw,
                           g_forceVariant.load(), g_forceSplit.load(), g_forceBM.load(), g_forceBN.load(),
-                          g_forcePosMajor.load()};
+                          g_forcePosMajor.load(), g_regionalOrder.load()};
     memcpy(k.v, vals, sizeof vals);
     {
         std::lock_guard<std::mutex> lock(g_planMutex);
@@ -968,11 +1072,11 @@ int make_plan(int op, const Shape &s, Plan *pl)
     switch (op) {
     case MI355CONV_OP_FWD:
         *pl = plan_fwd(s);
-        if (pl->variant == MI355CONV_VARIANT_MFMA) plan_balance_gather(s, *pl, false);
+        if (pl->variant == MI355CONV_VARIANT_MFMA) plan_order_gather(s, *pl, false);
         break;
     case MI355CONV_OP_BWD_DATA:
         *pl = plan_bwd_data(s);
-        if (pl->variant == MI355CONV_VARIANT_MFMA) plan_balance_gather(s, *pl, true);
+        if (pl->variant == MI355CONV_VARIANT_MFMA) plan_order_gather(s, *pl, true);
         break;
     default:
         *pl = plan_bwd_weight(s);
@@ -1040,6 +1144,23 @@ int run_gather(const float *A, const float *B, float *out, const Shape &s, const
             g.classes.divRows[c] = make_fastdiv((unsigned)(pl.classUnits[c] * g.rowTilesPerPos));
         }
     }
+    g.chunksPerSlice = pl.chunksPerSlice;
+    if (pl.regional) {
+        g.regional = 1;
+        g.rowTilesPerPos = s.N / pl.bm;
+        g.regSnake = pl.regSnake;
+        g.regLocal = pl.grid / 8;
+        g.regPerPos = pl.regPerPos;
+        g.regCsPer = pl.regCsPer;
+        g.regRowTiles = pl.regRowTiles;
+        g.regW = pl.regW;
+        g.regLutLo = (unsigned)pl.regLut[0] | ((unsigned)pl.regLut[1] << 8) | ((unsigned)pl.regLut[2] << 16) | ((unsigned)pl.regLut[3] << 24);
+        g.regLutHi = (unsigned)pl.regLut[4] | ((unsigned)pl.regLut[5] << 8) | ((unsigned)pl.regLut[6] << 16) | ((unsigned)pl.regLut[7] << 24);
+        g.divRegPerPos = make_fastdiv((unsigned)pl.regPerPos);
+        g.divRegCsPer = make_fastdiv((unsigned)pl.regCsPer);
+        g.divRegW = make_fastdiv((unsigned)pl.regW);
+        memcpy(g.posOrder, pl.order, sizeof g.posOrder);
+    }
     g.divRowTilesPerPos = make_fastdiv((unsigned)g.rowTilesPerPos);
     hipError_t e = pl.elem ? launch_gather_elem(g, bwd, pl.bm, pl.bn, pl.grid, st)
                            : launch_gather_gemm(g, bwd, pl.bm, pl.bn, pl.grid, st);
@@ -1084,6 +1205,7 @@ int conv2d_query_plan(int op, const conv2d_desc *d, conv2d_plan_info *info)
     else if (pl.smallIc) info->kernel = MI355CONV_KERNEL_FIRST_LAYER;
     else if (op == MI355CONV_OP_BWD_WEIGHT) info->kernel = pl.fast ? MI355CONV_KERNEL_WGRAD_FAST : MI355CONV_KERNEL_WGRAD;
     else info->kernel = pl.elem ? MI355CONV_KERNEL_GATHER_ELEM : MI355CONV_KERNEL_GATHER;
+    info->order = pl.regional ? MI355CONV_ORDER_REGIONS : pl.balance ? MI355CONV_ORDER_LONGEST : MI355CONV_ORDER_PLAIN;
     return MI355CONV_OK;
 }
 
@@ -1099,6 +1221,19 @@ int conv2d_query_workgroup(int op, const conv2d_desc *d, int workgroup, int *ran
     if (workgroup < 0 || workgroup >= pl.grid) return MI355CONV_ERR_BAD_DIM;
     *rank = workgroup;
     *work = 1;
+    if (pl.regional) {   // the kernels' region-wise decode: XCD = id % 8, place on the XCD = id / 8
+        const int q = workgroup >> 3, local = pl.grid / 8;
+        int lr = q;
+        if (pl.regSnake) {
+            const int lap = q >> 5, left = local - (lap << 5), w = left < 32 ? left : 32;
+            int c = q & 31;
+            if (lap & 1) c = w - 1 - c;
+            lr = (lap << 5) + c;
+        }
+        *rank = lr * 8 + (workgroup & 7);
+        *work = pl.unitWork[lr / pl.regPerPos];
+        return MI355CONV_OK;
+    }
     if (!pl.balance) return MI355CONV_OK;
     if (pl.runs.n) {   // the same lookup as the kernels' balanced_rank()
         const int slot = balance_slot(workgroup, pl.grid);
@@ -1129,6 +1264,14 @@ int conv2d_set_tile(int tile_m, int tile_n, int pos_major)
     g_forceBM.store(tile_m);
     g_forceBN.store(tile_n);
     g_forcePosMajor.store(pos_major);
+    return MI355CONV_OK;
+}
+
+
+int conv2d_set_order(int region_wise)
+{
+    if (region_wise < 0 || region_wise > 1) return MI355CONV_ERR_UNSUPPORTED;
+    g_regionalOrder.store(region_wise);
     return MI355CONV_OK;
 }
 

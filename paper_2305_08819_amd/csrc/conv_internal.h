@@ -120,6 +120,25 @@ struct GatherGemmParams {
     int grid;                // workgroups of the launch
     int runsN;               // runs.n, among the scalars fetched first
     int classesN;            // classes.n, likewise
+    // Region-wise order ((y,x,n) rows, one phase): XCD x = hardware id % 8 owns the product of a spatial
+    // region of the map (halves or quarters, mirrored so that every region looks like the first), a group
+    // of row tiles (images) and a group of (slice, column tile) pairs; regLut holds one byte per XCD:
+    // bits 0-2 column group, 3-5 image group, 6 mirrored in x, 7 mirrored in y.  Inside an XCD the tiles
+    // are ranked position by position (posOrder: positions of the first region, most taps first) and,
+    // while the whole launch is resident, dealt to its 32 CUs in a snake (ranks 0..31, 63..32, ...).
+    int regional;
+    int regSnake;
+    int regLocal;            // workgroups per XCD = grid / 8
+    int regPerPos;           // tiles per position inside one XCD = regRowTiles * regCsPer
+    int regCsPer;            // (slice, column tile) pairs per XCD
+    int regRowTiles;         // row tiles per position and image group
+    int regW;                // width of a region in positions
+    unsigned regLutLo, regLutHi;
+    FastDiv divRegPerPos, divRegCsPer, divRegW;
+    // > 0: slice s walks the source-channel chunks [s*chunksPerSlice, (s+1)*chunksPerSlice) of every tap
+    // (slices differ in channels, so a slice reads a 1/split part of both operands); 0: the list of
+    // stages (tap-major) is cut into split equal parts.
+    int chunksPerSlice;
     int phaseStart[kMaxPhases];   // first row tile of each phase; INT_MAX past the last phase
     GatherPhase phase[kMaxPhases];
     BalanceRuns runs;
@@ -146,6 +165,10 @@ struct GatherView {
     const float *bias;
     FastDiv divN, divTilesN, divSplit, divRowTilesPerPos, divChunksPerTap, divDHW, divDW, divXcdUnit;
     int xcdWhole, grid, runsN, classesN;
+    int regional, regSnake, regLocal, regPerPos, regCsPer, regRowTiles, regW;
+    unsigned regLutLo, regLutHi;
+    FastDiv divRegPerPos, divRegCsPer, divRegW;
+    int chunksPerSlice;
     const int *phaseStart;
     const GatherPhase *phase;
     const BalanceRuns &runs;
@@ -158,7 +181,9 @@ __device__ __forceinline__ GatherView gather_view(const GatherGemmParams &p)
     GatherView v{p.A, p.B, p.C, p.aBytes, p.bBytes, p.Nimg, p.SH, p.SW, p.SC, p.DH, p.DW, p.DC, p.FH, p.FW,
                  p.sh, p.sw, p.ph, p.pw, p.posMajor, p.split, p.sliceStride, p.tilesN, p.xcdUnit, p.nPhases,
                  p.balance, p.rowTilesPerPos, p.epilogue, p.slope, p.bias, p.divN, p.divTilesN, p.divSplit, p.divRowTilesPerPos,
-                 p.divChunksPerTap, p.divDHW, p.divDW, p.divXcdUnit, p.xcdWhole, p.grid, p.runsN, p.classesN, p.phaseStart, p.phase, p.runs, p.posOrder};
+                 p.divChunksPerTap, p.divDHW, p.divDW, p.divXcdUnit, p.xcdWhole, p.grid, p.runsN, p.classesN,
+                 p.regional, p.regSnake, p.regLocal, p.regPerPos, p.regCsPer, p.regRowTiles, p.regW, p.regLutLo, p.regLutHi,
+                 p.divRegPerPos, p.divRegCsPer, p.divRegW, p.chunksPerSlice, p.phaseStart, p.phase, p.runs, p.posOrder};
     MI355CONV_PIN(v.A); MI355CONV_PIN(v.B); MI355CONV_PIN(v.C);
     MI355CONV_PIN(v.aBytes); MI355CONV_PIN(v.bBytes);
     MI355CONV_PIN(v.Nimg); MI355CONV_PIN(v.SH); MI355CONV_PIN(v.SW); MI355CONV_PIN(v.SC);
@@ -176,6 +201,13 @@ __device__ __forceinline__ GatherView gather_view(const GatherGemmParams &p)
     MI355CONV_PIN(v.divDW.mul); MI355CONV_PIN(v.divDW.sh1); MI355CONV_PIN(v.divDW.sh2);
     MI355CONV_PIN(v.divXcdUnit.mul); MI355CONV_PIN(v.divXcdUnit.sh1); MI355CONV_PIN(v.divXcdUnit.sh2);
     MI355CONV_PIN(v.xcdWhole); MI355CONV_PIN(v.grid); MI355CONV_PIN(v.runsN); MI355CONV_PIN(v.classesN);
+    MI355CONV_PIN(v.regional); MI355CONV_PIN(v.regSnake); MI355CONV_PIN(v.regLocal); MI355CONV_PIN(v.regPerPos);
+    MI355CONV_PIN(v.regCsPer); MI355CONV_PIN(v.regRowTiles); MI355CONV_PIN(v.regW);
+    MI355CONV_PIN(v.regLutLo); MI355CONV_PIN(v.regLutHi);
+    MI355CONV_PIN(v.divRegPerPos.mul); MI355CONV_PIN(v.divRegPerPos.sh1); MI355CONV_PIN(v.divRegPerPos.sh2);
+    MI355CONV_PIN(v.divRegCsPer.mul); MI355CONV_PIN(v.divRegCsPer.sh1); MI355CONV_PIN(v.divRegCsPer.sh2);
+    MI355CONV_PIN(v.divRegW.mul); MI355CONV_PIN(v.divRegW.sh1); MI355CONV_PIN(v.divRegW.sh2);
+    MI355CONV_PIN(v.chunksPerSlice);
     return v;
 }
 #endif

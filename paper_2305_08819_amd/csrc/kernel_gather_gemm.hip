@@ -62,9 +62,18 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     const int vCnt = tile.vHi >= tile.vLo ? tile.vHi - tile.vLo + 1 : 0;
     const int chunksPerTap = RAGGED ? (p.SC + kBK - 1) / kBK : p.SC / kBK;
     const int lastValid = p.SC - (chunksPerTap - 1) * kBK;   // source channels in a tap's last stage
-    const int nIter = uCnt * vCnt * chunksPerTap;
-    const int it0 = (int)fast_div((unsigned)(slice * nIter), p.divSplit);          // nIter * split is far below 2^31
-    const int it1 = (int)fast_div((unsigned)((slice + 1) * nIter), p.divSplit);
+    // This slice's part of the reduction: either the chunks [cLo, cHi) of every tap (slices differ in
+    // source channels), or the stages [it0, it1) of the tap-major list of all stages.
+    int cLo = 0, cHi = chunksPerTap, it0 = 0, it1;
+    if (p.chunksPerSlice) {
+        cLo = slice * p.chunksPerSlice;
+        cHi = cLo + p.chunksPerSlice;
+        it1 = uCnt * vCnt * p.chunksPerSlice;
+    } else {
+        const int nIter = uCnt * vCnt * chunksPerTap;
+        it0 = (int)fast_div((unsigned)(slice * nIter), p.divSplit);          // nIter * split is far below 2^31
+        it1 = (int)fast_div((unsigned)((slice + 1) * nIter), p.divSplit);
+    }
 
     // ---- per-thread loader state --------------------------------------------------------
     // Operands are fetched with raw buffer loads: address = base + VGPR byte offset + SGPR byte
@@ -114,8 +123,8 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     for (int i = 0; i < T::PB; ++i) bLastOk[i] = BWD ? bRow + T::B_RPP * i < lastValid : bSeg * 4 < lastValid;
 
     // reduction cursor: current tap (u,v) and chunk within the tap
-    int chunk = 0, tapU = tile.uLo, tapV = tile.vLo;
-    if (it0 > 0 && it0 < it1) {   // only slices after the first start inside the tap list
+    int chunk = cLo, tapU = tile.uLo, tapV = tile.vLo;
+    if (it0 > 0 && it0 < it1) {   // only stage-list slices after the first start inside the tap list
         const int tapIdx = (int)fast_div((unsigned)it0, p.divChunksPerTap);
         chunk = it0 - tapIdx * chunksPerTap;
         const int du = tapIdx / vCnt;
@@ -178,8 +187,8 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
     };
 
     auto advance = [&]() __attribute__((always_inline)) {
-        if (++chunk == chunksPerTap) {
-            chunk = 0;
+        if (++chunk == cHi) {
+            chunk = cLo;
             if (++tapV > tile.vHi) {
                 tapV = tile.vLo;
                 ++tapU;

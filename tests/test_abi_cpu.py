@@ -134,10 +134,14 @@ def test_longest_first_dealing_is_a_permutation_and_balances(lib):
              (mc.OP_BWD_WEIGHT, mc.make_desc(128, 4, 4, 512, 512, 3, 3, 1, 1)),  # 576: 64 CUs hold three
              (mc.OP_BWD_WEIGHT, mc.make_desc(128, 4, 4, 256, 512, 3, 3, 1, 1)),  # 288
              (mc.OP_FWD, mc.make_desc(128, 8, 8, 256, 256, 3, 3, 1, 1))]
-    for op, d in cases:
+    for op, d, region_wise in [c + (1,) for c in cases] + [c + (0,) for c in cases]:
         mc.conv2d_set_tuning(mc.VARIANT_AUTO, 1 if op == mc.OP_BWD_WEIGHT else 0)   # backward-weight: one slice
+        mc.conv2d_set_order(region_wise)
         pl = mc.conv2d_query_plan(op, d)
         assert pl.pos_major == 1 and pl.grid > 256
+        # the gather operators deal region-wise per XCD unless that is switched off; backward-weight has one order
+        want = mc.ORDER_REGIONS if region_wise and op != mc.OP_BWD_WEIGHT else mc.ORDER_LONGEST
+        assert pl.order == want, (op, region_wise, pl.order)
         seen, load = set(), [0] * 256
         for wg in range(pl.grid):
             rank, work = mc.conv2d_query_workgroup(op, d, wg)
@@ -148,6 +152,9 @@ def test_longest_first_dealing_is_a_permutation_and_balances(lib):
         if pl.grid <= 1024:     # resident at once (64x64 tiles: four per CU); larger grids refill as workgroups finish
             assert max(load) <= 1.5 * mean if pl.grid < 512 else max(load) <= 1.1 * mean, (op, pl.grid, max(load), mean)
     mc.conv2d_set_tuning(mc.VARIANT_AUTO, 0)
+    mc.conv2d_set_order(1)
+    with pytest.raises(mc.Mi355ConvError):
+        mc.conv2d_set_order(2)
     # all workgroups alike: identity
     d = mc.make_desc(128, 16, 16, 256, 64, 1, 1, 1, 0)
     assert mc.conv2d_query_workgroup(mc.OP_FWD, d, 5) == (5, 1)

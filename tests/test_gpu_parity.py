@@ -27,9 +27,11 @@ def say(msg):
 def _reset_tuning():
     mc.conv2d_set_tuning(mc.VARIANT_AUTO, 0)
     mc.conv2d_set_tile(0, 0, -1)
+    mc.conv2d_set_order(1)
     yield
     mc.conv2d_set_tuning(mc.VARIANT_AUTO, 0)
     mc.conv2d_set_tile(0, 0, -1)
+    mc.conv2d_set_order(1)
 
 
 def small_inputs(desc, seed):
@@ -441,6 +443,57 @@ def test_balanced_dealing_odd_grids(shp, split):
         assert ranks == set(range(pl.grid))
     assert max(grids) > 256
     gu.check_all_ops(d, *small_inputs(d, hash(shp) & 0xffff), label=str(shp))
+
+
+# shape, tile, forced slices: (y,x,n) launches that the region-wise order takes, chosen so that every
+# factor of the division among the XCDs occurs (quarters, halves along one axis only, no spatial
+# split; one or several image groups; one or several (slice, column) groups), with slices by source
+# channels (slice count divides the 32-channel chunks) and by stages (it does not), grids that are
+# resident at once (snake dealing, also with a partial last lap of 32) and grids that are not.
+REGION_CASES = [
+    ((128, 8, 8, 64, 64, 3, 3, 1, 1), (64, 64), 2),      # quarters x 2 image groups
+    ((128, 4, 4, 128, 256, 3, 3, 1, 1), (64, 64), 4),    # small map, filter-heavy: slice/column groups
+    ((128, 4, 4, 96, 256, 3, 3, 1, 1), (64, 64), 2),     # 3 chunks per tap, 2 slices: slices by stages
+    ((128, 6, 4, 256, 256, 3, 3, 1, 1), (64, 64), 2),    # 6x4 map: regions of 3x2 positions
+    ((64, 8, 8, 64, 256, 3, 3, 1, 1), (64, 64), 1),      # one row tile per position: no image groups
+    ((128, 5, 4, 64, 256, 3, 3, 1, 1), (64, 64), 2),     # odd height: halves along x only
+    ((128, 5, 3, 64, 256, 3, 3, 1, 1), (64, 64), 3),     # odd both ways: no spatial split
+    ((128, 8, 8, 64, 256, 3, 3, 2, 1), (64, 64), 2),     # stride 2: tap counts do not mirror (forward only)
+    ((256, 16, 16, 32, 128, 3, 3, 1, 1), (64, 64), 1),   # 2048 workgroups: not resident at once
+    ((128, 6, 6, 32, 256, 5, 5, 1, 2), (64, 64), 1),     # 36 workgroups per XCD: partial last lap
+    ((256, 8, 8, 64, 128, 3, 3, 1, 1), (128, 64), 2),    # 128-row tiles
+    ((128, 8, 8, 64, 64, 3, 3, 1, 1), (128, 32), 2),
+]
+
+
+@pytest.mark.parametrize("case", REGION_CASES, ids=lambda c: "x".join(map(str, c[0][:5])) + "-%dx%d-s%d" % (c[1] + (c[2],)))
+def test_region_wise_order(case):
+    """The region-wise workgroup order is a permutation of the tiles: results are bitwise those of the
+    older order and within tolerance of the oracle."""
+    shp, tile, split = case
+    say("region-wise order %s tile %s split %d" % (shp, tile, split))
+    d = mc.make_desc(*shp)
+    X, W, G = small_inputs(d, hash(shp) & 0xffff)
+    mc.conv2d_set_tuning(mc.VARIANT_MFMA, split)
+    mc.conv2d_set_tile(tile[0], tile[1], 1)
+    taken = 0
+    for op, name in ((mc.OP_FWD, "fwd"), (mc.OP_BWD_DATA, "bwd_data")):
+        a, b = gu.operands(name, X, W, G)
+        mc.conv2d_set_order(1)
+        pl = mc.conv2d_query_plan(op, d)
+        assert pl.pos_major == 1 and pl.kernel == mc.KERNEL_GATHER
+        ranks = {mc.conv2d_query_workgroup(op, d, wg)[0] for wg in range(pl.grid)}
+        assert ranks == set(range(pl.grid))
+        taken += pl.order == mc.ORDER_REGIONS
+        got = gu.run_gpu(name, d, a, b)
+        mc.conv2d_set_order(0)
+        assert mc.conv2d_query_plan(op, d).order != mc.ORDER_REGIONS
+        old = gu.run_gpu(name, d, a, b)
+        assert np.array_equal(got, old), "%s %s: the two orders differ" % (shp, name)
+        rel, mx = gu.errors(got, gu.run_oracle(name, d, a, b))
+        assert rel <= gu.REL_L2_TOL and mx <= gu.MAX_ABS_TOL, (shp, name, rel, mx)
+    assert taken >= 1, "no operator of %s took the region-wise order" % (shp,)
+
 
 
 def _seeded_shapes(count, seed):
