@@ -92,7 +92,7 @@ typedef struct conv2d_plan_info {
 enum {
     MI355CONV_ORDER_PLAIN = 0,     /* tiles in id order (ids regrouped so that neighbours share an XCD) */
     MI355CONV_ORDER_LONGEST = 1,   /* unequal tiles dealt longest first to the 256 CUs                 */
-    MI355CONV_ORDER_REGIONS = 2    /* every XCD owns a region x image group x filter-slice group       */
+    MI355CONV_ORDER_REGIONS = 2    /* every XCD owns a part of the tiles that shares operands          */
 };
 
 /* Kernel families (conv2d_plan_info.kernel); for tests, which force every compiled variant. */
@@ -137,11 +137,13 @@ int conv2d_set_tuning(int variant, int split);
 int conv2d_set_tile(int tile_m, int tile_n, int pos_major);
 
 /* Third process-wide override for tests and sweeps: the order in which the workgroups of a
- * (y,x,n)-row forward / unit-stride backward-data launch are dealt to the chip.
- * region_wise = 1 (default): every XCD (workgroup id modulo 8, one L2 each) owns a spatial
- * region x image group x filter-slice group of the tiles wherever the shape allows it;
- * 0: the older order (longest tiles first over the whole chip).  Results are bitwise equal
- * either way. */
+ * launch with (y,x,n) rows (forward, unit-stride backward-data, backward-weight on small maps)
+ * are dealt to the chip.  region_wise = 1 (default): every XCD (workgroup id modulo 8, one L2
+ * each) owns a part of the tiles that shares operands - a spatial region x image group x
+ * filter-slice group for the gather operators, a group of output-channel tiles x
+ * input-channel tiles x slices for backward-weight - wherever the shape allows it; 0: the
+ * older order (longest tiles first over the whole chip).  Results are bitwise equal either
+ * way. */
 int conv2d_set_order(int region_wise);
 
 /* Forward convolution (Sec. III Layer-1; Fig. 2 conv3D arguments):

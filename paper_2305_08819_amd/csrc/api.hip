@@ -68,6 +68,8 @@ struct Plan {
     // region-wise order of the gather operators (see GatherGemmParams::regional); uses order / unitWork
     int regional = 0, regSnake = 0, regPerPos = 0, regCsPer = 0, regRowTiles = 0, regW = 0;
     unsigned char regLut[8] = {};
+    // group-wise order of the (oh,ow,n) backward-weight launches (see WgradParams::regional)
+    int regShiftA = 0, regShiftB = 0, regOcTiles = 0, regIcTiles = 0, regSlices = 0;
     int chunksPerSlice = 0;   // gather operators: slices by source channels (0: by stages)
 };
 
@@ -695,15 +697,19 @@ void fill_gather_params(GatherGemmParams &g, const Plan &pl)
 // still has a free id, CUs with equal contents are made neighbours, and the permutation comes
 // out as a few runs.  Returns false (identity order, still longest first) when the grid is
 // not resident at once or the runs do not fit.
-bool build_balance_runs(const int *unitWork, int nUnits, int perUnit, int grid, int resident, BalanceRuns *out)
+bool build_balance_runs(const int *unitWork, int nUnits, int perUnit, int grid, int resident, BalanceRuns *out,
+                        bool oneXcd = false)
 {
+    // oneXcd: the same dealing for the workgroups of a single XCD (32 CUs; slots are the ids' places on
+    // that XCD, so the columns of a partial last lap are simply its first ones)
     out->n = 0;
-    constexpr int cus = 256;
+    constexpr int kCus = 256;
+    const int cus = oneXcd ? 32 : kCus;
     if (grid <= cus || grid > cus * resident || resident > 8 || nUnits > 256) return false;
     const int laps = grid / cus, extra = grid % cus;
     struct Deal {
-        int load[cus], cnt[cus];
-        short cls[cus][8];
+        int load[kCus], cnt[kCus];
+        short cls[kCus][8];
         int worst;
     };
     auto fresh = [&](Deal &d) {
@@ -721,9 +727,9 @@ bool build_balance_runs(const int *unitWork, int nUnits, int perUnit, int grid, 
     // Columns are slots (balance_slot): column j of the last, partial lap exists iff some id
     // 256 * laps + c with c < extra has j as its slot in the whole laps - ids of the partial lap
     // keep their value, so those are the columns c' with slot-inverse below `extra`.
-    bool roomy[cus];
+    bool roomy[kCus];
     for (int j = 0; j < cus; ++j) roomy[j] = false;
-    for (int c = 0; c < extra; ++c) roomy[(c & 7) * 32 + (c >> 3)] = true;
+    for (int c = 0; c < extra; ++c) roomy[oneXcd ? c : (c & 7) * 32 + (c >> 3)] = true;
     // Two dealings, the better one is kept.  The roomy columns hold one item more than the
     // others: (a) give them the lightest items up front, then deal the rest to the other
     // columns; (b) deal everything to all columns, the roomy ones last among equals.
@@ -768,7 +774,7 @@ bool build_balance_runs(const int *unitWork, int nUnits, int perUnit, int grid, 
     short (*cls)[8] = d.cls;
     // neighbours with equal contents: within each capacity group the columns' contents are
     // reassigned in sorted order (column j takes the contents of abstract column col[j])
-    int col[cus], idxRoomy[cus], idxPlain[cus], nr = 0, np_ = 0;
+    int col[kCus], idxRoomy[kCus], idxPlain[kCus], nr = 0, np_ = 0;
     for (int c = 0; c < cus; ++c) (roomy[c] ? idxRoomy[nr++] : idxPlain[np_++]) = c;
     auto less = [&](int x, int y) {   // by the lengths of the contents, longest first
         for (int l = 0; l < 8; ++l) {
@@ -778,7 +784,7 @@ bool build_balance_runs(const int *unitWork, int nUnits, int perUnit, int grid, 
         return false;
     };
     {
-        int tmp[cus];
+        int tmp[kCus];
         for (int i = 0; i < nr; ++i) tmp[i] = idxRoomy[i];
         std::stable_sort(tmp, tmp + nr, less);
         for (int i = 0; i < nr; ++i) col[idxRoomy[i]] = tmp[i];
@@ -802,7 +808,7 @@ bool build_balance_runs(const int *unitWork, int nUnits, int perUnit, int grid, 
         const int width = l < laps ? cus : extra;
         for (int c = 0; c < width; ++c) {
             // whole laps are walked by slot; in the partial lap id c sits in column slot(c)
-            const int column = l < laps ? c : (c & 7) * 32 + (c >> 3);
+            const int column = (l < laps || oneXcd) ? c : (c & 7) * 32 + (c >> 3);
             const int u = cls[col[column]][l];
             if (u < 0) return false;
             const int k = classOf[u];
@@ -1005,10 +1011,49 @@ void plan_balance_wgrad(const Shape &s, Plan &pl)
         work[i] = live[order[i]];
         pl.unitWork[i] = (unsigned char)(work[i] < 255 ? work[i] : 255);
     }
-    pl.itemsPerClassUnit = (s.IC / pl.bn) * pl.tilesM * pl.split;
     const int resident = pl.bm * pl.bn <= 64 * 64 ? 4 : pl.bm * pl.bn >= 128 * 128 ? 1 : 2;
-    build_balance_runs(work, nTaps, pl.itemsPerClassUnit, pl.grid, resident, &pl.runs);
     pl.balance = 1;
+    // Group-wise order: the 8 XCDs (workgroup id % 8, one L2 each) divide the tiles as (A groups of
+    // output-channel tiles) x (B groups of input-channel tiles) x (S groups of slices), A*B*S = 8; an
+    // XCD then reads 1/(A*S) of dY and about 1/(B*S) of X (a slice group's rows plus the rows its taps
+    // reach beyond them), so dY is fetched B times and X A times over.  Powers of two only.
+    pl.regional = 0;
+    const int icTiles = s.IC / pl.bn;
+    if (g_regionalOrder.load() && pl.grid % 8 == 0) {
+        const double gBytes = 4.0 * s.N * s.OH * s.OW * s.OC, xBytes = 4.0 * s.N * s.IH * s.IW * s.IC;
+        const int ohow = s.OH * s.OW;
+        double bestCost = 0;
+        int bA = 0, bB = 0, bS = 0;
+        for (int A = 1; A <= 8; A *= 2)
+            for (int B = 1; A * B <= 8; B *= 2) {
+                const int S = 8 / (A * B);
+                if (pl.tilesM % A != 0 || icTiles % B != 0 || pl.split % S != 0) continue;
+                // positions a slice group covers, and those its taps reach on either side
+                const double len = (double)ohow / S, reach = (s.FH / 2) * s.OW + s.FW / 2;
+                const double halo = S == 1 ? 1.0 : std::min((double)S, (len + 2 * reach) / len);
+                const double cost = gBytes * B + xBytes * A * halo;
+                if (!bA || cost < bestCost) {
+                    bestCost = cost;
+                    bA = A; bB = B; bS = S;
+                }
+            }
+        if (bA) {
+            int lgA = 0, lgB = 0;
+            while ((1 << lgA) < bA) ++lgA;
+            while ((1 << lgB) < bB) ++lgB;
+            pl.regional = 1;
+            pl.regShiftA = lgA;
+            pl.regShiftB = lgB;
+            pl.regOcTiles = pl.tilesM / bA;
+            pl.regIcTiles = icTiles / bB;
+            pl.regSlices = pl.split / bS;
+            pl.itemsPerClassUnit = pl.regOcTiles * pl.regIcTiles * pl.regSlices;
+            build_balance_runs(work, nTaps, pl.itemsPerClassUnit, pl.grid / 8, resident, &pl.runs, true);
+            return;
+        }
+    }
+    pl.itemsPerClassUnit = icTiles * pl.tilesM * pl.split;
+    build_balance_runs(work, nTaps, pl.itemsPerClassUnit, pl.grid, resident, &pl.runs);
 }
 
 // The plan against the preconditions of the launcher it names (the same predicates the launchers
@@ -1221,6 +1266,19 @@ int conv2d_query_workgroup(int op, const conv2d_desc *d, int workgroup, int *ran
     if (workgroup < 0 || workgroup >= pl.grid) return MI355CONV_ERR_BAD_DIM;
     *rank = workgroup;
     *work = 1;
+    if (pl.regional && op == MI355CONV_OP_BWD_WEIGHT) {   // group-wise: dealing inside the XCD through the run table
+        const int q = workgroup >> 3;
+        int lr = q;
+        if (pl.runs.n) {
+            int r = 0;
+            for (int i = 1; i < pl.runs.n; ++i)
+                if (q >= pl.runs.idStart[i]) r = i;
+            lr = pl.runs.rankStart[r] + (q - pl.runs.idStart[r]);
+        }
+        *rank = lr * 8 + (workgroup & 7);
+        *work = pl.unitWork[lr / pl.itemsPerClassUnit];
+        return MI355CONV_OK;
+    }
     if (pl.regional) {   // the kernels' region-wise decode: XCD = id % 8, place on the XCD = id / 8
         const int q = workgroup >> 3, local = pl.grid / 8;
         int lr = q;
@@ -1266,6 +1324,7 @@ int conv2d_set_tile(int tile_m, int tile_n, int pos_major)
     g_forcePosMajor.store(pos_major);
     return MI355CONV_OK;
 }
+
 
 
 int conv2d_set_order(int region_wise)
@@ -1475,6 +1534,14 @@ static int bwd_weight_impl(const float *X, const float *dY, float *dW, const con
         w.tilesPerTap = s.IC / pl.bn;
         w.divTilesPerTap = make_fastdiv((unsigned)w.tilesPerTap);
         w.divPerTap = make_fastdiv((unsigned)(w.tilesPerTap * pl.tilesM * pl.split));
+        if (pl.regional) {
+            w.regional = 1;
+            w.regShift = pl.regShiftA | (pl.regShiftB << 8);
+            w.regOcTiles = pl.regOcTiles;
+            w.divRegIc = make_fastdiv((unsigned)pl.regIcTiles);
+            w.divRegSplit = make_fastdiv((unsigned)pl.regSlices);
+            w.divPerTap = make_fastdiv((unsigned)pl.itemsPerClassUnit);
+        }
         w.runs.n = w.runsN = pl.runs.n;
         for (int i = 0; i < pl.runs.n; ++i) {
             w.runs.idStart[i] = pl.runs.idStart[i];

@@ -243,6 +243,15 @@ struct WgradParams {
     int runsN;            // runs.n, among the scalars fetched first
     int xcdWhole;         // workgroup ids below this are remapped (a whole number of 8 * xcdUnit)
     FastDiv divXcdUnit;
+    // Group-wise order of the (oh,ow,n) launches: XCD x = hardware id % 8 owns a group of output-channel
+    // tiles (x % A), of input-channel tiles ((x / A) % B) and of slices (x / (A*B)), A*B*S = 8, all powers
+    // of two, for every tap; regShift = log2 A | log2 B << 8.  Inside an XCD the tiles are ranked tap by
+    // tap (tapOrder) and dealt to its 32 CUs through `runs` (slots = place of the id on the XCD).
+    // divPerTap then divides by the tiles of a tap on one XCD.
+    int regional;
+    int regShift;
+    int regOcTiles;       // output-channel tiles per group
+    FastDiv divRegIc, divRegSplit;   // by input-channel tiles per group, by slices per group
     BalanceRuns runs;
     unsigned char tapOrder[256];   // kMaxBalancedTaps entries used; sized for one 4-byte load per lane
 };
@@ -262,6 +271,8 @@ struct WgradView {
     FastDiv divTilesPerTap, divPerTap;
     int grid, runsN, xcdWhole;
     FastDiv divXcdUnit;
+    int regional, regShift, regOcTiles;
+    FastDiv divRegIc, divRegSplit;
     const BalanceRuns &runs;
     const unsigned char *tapOrder;
 };
@@ -275,7 +286,8 @@ __device__ __forceinline__ WgradView wgrad_view(const WgradParams &p)
     WgradView v{p.X, p.G, p.C, p.N, p.IH, p.IW, p.IC, p.OC, p.OH, p.OW, p.FH, p.FW, p.sh, p.sw, p.ph, p.pw,
                 p.posMajor, p.split, p.sliceStride, p.tilesN, p.xcdUnit, p.M, p.flushChunks, p.xBytes, p.gBytes,
                 p.divOHOW, p.divOW, p.divN, p.divIC, p.divFW, p.divTilesN, p.divSplit, p.balance, p.tilesPerTap,
-                p.tilesM, p.divTilesPerTap, p.divPerTap, p.grid, p.runsN, p.xcdWhole, p.divXcdUnit, p.runs, p.tapOrder};
+                p.tilesM, p.divTilesPerTap, p.divPerTap, p.grid, p.runsN, p.xcdWhole, p.divXcdUnit,
+                p.regional, p.regShift, p.regOcTiles, p.divRegIc, p.divRegSplit, p.runs, p.tapOrder};
     MI355CONV_PIN(v.X); MI355CONV_PIN(v.G); MI355CONV_PIN(v.C);
     MI355CONV_PIN(v.N); MI355CONV_PIN(v.IH); MI355CONV_PIN(v.IW); MI355CONV_PIN(v.IC); MI355CONV_PIN(v.OC);
     MI355CONV_PIN(v.OH); MI355CONV_PIN(v.OW); MI355CONV_PIN(v.FH); MI355CONV_PIN(v.FW);
@@ -288,6 +300,9 @@ __device__ __forceinline__ WgradView wgrad_view(const WgradParams &p)
     MI355CONV_PIN(v.balance); MI355CONV_PIN(v.tilesPerTap); MI355CONV_PIN(v.tilesM);
     pin_fastdiv(v.divTilesPerTap); pin_fastdiv(v.divPerTap); pin_fastdiv(v.divXcdUnit);
     MI355CONV_PIN(v.grid); MI355CONV_PIN(v.runsN); MI355CONV_PIN(v.xcdWhole);
+    MI355CONV_PIN(v.regional); MI355CONV_PIN(v.regShift); MI355CONV_PIN(v.regOcTiles);
+    pin_fastdiv(v.divRegIc); pin_fastdiv(v.divRegSplit);
+    MI355CONV_PIN(v.divPerTap.d); MI355CONV_PIN(v.divRegIc.d); MI355CONV_PIN(v.divRegSplit.d);
     return v;
 }
 #endif
@@ -396,6 +411,12 @@ __device__ __forceinline__ void balance_class_decode(const BalancePrefetch &b, i
 __device__ __forceinline__ int balanced_rank(int bid, int grid, const BalancePrefetch &b)
 {
     const int slot = balance_slot(bid, grid);
+    const int r = __popcll(__ballot(slot >= b.runId)) - 1;   // idStart[0] == 0
+    return __builtin_amdgcn_readlane(b.runRank, r) + (slot - __builtin_amdgcn_readlane(b.runId, r));
+}
+// The same look-up for a dealing inside one XCD: the slot is the id's place on the XCD (id / 8).
+__device__ __forceinline__ int balanced_rank_local(int slot, const BalancePrefetch &b)
+{
     const int r = __popcll(__ballot(slot >= b.runId)) - 1;   // idStart[0] == 0
     return __builtin_amdgcn_readlane(b.runRank, r) + (slot - __builtin_amdgcn_readlane(b.runId, r));
 }

@@ -139,8 +139,8 @@ def test_longest_first_dealing_is_a_permutation_and_balances(lib):
         mc.conv2d_set_order(region_wise)
         pl = mc.conv2d_query_plan(op, d)
         assert pl.pos_major == 1 and pl.grid > 256
-        # the gather operators deal region-wise per XCD unless that is switched off; backward-weight has one order
-        want = mc.ORDER_REGIONS if region_wise and op != mc.OP_BWD_WEIGHT else mc.ORDER_LONGEST
+        # every XCD owns a group of the tiles unless that is switched off
+        want = mc.ORDER_REGIONS if region_wise else mc.ORDER_LONGEST
         assert pl.order == want, (op, region_wise, pl.order)
         seen, load = set(), [0] * 256
         for wg in range(pl.grid):

@@ -496,6 +496,39 @@ def test_region_wise_order(case):
 
 
 
+# shape, forced slices: (oh,ow,n) backward-weight launches that the group-wise order takes, with one or
+# several slice groups, grids of one to nine workgroups per CU and an odd slice count
+WGRAD_GROUP_CASES = [((128, 4, 4, 256, 512, 3, 3, 1, 1), 0), ((128, 4, 4, 256, 512, 3, 3, 1, 1), 1),
+                     ((128, 4, 4, 256, 512, 3, 3, 1, 1), 8), ((128, 8, 8, 128, 256, 3, 3, 1, 1), 0),
+                     ((128, 8, 8, 128, 256, 3, 3, 1, 1), 4), ((128, 2, 2, 256, 256, 3, 3, 1, 1), 2),
+                     ((96, 4, 4, 192, 192, 3, 3, 1, 1), 8), ((128, 4, 4, 128, 128, 3, 3, 1, 1), 0)]
+
+
+@pytest.mark.parametrize("case", WGRAD_GROUP_CASES, ids=lambda c: "x".join(map(str, c[0][:5])) + "-s%d" % c[1])
+def test_group_wise_order_bwd_weight(case):
+    """Backward-weight with every XCD owning a group of output-channel tiles, input-channel tiles and
+    slices: a permutation of the workgroups, so results are bitwise those of the older order."""
+    shp, split = case
+    say("group-wise backward-weight %s split %d" % (shp, split))
+    d = mc.make_desc(*shp)
+    X, W, G = small_inputs(d, hash(shp) & 0xffff)
+    mc.conv2d_set_tuning(mc.VARIANT_AUTO, split)
+    a, b = gu.operands("bwd_weight", X, W, G)
+    mc.conv2d_set_order(1)
+    pl = mc.conv2d_query_plan(mc.OP_BWD_WEIGHT, d)
+    assert pl.kernel == mc.KERNEL_WGRAD_FAST and pl.pos_major == 1 and pl.order == mc.ORDER_REGIONS, (pl.kernel, pl.order)
+    ranks = {mc.conv2d_query_workgroup(mc.OP_BWD_WEIGHT, d, wg)[0] for wg in range(pl.grid)}
+    assert ranks == set(range(pl.grid))
+    got = gu.run_gpu("bwd_weight", d, a, b)
+    mc.conv2d_set_order(0)
+    assert mc.conv2d_query_plan(mc.OP_BWD_WEIGHT, d).order != mc.ORDER_REGIONS
+    old = gu.run_gpu("bwd_weight", d, a, b)
+    assert np.array_equal(got, old), "%s: the two orders differ" % (shp,)
+    rel, mx = gu.errors(got, gu.run_oracle("bwd_weight", d, a, b))
+    assert rel <= gu.REL_L2_TOL and mx <= gu.MAX_ABS_TOL, (shp, rel, mx)
+
+
+
 def _seeded_shapes(count, seed):
     """A fixed list of shapes drawn once from a seeded generator: every loader, row order, tile and
     slicing rule meets sizes nobody picked by hand."""
