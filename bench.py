@@ -394,6 +394,8 @@ def main():
                     help="with --table: also time forward with bias + leaky-ReLU in the epilogue")
     ap.add_argument("--with-oracle", action="store_true",
                     help="with --table: also time the CPU oracle once per layer and operator")
+    ap.add_argument("--plain-order", action="store_true",
+                    help="older workgroup order (longest first over the whole chip) instead of the per-XCD orders")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 256 MiB device copy 5 times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -406,6 +408,9 @@ def main():
     mc.load()   # fails loudly if the HIP library is not built
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+
+    if args.plain_order:
+        mc.conv2d_set_order(0)
 
     if args.calibrate_copy:
         # known traffic: 256 MiB read + 256 MiB written per copy; used to scale FETCH_SIZE / WRITE_SIZE
