@@ -214,8 +214,8 @@ def table(mc, torch, cfg_names, with_oracle=False, with_epilogue=False):
                     cold = r.event_ms(rotate)
                 tf, tfe = layer.flops / ms / 1e9, layer.effective_flops / ms / 1e9
                 pl = r.plans[op]
-                plan = "v%d %dx%d s%d pm%d g%d" % (pl.variant, pl.tile_m, pl.tile_n, pl.split,
-                                                   pl.pos_major, pl.grid)
+                plan = "v%d %dx%d s%d pm%d o%d g%d" % (pl.variant, pl.tile_m, pl.tile_n, pl.split,
+                                                       pl.pos_major, pl.order, pl.grid)
                 gbs = op_bytes(layer, op) / ms / 1e6
                 rows.append({"layer": layer.name, "op": op, "ms": round(ms, 5), "tflops": round(tf, 2),
                              "pct_peak": round(100 * tf / PEAK_FP32_MFMA_TFLOPS, 1),
