@@ -126,6 +126,14 @@ int conv2d_query_plan(int op, const conv2d_desc *d, conv2d_plan_info *info);
  * this mapping (paper Sec. IV: the small-feature-map operators).  Host only; for tests. */
 int conv2d_query_workgroup(int op, const conv2d_desc *d, int workgroup, int *rank, int *work);
 
+/* The tile that workgroup id `workgroup` of a region-wise / group-wise launch
+ * (conv2d_plan_info.order == MI355CONV_ORDER_REGIONS) works on: its row tile (forward /
+ * backward-data: tile_m rows of the GEMM in (y,x,n) order; backward-weight: tile_m output
+ * channels), column tile and reduction slice - computed by the functions the kernels use.
+ * MI355CONV_ERR_UNSUPPORTED for the other orders.  Host only; for tests, which check that the
+ * ids of a launch map one-to-one onto its tiles. */
+int conv2d_query_tile(int op, const conv2d_desc *d, int workgroup, int *row_tile, int *col_tile, int *slice);
+
 /* Process-wide override for tests and sweeps: variant = MI355CONV_VARIANT_AUTO or a
  * variant code, split = 0 (auto) or a forced slice count >= 1 (clamped to what the shape
  * allows).  Not thread-safe against concurrent operator calls. */

@@ -19,7 +19,7 @@ VARIANT_AUTO, VARIANT_DIRECT, VARIANT_MFMA = -1, 0, 1
 KERNEL_DIRECT, KERNEL_GATHER, KERNEL_GATHER_ELEM, KERNEL_FIRST_LAYER, KERNEL_WGRAD, KERNEL_WGRAD_FAST = range(6)
 ORDER_PLAIN, ORDER_LONGEST, ORDER_REGIONS = range(3)
 
-EXPORTS = ("conv2d_workspace_bytes", "conv2d_query_plan", "conv2d_query_workgroup", "conv2d_set_tuning", "conv2d_set_tile", "conv2d_set_order", "conv2d_fwd",
+EXPORTS = ("conv2d_workspace_bytes", "conv2d_query_plan", "conv2d_query_workgroup", "conv2d_query_tile", "conv2d_set_tuning", "conv2d_set_tile", "conv2d_set_order", "conv2d_fwd",
            "conv2d_fwd_bias_act", "conv2d_fwd_u8",
            "conv2d_bwd_data", "deconv2d", "conv2d_bwd_weight", "conv2d_status_string",
            "conv2d_last_hip_error", "conv2d_init", "conv2d_bwd_weight_noalloc", "conv2d_noalloc_scratch_bytes",
@@ -144,6 +144,15 @@ def conv2d_query_workgroup(op: int, desc: ConvDesc, workgroup: int):
     if rc != 0:
         raise Mi355ConvError(rc, "conv2d_query_workgroup")
     return rank.value, work.value
+
+
+def conv2d_query_tile(op: int, desc: ConvDesc, workgroup: int):
+    """(row tile, column tile, slice) of hardware workgroup id `workgroup` of a region-/group-wise launch."""
+    a, b, c = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0)
+    rc = load().conv2d_query_tile(op, ctypes.byref(desc), workgroup, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+    if rc != 0:
+        raise Mi355ConvError(rc, "conv2d_query_tile")
+    return a.value, b.value, c.value
 
 
 def conv2d_set_tuning(variant: int = VARIANT_AUTO, split: int = 0) -> None:

@@ -1144,14 +1144,11 @@ struct Epilogue {
     float slope = 1.f;
 };
 
-int run_gather(const float *A, const float *B, float *out, const Shape &s, const Plan &pl, bool bwd,
-               void *ws, hipStream_t st, const Epilogue &epi = Epilogue())
+// Everything in the kernel arguments of a gather-operator launch that follows from the shape and the
+// plan (no pointers, no epilogue): also what conv2d_query_tile decodes workgroup ids with.
+void fill_gather_geometry(GatherGemmParams &g, const Shape &s, const Plan &pl, bool bwd)
 {
-    GatherGemmParams g;
     memset(&g, 0, sizeof g);
-    g.A = A;
-    g.B = B;
-    g.C = pl.split > 1 ? static_cast<float *>(ws) : out;
     g.Nimg = s.N;
     if (bwd) {
         g.SH = s.OH; g.SW = s.OW; g.SC = s.OC;
@@ -1169,9 +1166,6 @@ int run_gather(const float *A, const float *B, float *out, const Shape &s, const
     g.aBytes = (unsigned)((long long)g.Nimg * g.SH * g.SW * g.SC * 4);
     g.bBytes = (unsigned)((long long)s.OC * s.FH * s.FW * s.IC * 4);
     fill_gather_params(g, pl);
-    g.epilogue = epi.on ? 1 : 0;
-    g.bias = epi.bias;
-    g.slope = epi.slope;
     g.balance = pl.balance;
     g.rowTilesPerPos = 1;
     if (pl.balance) {
@@ -1207,6 +1201,70 @@ int run_gather(const float *A, const float *B, float *out, const Shape &s, const
         memcpy(g.posOrder, pl.order, sizeof g.posOrder);
     }
     g.divRowTilesPerPos = make_fastdiv((unsigned)g.rowTilesPerPos);
+}
+
+// The shape- and plan-dependent part of the backward-weight kernel arguments (no pointers).
+void fill_wgrad_geometry(WgradParams &w, const Shape &s, const Plan &pl)
+{
+    memset(&w, 0, sizeof w);
+    w.N = s.N; w.IH = s.IH; w.IW = s.IW; w.IC = s.IC; w.OC = s.OC; w.OH = s.OH; w.OW = s.OW;
+    w.FH = s.FH; w.FW = s.FW; w.sh = s.sh; w.sw = s.sw; w.ph = s.ph; w.pw = s.pw;
+    w.posMajor = pl.posMajor;
+    w.split = pl.split;
+    w.sliceStride = pl.sliceStride;
+    w.tilesN = pl.tilesN;
+    w.xcdUnit = pl.tilesN;   // the column tiles of one slice read the same G and X rows
+    w.M = s.N * s.OH * s.OW;
+    w.flushChunks = pl.flushChunks;
+    w.xBytes = (unsigned)((long long)s.N * s.IH * s.IW * s.IC * 4);
+    w.gBytes = (unsigned)((long long)w.M * s.OC * 4);
+    w.divOHOW = make_fastdiv((unsigned)(s.OH * s.OW));
+    w.divOW = make_fastdiv((unsigned)s.OW);
+    w.divN = make_fastdiv((unsigned)s.N);
+    w.divIC = make_fastdiv((unsigned)s.IC);
+    w.divFW = make_fastdiv((unsigned)s.FW);
+    w.divTilesN = make_fastdiv((unsigned)pl.tilesN);
+    w.divSplit = make_fastdiv((unsigned)pl.split);
+    w.balance = pl.balance;
+    w.tilesM = pl.tilesM;
+    w.grid = pl.grid;
+    w.divXcdUnit = make_fastdiv((unsigned)w.xcdUnit);
+    w.xcdWhole = (pl.grid / (8 * w.xcdUnit)) * (8 * w.xcdUnit);
+    w.divTilesPerTap = w.divPerTap = make_fastdiv(1u);
+    for (int i = 0; i < kMaxBalanceRuns; ++i) w.runs.idStart[i] = 0x7fffffff;   // unused run entries never match
+    if (pl.balance) {
+        w.tilesPerTap = s.IC / pl.bn;
+        w.divTilesPerTap = make_fastdiv((unsigned)w.tilesPerTap);
+        w.divPerTap = make_fastdiv((unsigned)(w.tilesPerTap * pl.tilesM * pl.split));
+        if (pl.regional) {
+            w.regional = 1;
+            w.regShift = pl.regShiftA | (pl.regShiftB << 8);
+            w.regOcTiles = pl.regOcTiles;
+            w.divRegIc = make_fastdiv((unsigned)pl.regIcTiles);
+            w.divRegSplit = make_fastdiv((unsigned)pl.regSlices);
+            w.divPerTap = make_fastdiv((unsigned)pl.itemsPerClassUnit);
+        }
+        w.runs.n = w.runsN = pl.runs.n;
+        for (int i = 0; i < pl.runs.n; ++i) {
+            w.runs.idStart[i] = pl.runs.idStart[i];
+            w.runs.rankStart[i] = pl.runs.rankStart[i];
+        }
+        static_assert(sizeof pl.order >= kMaxBalancedTaps && sizeof w.tapOrder >= kMaxBalancedTaps, "tap order fits");
+        memcpy(w.tapOrder, pl.order, kMaxBalancedTaps);
+    }
+}
+
+int run_gather(const float *A, const float *B, float *out, const Shape &s, const Plan &pl, bool bwd,
+               void *ws, hipStream_t st, const Epilogue &epi = Epilogue())
+{
+    GatherGemmParams g;
+    fill_gather_geometry(g, s, pl, bwd);
+    g.A = A;
+    g.B = B;
+    g.C = pl.split > 1 ? static_cast<float *>(ws) : out;
+    g.epilogue = epi.on ? 1 : 0;
+    g.bias = epi.bias;
+    g.slope = epi.slope;
     hipError_t e = pl.elem ? launch_gather_elem(g, bwd, pl.bm, pl.bn, pl.grid, st)
                            : launch_gather_gemm(g, bwd, pl.bm, pl.bn, pl.grid, st);
     if (e != hipSuccess) return hip_fail(e);
@@ -1301,6 +1359,42 @@ int conv2d_query_workgroup(int op, const conv2d_desc *d, int workgroup, int *ran
         *rank = pl.runs.rankStart[r] + (slot - pl.runs.idStart[r]);
     }
     *work = pl.unitWork[*rank / pl.itemsPerClassUnit];
+    return MI355CONV_OK;
+}
+
+int conv2d_query_tile(int op, const conv2d_desc *d, int workgroup, int *row_tile, int *col_tile, int *slice)
+{
+    if (!row_tile || !col_tile || !slice) return MI355CONV_ERR_NULL_PTR;
+    Shape s;
+    Plan pl;
+    int rc = check_desc(d, &s);
+    if (rc != MI355CONV_OK) return rc;
+    rc = make_plan(op, s, &pl);
+    if (rc != MI355CONV_OK) return rc;
+    if (workgroup < 0 || workgroup >= pl.grid) return MI355CONV_ERR_BAD_DIM;
+    if (!pl.regional) return MI355CONV_ERR_UNSUPPORTED;
+    // the kernels' own decode functions, fed with the same argument block the launch would get
+    if (op == MI355CONV_OP_BWD_WEIGHT) {
+        static thread_local WgradParams w;
+        fill_wgrad_geometry(w, s, pl);
+        const int q = workgroup >> 3;
+        int lr = q;
+        if (w.runsN) {
+            int r = 0;
+            for (int i = 1; i < kMaxBalanceRuns; ++i)
+                if (q >= w.runs.idStart[i]) r = i;
+            lr = w.runs.rankStart[r] + (q - w.runs.idStart[r]);
+        }
+        int tapRank, icTile;
+        group_wise_tile(w, workgroup & 7, lr, &tapRank, &icTile, row_tile, slice);
+        *col_tile = w.tapOrder[tapRank] * w.tilesPerTap + icTile;
+        return MI355CONV_OK;
+    }
+    static thread_local GatherGemmParams g;
+    fill_gather_geometry(g, s, pl, op == MI355CONV_OP_BWD_DATA);
+    int xcd, posRank, inner;
+    region_wise_place(g, workgroup, &xcd, &posRank, &inner);
+    region_wise_tile(g, xcd, g.posOrder[posRank], inner, row_tile, col_tile, slice);
     return MI355CONV_OK;
 }
 
@@ -1501,55 +1595,10 @@ static int bwd_weight_impl(const float *X, const float *dY, float *dW, const con
         return MI355CONV_OK;
     }
     WgradParams w;
-    memset(&w, 0, sizeof w);
+    fill_wgrad_geometry(w, s, pl);
     w.X = X;
     w.G = dY;
     w.C = pl.split > 1 ? static_cast<float *>(ws) : dW;
-    w.N = s.N; w.IH = s.IH; w.IW = s.IW; w.IC = s.IC; w.OC = s.OC; w.OH = s.OH; w.OW = s.OW;
-    w.FH = s.FH; w.FW = s.FW; w.sh = s.sh; w.sw = s.sw; w.ph = s.ph; w.pw = s.pw;
-    w.posMajor = pl.posMajor;
-    w.split = pl.split;
-    w.sliceStride = pl.sliceStride;
-    w.tilesN = pl.tilesN;
-    w.xcdUnit = pl.tilesN;   // the column tiles of one slice read the same G and X rows
-    w.M = s.N * s.OH * s.OW;
-    w.flushChunks = pl.flushChunks;
-    w.xBytes = (unsigned)((long long)s.N * s.IH * s.IW * s.IC * 4);
-    w.gBytes = (unsigned)((long long)w.M * s.OC * 4);
-    w.divOHOW = make_fastdiv((unsigned)(s.OH * s.OW));
-    w.divOW = make_fastdiv((unsigned)s.OW);
-    w.divN = make_fastdiv((unsigned)s.N);
-    w.divIC = make_fastdiv((unsigned)s.IC);
-    w.divFW = make_fastdiv((unsigned)s.FW);
-    w.divTilesN = make_fastdiv((unsigned)pl.tilesN);
-    w.divSplit = make_fastdiv((unsigned)pl.split);
-    w.balance = pl.balance;
-    w.tilesM = pl.tilesM;
-    w.grid = pl.grid;
-    w.divXcdUnit = make_fastdiv((unsigned)w.xcdUnit);
-    w.xcdWhole = (pl.grid / (8 * w.xcdUnit)) * (8 * w.xcdUnit);
-    w.divTilesPerTap = w.divPerTap = make_fastdiv(1u);
-    for (int i = 0; i < kMaxBalanceRuns; ++i) w.runs.idStart[i] = 0x7fffffff;   // unused run entries never match
-    if (pl.balance) {
-        w.tilesPerTap = s.IC / pl.bn;
-        w.divTilesPerTap = make_fastdiv((unsigned)w.tilesPerTap);
-        w.divPerTap = make_fastdiv((unsigned)(w.tilesPerTap * pl.tilesM * pl.split));
-        if (pl.regional) {
-            w.regional = 1;
-            w.regShift = pl.regShiftA | (pl.regShiftB << 8);
-            w.regOcTiles = pl.regOcTiles;
-            w.divRegIc = make_fastdiv((unsigned)pl.regIcTiles);
-            w.divRegSplit = make_fastdiv((unsigned)pl.regSlices);
-            w.divPerTap = make_fastdiv((unsigned)pl.itemsPerClassUnit);
-        }
-        w.runs.n = w.runsN = pl.runs.n;
-        for (int i = 0; i < pl.runs.n; ++i) {
-            w.runs.idStart[i] = pl.runs.idStart[i];
-            w.runs.rankStart[i] = pl.runs.rankStart[i];
-        }
-        static_assert(sizeof pl.order >= kMaxBalancedTaps && sizeof w.tapOrder >= kMaxBalancedTaps, "tap order fits");
-        memcpy(w.tapOrder, pl.order, kMaxBalancedTaps);
-    }
     hipError_t e = pl.fast ? launch_wgrad_fast(w, pl.bm, pl.bn, pl.grid, st)
                            : launch_wgrad(w, pl.bm, pl.bn, pl.elem != 0, pl.grid, st);
     if (e != hipSuccess) return hip_fail(e);

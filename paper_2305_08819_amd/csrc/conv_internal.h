@@ -55,13 +55,15 @@ inline FastDiv make_fastdiv(unsigned d)
     f.d = d;
     return f;
 }
-#if defined(__HIPCC__)
-__device__ __forceinline__ unsigned fast_div(unsigned n, const FastDiv &f)
+__host__ __device__ inline unsigned fast_div(unsigned n, const FastDiv &f)
 {
+#if defined(__HIP_DEVICE_COMPILE__)
     const unsigned t = __umulhi(f.mul, n);
+#else
+    const unsigned t = (unsigned)(((unsigned long long)f.mul * n) >> 32);
+#endif
     return (t + ((n - t) >> f.sh1)) >> f.sh2;
 }
-#endif
 
 struct BalanceClasses {
     int n;                                  // 0: ranks enumerate unit by unit (no class-wise order)
@@ -345,6 +347,62 @@ __host__ __device__ __forceinline__ int balance_slot(int bid, int grid)
     if ((lap + 1) * 256 > grid) return bid;
     const int c = bid & 255;
     return (lap << 8) + (c & 7) * 32 + (c >> 3);
+}
+
+// ---- region-wise / group-wise orders: the arithmetic between workgroup id and tile ------------------
+// Shared by the kernels and by the host (conv2d_query_tile, which the CPU tests sweep over shapes to
+// check that every plan maps the workgroup ids one-to-one onto the tiles).  P is GatherGemmParams /
+// GatherView resp. WgradParams / WgradView.
+
+// Gather operators, first half: hardware id -> XCD, rank of the tile's position on that XCD (index
+// into posOrder) and place among that position's tiles.
+template <class P>
+__host__ __device__ inline void region_wise_place(const P &p, int bid, int *xcd, int *posRank, int *inner)
+{
+    const int q = bid >> 3;
+    int lr = q;
+    if (p.regSnake) {   // ids 32 apart share a CU: every other lap of 32 is dealt backwards
+        const int lap = q >> 5;
+        int c = q & 31;
+        const int left = p.regLocal - (lap << 5);
+        const int w = left < 32 ? left : 32;
+        if (lap & 1) c = w - 1 - c;
+        lr = (lap << 5) + c;
+    }
+    *xcd = bid & 7;
+    *posRank = (int)fast_div((unsigned)lr, p.divRegPerPos);
+    *inner = lr - *posRank * p.regPerPos;
+}
+// Second half: lpos = posOrder[posRank], a position of the first region -> row tile, column tile, slice.
+template <class P>
+__host__ __device__ inline void region_wise_tile(const P &p, int xcd, int lpos, int inner, int *tmGlobal, int *tn, int *slice)
+{
+    const int ly = (int)fast_div((unsigned)lpos, p.divRegW);
+    const int lx = lpos - ly * p.regW;
+    const unsigned lut = ((xcd < 4 ? p.regLutLo : p.regLutHi) >> ((xcd & 3) * 8)) & 255u;
+    const int y = (lut & 128u) ? p.DH - 1 - ly : ly;
+    const int x = (lut & 64u) ? p.DW - 1 - lx : lx;
+    const int rt = (int)fast_div((unsigned)inner, p.divRegCsPer);
+    const int cs = (int)(lut & 7u) * p.regCsPer + (inner - rt * p.regCsPer);
+    *slice = (int)fast_div((unsigned)cs, p.divTilesN);
+    *tn = cs - *slice * p.tilesN;
+    *tmGlobal = (y * p.DW + x) * p.rowTilesPerPos + (int)((lut >> 3) & 7u) * p.regRowTiles + rt;
+}
+// Backward-weight: XCD and rank on that XCD (after the dealing) -> rank of the tap (index into
+// tapOrder), input-channel tile inside the tap, output-channel tile, slice.
+template <class P>
+__host__ __device__ inline void group_wise_tile(const P &p, int xcd, int lr, int *tapRank, int *icTile, int *tmo, int *slice)
+{
+    const int perTap = (int)p.divPerTap.d, icTiles = (int)p.divRegIc.d, slices = (int)p.divRegSplit.d;
+    *tapRank = (int)fast_div((unsigned)lr, p.divPerTap);
+    const int inner = lr - *tapRank * perTap;
+    const int r2 = (int)fast_div((unsigned)inner, p.divRegIc);
+    const int lgA = p.regShift & 255, lgB = p.regShift >> 8;
+    const int ga = xcd & ((1 << lgA) - 1), gb = (xcd >> lgA) & ((1 << lgB) - 1), gs = xcd >> (lgA + lgB);
+    *icTile = gb * icTiles + (inner - r2 * icTiles);
+    const int ocl = (int)fast_div((unsigned)r2, p.divRegSplit);
+    *tmo = ga * p.regOcTiles + ocl;
+    *slice = gs * slices + (r2 - ocl * slices);
 }
 
 #if defined(__HIPCC__)   // device-side decode of the workgroup id

@@ -56,29 +56,9 @@ __device__ __forceinline__ GatherTile gather_tile_setup(const P &p, const Balanc
     if (p.regional) {
         // region-wise order: the XCD (hardware id % 8) fixes the spatial region, the image group and the
         // group of (slice, column tile) pairs; the id's place on the XCD is the tile's rank there
-        const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
-        int lr = q;
-        if (p.regSnake) {   // ids 32 apart share a CU: every other lap of 32 is dealt backwards
-            const int lap = q >> 5;
-            int c = q & 31;
-            const int left = p.regLocal - (lap << 5);
-            const int w = left < 32 ? left : 32;
-            if (lap & 1) c = w - 1 - c;
-            lr = (lap << 5) + c;
-        }
-        const int posRank = (int)fast_div((unsigned)lr, p.divRegPerPos);
-        const int inner = lr - posRank * p.regPerPos;
-        const int lpos = balance_order(pre, posRank);
-        const int ly = (int)fast_div((unsigned)lpos, p.divRegW);
-        const int lx = lpos - ly * p.regW;
-        const unsigned lut = ((xcd < 4 ? p.regLutLo : p.regLutHi) >> ((xcd & 3) * 8)) & 255u;
-        const int y = (lut & 128u) ? p.DH - 1 - ly : ly;
-        const int x = (lut & 64u) ? p.DW - 1 - lx : lx;
-        const int rt = (int)fast_div((unsigned)inner, p.divRegCsPer);
-        const int cs = (int)(lut & 7u) * p.regCsPer + (inner - rt * p.regCsPer);
-        slice = (int)fast_div((unsigned)cs, p.divTilesN);
-        tn = cs - slice * p.tilesN;
-        tmGlobal = (y * p.DW + x) * p.rowTilesPerPos + (int)((lut >> 3) & 7u) * p.regRowTiles + rt;
+        int xcd, posRank, inner;
+        region_wise_place(p, (int)blockIdx.x, &xcd, &posRank, &inner);
+        region_wise_tile(p, xcd, balance_order(pre, posRank), inner, &tmGlobal, &tn, &slice);
     } else {
     int bid = p.balance && p.runsN ? balanced_rank(blockIdx.x, p.grid, pre)
                                     : xcd_remap_fast(blockIdx.x, p.xcdWhole, p.xcdUnit, p.divXcdUnit);

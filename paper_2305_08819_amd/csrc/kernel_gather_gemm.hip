@@ -148,10 +148,17 @@ __global__ __launch_bounds__(kThreads, 2) void gather_gemm_kernel(const GatherGe
             tapOffB = t * p.SC;
         }
         const int tapBytesA = (dy * p.SW + dx) * p.SC * 4;
+        if (p.posMajor) {
+            // (y,x,n) rows: the tile sits on one pixel position (the batch is a multiple of the row tile),
+            // so its tap rectangle holds exactly the taps inside the image - no row needs a test
 #pragma unroll
-        for (int i = 0; i < T::PA; ++i) {
-            const bool ok = (unsigned)(rY[i] + dy) < (unsigned)p.SH && (unsigned)(rX[i] + dx) < (unsigned)p.SW;
-            aOff[i] = ok ? rBase[i] + tapBytesA : kOutOfRange;
+            for (int i = 0; i < T::PA; ++i) aOff[i] = rBase[i] + tapBytesA;
+        } else {
+#pragma unroll
+            for (int i = 0; i < T::PA; ++i) {
+                const bool ok = (unsigned)(rY[i] + dy) < (unsigned)p.SH && (unsigned)(rX[i] + dx) < (unsigned)p.SW;
+                aOff[i] = ok ? rBase[i] + tapBytesA : kOutOfRange;
+            }
         }
     };
 

@@ -64,16 +64,9 @@ __global__ __launch_bounds__(kThreads, (BM * BN >= 128 * 128) ? 1 : (BM * BN <= 
         // slices; the id's place on the XCD gives the tile's rank there (tap by tap, longest taps first)
         const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
         const int lr = p.runsN ? balanced_rank_local(q, pre) : q;
-        const int perTap = (int)p.divPerTap.d, icTiles = (int)p.divRegIc.d, slices = (int)p.divRegSplit.d;
-        const int tapRank = (int)fast_div((unsigned)lr, p.divPerTap);
-        const int inner = lr - tapRank * perTap;
-        const int r2 = (int)fast_div((unsigned)inner, p.divRegIc);
-        const int lgA = p.regShift & 255, lgB = p.regShift >> 8;
-        const int ga = xcd & ((1 << lgA) - 1), gb = (xcd >> lgA) & ((1 << lgB) - 1), gs = xcd >> (lgA + lgB);
-        tn = balance_order(pre, tapRank) * p.tilesPerTap + gb * icTiles + (inner - r2 * icTiles);
-        const int ocl = (int)fast_div((unsigned)r2, p.divRegSplit);
-        tmo = ga * p.regOcTiles + ocl;
-        slice = gs * slices + (r2 - ocl * slices);
+        int tapRank, icTile;
+        group_wise_tile(p, xcd, lr, &tapRank, &icTile, &tmo, &slice);
+        tn = balance_order(pre, tapRank) * p.tilesPerTap + icTile;
     } else if (PM && p.balance) {   // tiles enumerated tap by tap, taps with the most live positions first
         const int rank = p.runsN ? balanced_rank(blockIdx.x, p.grid, pre) : (int)blockIdx.x;
         const int tapRank = (int)fast_div((unsigned)rank, p.divPerTap);

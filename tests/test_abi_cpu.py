@@ -269,3 +269,53 @@ def test_matmul_argument_errors_and_plans_before_any_hip_call(lib):
     assert mc.matmul_workspace_bytes(7, 4, 4, 4) == 0
     # the weight gradient of a 512 -> 10 classifier head over a batch of 128 is a sliced reduction or a single tile
     assert mc.matmul_workspace_bytes(mc.MATMUL_TN, 10, 512, 128) % 16 == 0
+
+
+def test_region_and_group_wise_orders_map_ids_onto_tiles_one_to_one(lib):
+    """Sweep of shapes, tiles and slice counts through the planner: wherever a plan names the region-wise
+    (forward, backward-data) or group-wise (backward-weight) order, the kernels' own decode functions
+    (conv2d_query_tile runs them on the host) must send the workgroup ids of the launch to every
+    (row tile, column tile, slice) exactly once."""
+    shapes = []
+    for n in (64, 128, 256):
+        for hw in ((2, 2), (4, 4), (8, 8), (16, 16), (6, 4), (5, 4), (4, 6), (3, 5), (8, 2)):
+            for ic, oc in ((64, 64), (128, 256), (256, 128), (512, 512), (96, 160), (192, 64)):
+                shapes.append((n, hw[0], hw[1], ic, oc, 3, 3, 1, 1))
+    shapes += [(128, 8, 8, 64, 128, 5, 5, 1, 2), (128, 8, 8, 64, 256, 3, 3, 2, 1), (128, 7, 7, 64, 128, 3, 3, 1, 1),
+               (256, 32, 32, 32, 64, 3, 3, 1, 1), (128, 8, 8, 128, 128, 3, 1, 1, (1, 0)), (128, 4, 4, 256, 512, 1, 3, 1, (0, 1))]
+    checked = {mc.OP_FWD: 0, mc.OP_BWD_DATA: 0, mc.OP_BWD_WEIGHT: 0}
+    try:
+        for shp in shapes:
+            d = mc.make_desc(*shp)
+            for split in (0, 2, 3, 8):
+                for tile in ((0, 0), (128, 64)):
+                    mc.conv2d_set_tuning(mc.VARIANT_AUTO, split)
+                    mc.conv2d_set_tile(tile[0], tile[1], -1)
+                    for op in (mc.OP_FWD, mc.OP_BWD_DATA, mc.OP_BWD_WEIGHT):
+                        pl = mc.conv2d_query_plan(op, d)
+                        if pl.order != mc.ORDER_REGIONS:
+                            if pl.variant == mc.VARIANT_MFMA and pl.grid > 0:
+                                with pytest.raises(mc.Mi355ConvError):
+                                    mc.conv2d_query_tile(op, d, 0)
+                            continue
+                        if pl.grid > 4096:      # keep the sweep short
+                            continue
+                        tiles = [mc.conv2d_query_tile(op, d, wg) for wg in range(pl.grid)]
+                        assert len(set(tiles)) == pl.grid, (shp, split, tile, op)
+                        rows = {t[0] for t in tiles}
+                        cols = {t[1] for t in tiles}
+                        slices = {t[2] for t in tiles}
+                        assert slices == set(range(pl.split)), (shp, split, op, sorted(slices))
+                        assert rows == set(range(len(rows))) and cols == set(range(len(cols)))
+                        assert len(rows) * len(cols) * pl.split == pl.grid, (shp, split, op, len(rows), len(cols), pl.split, pl.grid)
+                        if op == mc.OP_BWD_WEIGHT:
+                            assert len(rows) == -(-d.OC // pl.tile_m) and len(cols) == -(-(d.FH * d.FW * d.IC) // pl.tile_n)
+                        else:
+                            dst_c = d.IC if op == mc.OP_BWD_DATA else d.OC
+                            m = d.N * (d.IH * d.IW if op == mc.OP_BWD_DATA else d.OH * d.OW)
+                            assert len(cols) == -(-dst_c // pl.tile_n) and len(rows) == -(-m // pl.tile_m)
+                        checked[op] += 1
+    finally:
+        mc.conv2d_set_tuning(mc.VARIANT_AUTO, 0)
+        mc.conv2d_set_tile(0, 0, -1)
+    assert min(checked.values()) >= 20, checked
