@@ -319,3 +319,46 @@ def test_region_and_group_wise_orders_map_ids_onto_tiles_one_to_one(lib):
         mc.conv2d_set_tuning(mc.VARIANT_AUTO, 0)
         mc.conv2d_set_tile(0, 0, -1)
     assert min(checked.values()) >= 20, checked
+
+
+def test_plan_queries_from_many_threads(lib):
+    """The planner and its plan cache are shared by all threads of a process: eight threads that query
+    plans and workspace sizes for interleaved shapes at once (ctypes drops the interpreter lock during a
+    call) get exactly what one thread gets."""
+    import threading
+    shapes = [(128, hw, hw, ic, oc, 3, 3, 1, 1) for hw in (2, 4, 8, 16) for ic in (64, 128, 256) for oc in (64, 256, 512)]
+    shapes += [(64, 7, 5, 24, 40, 3, 3, 2, 1), (128, 32, 32, 64, 128, 3, 3, 2, 1), (128, 16, 16, 256, 64, 1, 1, 1, 0)]
+
+    def answers(order):
+        out = {}
+        for i in order:
+            d = mc.make_desc(*shapes[i])
+            for op in (mc.OP_FWD, mc.OP_BWD_DATA, mc.OP_BWD_WEIGHT):
+                pl = mc.conv2d_query_plan(op, d)
+                out[(i, op)] = (pl.variant, pl.tile_m, pl.tile_n, pl.split, pl.pos_major, pl.grid, pl.workspace_bytes,
+                                pl.kernel, pl.order, mc.conv2d_workspace_bytes(op, d),
+                                mc.conv2d_query_workgroup(op, d, pl.grid - 1) if pl.grid else None)
+        return out
+
+    want = answers(range(len(shapes)))
+    got, errors = [None] * 8, []
+
+    def work(t):
+        try:
+            order = list(range(len(shapes)))
+            order = order[3 * t:] + order[:3 * t]      # every thread its own order over all shapes
+            if t % 2:
+                order.reverse()
+            for _ in range(3):
+                got[t] = answers(order)
+        except Exception as e:      # reported by the main thread
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=work, args=(t,)) for t in range(8)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors
+    for t in range(8):
+        assert got[t] == want, t
