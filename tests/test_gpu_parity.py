@@ -325,6 +325,49 @@ def test_side_stream():
         assert rel <= gu.REL_L2_TOL and mx <= gu.MAX_ABS_TOL
 
 
+def test_host_threads_launch_on_their_own_streams():
+    """Four host threads, each with its own stream, workspace and shape, enqueue all three operators
+    repeatedly at the same time (plan cache, per-device set-up and error text are shared or per thread);
+    every result must be the one a single thread gets."""
+    import threading
+    shapes = [(64, 4, 4, 128, 256, 3, 3, 1, 1), (32, 8, 8, 64, 64, 3, 3, 1, 1), (8, 16, 16, 32, 48, 3, 3, 2, 1),
+              (128, 2, 2, 256, 256, 3, 3, 1, 1)]
+    jobs = []
+    for i, shp in enumerate(shapes):
+        d = mc.make_desc(*shp)
+        X, W, G = small_inputs(d, 900 + i)
+        ref = {op: gu.run_gpu(op, d, *gu.operands(op, X, W, G)) for op in ("fwd", "bwd_data", "bwd_weight")}
+        dev = {k: torch.from_numpy(v).cuda() for k, v in (("X", X), ("W", W), ("G", G))}
+        need = max(mc.conv2d_workspace_bytes(o, d) for o in (mc.OP_FWD, mc.OP_BWD_DATA, mc.OP_BWD_WEIGHT))
+        jobs.append({"d": d, "ref": ref, "dev": dev, "st": torch.cuda.Stream(),
+                     "ws": torch.empty(max(need, 16) // 4, dtype=torch.float32, device="cuda"),
+                     "Y": torch.empty((d.N, d.OH, d.OW, d.OC), dtype=torch.float32, device="cuda"),
+                     "dX": torch.empty((d.N, d.IH, d.IW, d.IC), dtype=torch.float32, device="cuda"),
+                     "dW": torch.empty((d.OC, d.FH, d.FW, d.IC), dtype=torch.float32, device="cuda")})
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(j):
+        try:
+            for _ in range(20):
+                mc.conv2d_fwd(j["dev"]["X"], j["dev"]["W"], j["Y"], j["d"], ws=j["ws"], stream=j["st"])
+                mc.conv2d_bwd_data(j["dev"]["G"], j["dev"]["W"], j["dX"], j["d"], ws=j["ws"], stream=j["st"])
+                mc.conv2d_bwd_weight(j["dev"]["X"], j["dev"]["G"], j["dW"], j["d"], ws=j["ws"], stream=j["st"])
+        except Exception as e:      # reported by the main thread
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=work, args=(j,)) for j in jobs]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for i, j in enumerate(jobs):
+        for op, key in (("fwd", "Y"), ("bwd_data", "dX"), ("bwd_weight", "dW")):
+            assert np.array_equal(j[key].cpu().numpy(), j["ref"][op]), (shapes[i], op)
+
+
 BIAS_ACT_SHAPES = [
     (3, 9, 9, 64, 48, 3, 3, 1, 1),       # 16-byte loaders
     (2, 7, 6, 5, 7, 3, 2, (2, 1), (1, 0)),   # element-wise loaders, odd output count (scalar tail of the combine pass)
