@@ -9,6 +9,7 @@
 #include <atomic>
 #include <cstdio>
 #include <cstring>
+#include <functional>
 #include <mutex>
 #include <unordered_map>
 
@@ -142,8 +143,12 @@ constexpr double kCuFlopPerUs = 157.3e6 / 256.0;   // fp32 MFMA FLOP per microse
 constexpr size_t kMaxWorkspace = (size_t)1 << 30;
 
 // balanced: long and short workgroups are dealt evenly to the CUs (see GatherGemmParams::balance)
+// exactBusiestStages >= 0 (ranking of slice counts only, see best_split): the stages of the busiest CU as
+// the host's own dealing leaves them, in place of the estimate from average and longest workgroup, plus
+// wgUs per workgroup on that CU for the part of a workgroup's prologue and epilogue that nothing hides.
 double launch_cost(const CostParams &k, const TileCand &c, long long tiles, double avgStages, double maxStages,
-                   int split, long long outElems, bool balanced = false)
+                   int split, long long outElems, bool balanced = false, double exactBusiestStages = -1.0,
+                   double wgUs = 0.0)
 {
     const long long grid = tiles * split;
     const int cus = 256;
@@ -161,6 +166,7 @@ double launch_cost(const CostParams &k, const TileCand &c, long long tiles, doub
                                        ? busiest + (maxWg - avgWg) * 2.0 / (double)perCu   // what pairing cannot even out
                                        : maxWg + (double)(perCu - 1) * avgWg * k.mix;
         if (withLongest > busiest) busiest = withLongest;
+        if (exactBusiestStages >= 0) busiest = exactBusiestStages * unit + (double)perCu * wgUs * eff;
         t = busiest / eff;
     } else {
         // finished workgroups are replaced at once: work divides evenly, plus the drain
@@ -172,8 +178,12 @@ double launch_cost(const CostParams &k, const TileCand &c, long long tiles, doub
 }
 
 // Best slice count for one candidate; returns the cost.
+// busiestFn (optional): stages of the busiest CU for a slice count under the order the launch will use, or a
+// negative value where unknown.  Where it is known for every candidate slice count, the slice count is
+// ranked with it; the cost returned - what tiles and row orders are compared by - stays the estimate.
 double best_split(const CostParams &k, const TileCand &c, long long tiles, double avgStages, double maxStages,
-                  long long outElems, int *splitOut, int minS = 1, bool balanced = false)
+                  long long outElems, int *splitOut, int minS = 1, bool balanced = false,
+                  const std::function<double(int)> *busiestFn = nullptr)
 {
     const int forced = g_forceSplit.load();
     int maxS = (int)(avgStages / 2.0);              // keep >= 2 stages per slice on average
@@ -191,6 +201,23 @@ double best_split(const CostParams &k, const TileCand &c, long long tiles, doubl
     for (int sp = minS; sp <= maxS; ++sp) {
         const double t = launch_cost(k, c, tiles, avgStages, maxStages, sp, outElems, balanced);
         if (t < best) { best = t; bestS = sp; }
+    }
+    if (busiestFn) {   // second opinion on the slice count from the dealing itself
+        constexpr double kWgUs = 0.7;
+        double bestExact = 1e300;
+        int exactS = 0;
+        bool pickKnown = false;
+        for (int sp = minS; sp <= maxS; ++sp) {
+            const double stages = (*busiestFn)(sp);
+            if (stages < 0) continue;   // not resident at once, or another order: no opinion
+            if (sp == bestS) pickKnown = true;
+            const double t = launch_cost(k, c, tiles, avgStages, maxStages, sp, outElems, balanced, stages, kWgUs);
+            if (t < bestExact) { bestExact = t; exactS = sp; }
+        }
+        if (exactS && pickKnown) {
+            bestS = exactS;
+            best = launch_cost(k, c, tiles, avgStages, maxStages, bestS, outElems, balanced);
+        }
     }
     *splitOut = bestS;
     return best;
@@ -232,6 +259,14 @@ int resolve_order(int wanted, bool allowed)
     if (f == 1) return allowed ? 1 : 0;
     return wanted && allowed;
 }
+
+bool plan_regional_gather(const Shape &s, Plan &pl, bool bwd);
+
+// Stages of the busiest CU of a (y,x,n)-row forward / unit-stride backward-data launch with the given
+// tile and slice count under the region-wise order: the dealing is carried out as the kernels will
+// see it (XCD = id % 8, ids 32 apart on an XCD share a CU).  Negative where that order does not apply
+// or the launch is not resident at once.
+double regional_busiest_stages(const Shape &s, bool bwd, int bm, int bn, int split, int chunksPerTap);
 
 // Forward convolution has a single "phase": all output pixels, all taps.
 void set_forward_phase(Plan &pl, const Shape &s)
@@ -354,7 +389,11 @@ Plan plan_fwd(const Shape &s)
             const double maxStages = (order ? maxTapsPos : s.FH * s.FW) * chunksPerTap;
             int sp = 1;
             const bool balanced = order && s.OH * s.OW <= kMaxBalancedPositions;
-            const double t = best_split(kGatherCost, c, tiles, avgStages, maxStages, pl.outElems, &sp, 1, balanced);
+            const std::function<double(int)> busiest = [&](int split) {
+                return order ? regional_busiest_stages(s, false, c.bm, c.bn, split, chunksPerTap) : -1.0;
+            };
+            const double t = best_split(kGatherCost, c, tiles, avgStages, maxStages, pl.outElems, &sp, 1, balanced,
+                                        order ? &busiest : nullptr);
             if (t < best) {
                 best = t;
                 pl.bm = c.bm;
@@ -506,8 +545,11 @@ Plan plan_bwd_data(const Shape &s)
             const double m = order && unitStride ? (double)maxTapsPos : (double)maxTaps;
             int sp = 1;
             const bool balanced = order && unitStride && s.IH * s.IW <= kMaxBalancedPositions;
+            const std::function<double(int)> busiest = [&](int split) {
+                return regional_busiest_stages(s, true, c.bm, c.bn, split, chunksPerTap);
+            };
             const double t = best_split(kGatherCost, c, tiles, a * chunksPerTap, m * chunksPerTap, pl.outElems, &sp, 1,
-                                        balanced);
+                                        balanced, order && unitStride ? &busiest : nullptr);
             if (t < best) {
                 best = t;
                 trial.bm = c.bm;
@@ -967,6 +1009,36 @@ bool plan_regional_gather(const Shape &s, Plan &pl, bool bwd)
     pl.regSnake = pl.grid / 8 <= 32 * resident;
     pl.regional = 1;
     return true;
+}
+
+double regional_busiest_stages(const Shape &s, bool bwd, int bm, int bn, int split, int chunksPerTap)
+{
+    if (!g_regionalOrder.load() || s.N % bm != 0) return -1.0;
+    Plan t;
+    t.variant = MI355CONV_VARIANT_MFMA;
+    t.bm = bm;
+    t.bn = bn;
+    t.posMajor = 1;
+    t.nPhases = 1;
+    t.split = split;
+    const int dh = bwd ? s.IH : s.OH, dw = bwd ? s.IW : s.OW;
+    t.tilesM = ceil_div((long long)s.N * dh * dw, bm);
+    t.tilesN = ceil_div(bwd ? s.IC : s.OC, bn);
+    t.grid = t.tilesM * t.tilesN * split;
+    if (split > 1 && chunksPerTap % split == 0) t.chunksPerSlice = chunksPerTap / split;
+    if (!plan_regional_gather(s, t, bwd) || !t.regSnake) return -1.0;
+    int load[32] = {};
+    const int local = t.grid / 8;
+    for (int q = 0; q < local; ++q) {
+        const int lap = q >> 5, left = local - (lap << 5), w = left < 32 ? left : 32;
+        int c = q & 31;
+        if (lap & 1) c = w - 1 - c;
+        load[q & 31] += t.unitWork[((lap << 5) + c) / t.regPerPos];
+    }
+    int worst = 0;
+    for (int c = 0; c < 32; ++c)
+        if (load[c] > worst) worst = load[c];
+    return (double)worst * chunksPerTap / split;
 }
 
 // Slicing and workgroup order of a gather-operator plan.
