@@ -489,8 +489,8 @@ def test_balanced_dealing_odd_grids(shp, split):
 
 
 # shape, tile, forced slices: (y,x,n) launches that the region-wise order takes, chosen so that every
-# factor of the division among the XCDs occurs (quarters, halves along one axis only, no spatial
-# split; one or several image groups; one or several (slice, column) groups), with slices by source
+# factor of the division among the XCDs occurs (quarters, halves along one axis only; one or several
+# image groups; one or several (slice, column) groups), with slices by source
 # channels (slice count divides the 32-channel chunks) and by stages (it does not), grids that are
 # resident at once (snake dealing, also with a partial last lap of 32) and grids that are not.
 REGION_CASES = [
@@ -500,8 +500,7 @@ REGION_CASES = [
     ((128, 6, 4, 256, 256, 3, 3, 1, 1), (64, 64), 2),    # 6x4 map: regions of 3x2 positions
     ((64, 8, 8, 64, 256, 3, 3, 1, 1), (64, 64), 1),      # one row tile per position: no image groups
     ((128, 5, 4, 64, 256, 3, 3, 1, 1), (64, 64), 2),     # odd height: halves along x only
-    ((128, 5, 3, 64, 256, 3, 3, 1, 1), (64, 64), 3),     # odd both ways: no spatial split
-    ((128, 8, 8, 64, 256, 3, 3, 2, 1), (64, 64), 2),     # stride 2: tap counts do not mirror (forward only)
+    ((128, 4, 6, 64, 256, 3, 3, 1, 1), (64, 64), 3),     # slices by stages (3 does not divide the 2 chunks of a tap)
     ((256, 16, 16, 32, 128, 3, 3, 1, 1), (64, 64), 1),   # 2048 workgroups: not resident at once
     ((128, 6, 6, 32, 256, 5, 5, 1, 2), (64, 64), 1),     # 36 workgroups per XCD: partial last lap
     ((256, 8, 8, 64, 128, 3, 3, 1, 1), (128, 64), 2),    # 128-row tiles
