@@ -137,7 +137,7 @@ struct CostParams {
     double reduceBytesPerUs;
 };
 constexpr CostParams kGatherCost = {0.85, 0.95, 1.0, 1.0, 0.25, 4.0, 0.5, 8.0e6};
-constexpr CostParams kWgradCost = {0.80, 0.95, 1.05, 0.56, 0.20, 4.0, 10.0, 6.2e6};
+constexpr CostParams kWgradCost = {0.80, 0.95, 1.03, 0.56, 0.20, 4.0, 10.0, 6.2e6};
 
 constexpr double kCuFlopPerUs = 157.3e6 / 256.0;   // fp32 MFMA FLOP per microsecond per CU
 constexpr size_t kMaxWorkspace = (size_t)1 << 30;
